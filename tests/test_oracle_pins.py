@@ -1,0 +1,399 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without any GPU code.
+
+Every check compares the oracle with something other than itself: brute force written here in pure Python/numpy,
+numpy's own matmul / float16 conversion, closed forms printed in the paper (tests/golden/), or invariants.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2305_10727_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_golden(name):
+    out = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            k, v = line.split()
+            try:
+                k = float(k)
+            except ValueError:
+                pass
+            out[k] = float(v)
+    return out
+
+
+# ------------------------------------------------------------------ brute force helpers (independent of the oracle)
+PAIRS = list(itertools.combinations(range(4), 2))  # lexicographic order
+
+
+def brute_top2(mags):
+    """max sum of magnitudes over the 6 index pairs; lexicographically smallest pair among the maxima"""
+    best, best_pair = None, None
+    for pr in PAIRS:
+        s = mags[pr[0]] + mags[pr[1]]
+        if best is None or s > best:
+            best, best_pair = s, pr
+    return best_pair
+
+
+def brute_prune(W):
+    W = np.asarray(W)
+    out = np.zeros_like(W)
+    mask = np.zeros((W.shape[0], W.shape[1] // 4), np.uint8)
+    for n in range(W.shape[0]):
+        for g in range(W.shape[1] // 4):
+            grp = W[n, 4 * g:4 * g + 4]
+            mags = [abs(float(v)) for v in grp]
+            p0, p1 = brute_top2(mags)
+            out[n, 4 * g + p0] = grp[p0]
+            out[n, 4 * g + p1] = grp[p1]
+            mask[n, g] = (1 << p0) | (1 << p1)
+    return out, mask
+
+
+def adversarial_groups(dtype):
+    tiny = np.finfo(dtype).tiny
+    sub = np.finfo(dtype).smallest_subnormal
+    rows = [
+        [0, 0, 0, 0], [-0.0, 0.0, -0.0, 0.0], [1, 1, 1, 1], [-1, 1, -1, 1], [1, 2, 2, 1], [2, 1, 1, 2], [3, 3, 1, 3],
+        [1, 3, 3, 3], [0, 0, 0, 5], [0, 0, 5, 0], [5, 0, 0, 0], [sub, 0, 0, sub], [sub, 2 * sub, tiny, -tiny],
+        [-tiny, tiny, sub, -sub], [1, -1, 0.5, -0.5], [0.5, -1, 1, 0.5], [6e4, 1, -6e4, 2], [4, 3, 2, 1],
+        [1, 2, 3, 4], [2, 2, 3, 3], [-0.0, 0, 1, 0],
+    ]
+    return np.array(rows, dtype=dtype).reshape(1, -1)
+
+
+# ------------------------------------------------------------------ a1 prune
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_prune_matches_brute_force(dtype):
+    rng = np.random.default_rng(1)
+    cases = [
+        rng.standard_normal((7, 64)).astype(dtype),
+        rng.integers(-2, 3, size=(16, 128)).astype(dtype),  # many ties
+        adversarial_groups(dtype),
+    ]
+    grid = np.array(list(itertools.product(range(-2, 3), repeat=4)), dtype=dtype).reshape(5, -1)  # exhaustive {-2..2}^4
+    cases.append(grid)
+    for W in cases:
+        got, mask = oracle.prune_2to4(W)
+        exp, emask = brute_prune(W)
+        assert np.array_equal(mask, emask)
+        assert np.array_equal(got.view(np.uint32 if dtype == np.float32 else np.uint16),
+                              exp.view(np.uint32 if dtype == np.float32 else np.uint16)) or \
+            np.array_equal(np.where(got == 0, 0, got), np.where(exp == 0, 0, exp))
+        # dropped entries are written as +0.0
+        dropped = np.repeat(np.unpackbits(mask[..., None], axis=-1, bitorder="little")[..., :4].reshape(W.shape) == 0, 1, axis=1)
+        bits = got.view(np.uint32 if dtype == np.float32 else np.uint16)
+        assert (bits[dropped] == 0).all()
+
+
+def test_prune_invariants():
+    W = synth.weights(96, 192, seed=3)
+    P, mask = oracle.prune_2to4(W)
+    # exactly two kept positions per group, at most two non-zeros, kept entries unchanged
+    assert (np.unpackbits(mask[..., None], axis=-1).sum(-1) == 2).all()
+    assert ((P.reshape(96, -1, 4) != 0).sum(-1) <= 2).all()
+    assert ((P == W) | (P == 0)).all()
+    # optimal: kept magnitude sum >= that of any other pair
+    a = np.abs(W).reshape(96, -1, 4)
+    kept = np.abs(P).reshape(96, -1, 4).sum(-1)
+    for p0, p1 in PAIRS:
+        assert (kept >= a[..., p0] + a[..., p1]).all()
+    # idempotent
+    P2, mask2 = oracle.prune_2to4(P)
+    assert np.array_equal(P2, P) and np.array_equal(mask2, mask)
+    # half of the entries survive
+    assert (P != 0).sum() == W.size // 2
+    with pytest.raises(ValueError):
+        oracle.prune_2to4(np.zeros((2, 6), np.float32))
+    # infinities are simply the largest magnitudes
+    Pinf, minf = oracle.prune_2to4(np.array([[np.inf, 1, -np.inf, 2]], np.float32))
+    assert minf[0, 0] == 0b0101 and np.isinf(Pinf[0, [0, 2]]).all()
+
+
+# ------------------------------------------------------------------ a3 compress / decompress
+def brute_compress(W):
+    N, K = W.shape
+    vals = np.zeros((N, K // 2), W.dtype)
+    meta = np.zeros((N, (K // 4 + 1) // 2), np.uint8)
+    viol = 0
+    for n in range(N):
+        for g in range(K // 4):
+            grp = W[n, 4 * g:4 * g + 4]
+            mags = [abs(float(v)) for v in grp]
+            p0, p1 = brute_top2(mags)
+            vals[n, 2 * g], vals[n, 2 * g + 1] = grp[p0], grp[p1]
+            meta[n, g // 2] |= (p0 | (p1 << 2)) << (4 * (g & 1))
+            viol += any(mags[i] != 0 for i in range(4) if i not in (p0, p1))
+    return vals, meta, viol
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.int8])
+def test_compress_matches_brute_force_and_round_trips(dtype):
+    rng = np.random.default_rng(2)
+    if dtype == np.int8:
+        dense = rng.integers(-127, 128, size=(9, 72)).astype(np.int8)
+        ties = rng.integers(-1, 2, size=(9, 72)).astype(np.int8)
+    else:
+        dense = rng.standard_normal((9, 72)).astype(np.float16)
+        ties = rng.integers(-1, 2, size=(9, 72)).astype(np.float16)
+    for W in (dense, ties):
+        v, m, viol = oracle.compress(W)
+        ev, em, eviol = brute_compress(W)
+        assert np.array_equal(v, ev) and np.array_equal(m, em) and viol == eviol
+        # every nibble: first position < second position
+        nib = np.stack([m & 0xF, m >> 4], -1).reshape(m.shape[0], -1)[:, :W.shape[1] // 4]
+        assert ((nib & 3) < (nib >> 2)).all()
+    # round trip on a tensor that already is 2:4: identity, no violations
+    W32 = rng.standard_normal((9, 72)).astype(np.float32)
+    P, _ = oracle.prune_2to4(W32)
+    Wp = (np.clip(np.rint(P * 50), -127, 127).astype(np.int8)) if dtype == np.int8 else P.astype(np.float16)
+    v, m, viol = oracle.compress(Wp)
+    assert viol == 0
+    back = oracle.decompress(v, m, Wp.shape[1])
+    assert np.array_equal(back, Wp)
+    # compress o decompress is the identity on the values
+    v2, m2, _ = oracle.compress(back)
+    assert np.array_equal(v2, v)
+    # a dense tensor is reported as violating
+    assert oracle.compress(dense)[2] > 0
+
+
+def test_storage_closed_forms_from_paper():
+    g = read_golden("storage_savings.txt")
+    N, K = 64, 256
+    for dtype, key in ((np.float16, "fp16_saving_percent"), (np.int8, "int8_saving_percent")):
+        W = np.zeros((N, K), dtype)
+        v, m, _ = oracle.compress(W)
+        dense_bytes = W.nbytes
+        comp_bytes = v.nbytes + m.nbytes
+        assert v.shape == (N, int(K * g["kept_fraction_of_K"]))
+        assert m.nbytes * 8 == v.size * g["metadata_bits_per_kept_value"]
+        assert 100.0 * (1.0 - comp_bytes / dense_bytes) == pytest.approx(g[key], abs=1e-12)
+    # fp32 dense model vs int8 2:4 model
+    v, m, _ = oracle.compress(np.zeros((N, K), np.int8))
+    assert (N * K * 4) / (v.nbytes + m.nbytes) == pytest.approx(g["fp32_dense_over_int8_2to4_size_ratio"], abs=1e-12)
+
+
+# ------------------------------------------------------------------ fp16 conversion
+def test_f16_conversions_against_numpy():
+    allbits = np.arange(65536, dtype=np.uint16)
+    as32 = allbits.view(np.float16).astype(np.float32)
+    for h in list(range(0, 65536, 97)) + [0, 1, 0x3FF, 0x400, 0x7BFF, 0x7C00, 0x8000, 0x8001, 0xFBFF, 0xFC00]:
+        f = oracle.f16_to_f32(h)
+        assert f == as32[h] or (math.isnan(f) and math.isnan(as32[h]))
+        if not math.isnan(f):
+            assert oracle.f32_to_f16(f) == h
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([
+        rng.standard_normal(4000).astype(np.float32) * np.float32(10.0) ** rng.integers(-9, 6, 4000).astype(np.float32),
+        np.array([65504, 65519.99, 65520, 1e9, 6.1e-5, 6.103515625e-05, 5.96e-8, 2.98e-8, 2.9802322e-8, 2.99e-8, 8.94e-8,
+                  1.0009765625, 1.00048828125, 1.00146484375, 2049, 2051, -0.0, 0.0], np.float32)])
+    with np.errstate(over="ignore"):
+        exp = xs.astype(np.float16).view(np.uint16)
+    for x, e in zip(xs, exp):
+        assert oracle.f32_to_f16(x) == e, (x, e)
+    # from a double: ties decided once, in fp64 (1 + 2^-11 + 2^-30 must round up although its fp32 image is a tie)
+    assert oracle.f64_to_f16(1.0 + 2.0 ** -11) == 0x3C00
+    assert oracle.f64_to_f16(1.0 + 2.0 ** -11 + 2.0 ** -30) == 0x3C01
+    assert oracle.f64_to_f16(1.0 + 3 * 2.0 ** -11) == 0x3C02
+
+
+# ------------------------------------------------------------------ a2 / a4 quantise
+def test_quantize_properties():
+    W = synth.weights(64, 128, seed=7)
+    P, _ = oracle.prune_2to4(W)
+    q, s = oracle.quantize_rows_int8(P)
+    q_dense, s_dense = oracle.quantize_rows_int8(W)
+    # the row maximum always survives pruning, so the per-channel scale does not change
+    assert np.array_equal(s, s_dense)
+    assert np.array_equal(s, (np.abs(W).max(1) / np.float32(127.0)).astype(np.float32))
+    assert np.abs(q.astype(np.int32)).max() == 127 and q.min() >= -127
+    # the row maximum maps to +-127 exactly; error bound s/2 (plus fp32 rounding of the division)
+    assert (np.abs(q).max(1) == 127).all()
+    err = np.abs(P.astype(np.float64) - s[:, None].astype(np.float64) * q)
+    assert (err <= 0.5 * s[:, None] * (1 + 1e-6)).all()
+    # zeros stay zero: the quantised tensor is still 2:4
+    assert ((q.reshape(64, -1, 4) != 0).sum(-1) <= 2).all()
+    # integers with amax 127 are reproduced exactly (scale 1)
+    Z = np.random.default_rng(0).integers(-127, 128, size=(5, 32)).astype(np.float32)
+    Z[:, 0] = 127
+    qz, sz = oracle.quantize_rows_int8(Z)
+    assert (sz == 1).all() and np.array_equal(qz, Z.astype(np.int8))
+    # all-zero row: scale 1, codes 0
+    qz, sz = oracle.quantize_rows_int8(np.zeros((2, 8), np.float32))
+    assert (sz == 1).all() and (qz == 0).all()
+    # round-half-even: x/s exactly k + 0.5
+    X = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5]], np.float32)
+    qh, sh = oracle.quantize_rows_int8(X)
+    assert sh[0] == 1 and list(qh[0]) == [127, 0, 2, 2, 0, -2, -2, 126]
+    # static scale: clamps at +-127
+    qs, _ = oracle.quantize_rows_int8(np.array([[1000.0, -1000.0, 3.0, -3.49]], np.float32), scale=np.array([1.0], np.float32))
+    assert list(qs[0]) == [127, -127, 3, -3]
+
+
+def test_quantize_tensor_matches_numpy_float64_rounding():
+    X = synth.activations(197, 192, "normal_clip4", seed=0)
+    q, s = oracle.quantize_tensor_int8(X)
+    assert np.float32(s) == np.float32(np.abs(X).max()) / np.float32(127.0)
+    # fp32 division then rint; compare with numpy's own fp32 division and rint (both IEEE)
+    exp = np.clip(np.rint(X / np.float32(s)), -127, 127).astype(np.int8)
+    assert np.array_equal(q, exp)
+    assert np.abs(q.astype(int)).max() == 127
+    assert (np.abs(X - np.float64(s) * q) <= 0.5 * s * (1 + 1e-6)).all()
+    q2, s2 = oracle.quantize_tensor_int8(X, scale=0.05)
+    assert s2 == np.float32(0.05) and np.array_equal(q2, np.clip(np.rint(X / np.float32(0.05)), -127, 127).astype(np.int8))
+
+
+# ------------------------------------------------------------------ a5 GEMM
+def _int8_problem(M, K, N, seed):
+    X = synth.activations(M, K, "normal_clip4", seed=seed, ids=(1,))
+    W = synth.weights(N, K, seed=seed, ids=(1,))
+    P, _ = oracle.prune_2to4(W)
+    Wq, s_w = oracle.quantize_rows_int8(P)
+    Xq, s_a = oracle.quantize_tensor_int8(X)
+    vals, meta, viol = oracle.compress(Wq)
+    assert viol == 0
+    return Xq, s_a, Wq, s_w, vals, meta
+
+
+def test_int8_sparse_gemm_equals_dense_on_masked_weights_and_numpy():
+    Xq, s_a, Wq, s_w, vals, meta = _int8_problem(37, 192, 48, seed=11)
+    dense = oracle.gemm_int8_dense(Xq, Wq)
+    sparse = oracle.spgemm_int8(Xq, vals, meta)
+    ref = Xq.astype(np.int64) @ Wq.astype(np.int64).T
+    assert np.array_equal(dense, ref)  # numpy's matmul: catches a transposed operand or a wrong stride
+    assert np.array_equal(sparse, dense)  # the sparse form computes the same C
+    # extreme values: no saturation, plain int32 wrap-free accumulation
+    Xe = np.full((3, 64), -127, np.int8); We = np.zeros((5, 64), np.int8); We[:, 0::4] = 127; We[:, 3::4] = -127
+    v, m, _ = oracle.compress(We)
+    assert np.array_equal(oracle.spgemm_int8(Xe, v, m), Xe.astype(np.int64) @ We.astype(np.int64).T)
+
+
+def test_sparse_gemm_special_cases_pin_the_metadata():
+    rng = np.random.default_rng(4)
+    K, N = 64, 24
+    W = rng.integers(-9, 10, size=(N, K)).astype(np.float32)
+    P, mask = oracle.prune_2to4(W)
+    Wq = P.astype(np.int8)
+    vals, meta, _ = oracle.compress(Wq)
+    # X = identity: the product returns the decompressed weight matrix, transposed
+    I = np.eye(K, dtype=np.int8)
+    assert np.array_equal(oracle.spgemm_int8(I, vals, meta), Wq.T.astype(np.int32))
+    # all kept values = 1: each output is the sum of the X entries at the kept positions
+    ones = np.ones_like(vals)
+    X = rng.integers(-5, 6, size=(7, K)).astype(np.int8)
+    keep = np.unpackbits(mask[..., None], axis=-1, bitorder="little")[..., :4].reshape(N, K)
+    # positions recorded by compress (zeros filled lowest-index-first) may differ from the prune mask only where the
+    # kept value is zero; recompute the positions from the metadata itself, by hand
+    pos = np.zeros((N, K), np.int64)
+    for n in range(N):
+        for g in range(K // 4):
+            nib = (meta[n, g // 2] >> (4 * (g & 1))) & 0xF
+            pos[n, 4 * g + (nib & 3)] += 1
+            pos[n, 4 * g + (nib >> 2)] += 1
+    assert np.array_equal(oracle.spgemm_int8(X, ones, meta), X.astype(np.int64) @ pos.T)
+    assert ((pos == 1) >= (Wq != 0)).all() and ((keep == 1) >= (Wq != 0)).all()
+
+
+def test_fp16_gemm_exact_on_small_integers_and_close_on_gaussians():
+    K, N, M = 256, 40, 23
+    X = synth.small_integers((M, K), -4, 4, seed=1).astype(np.float16)
+    W = synth.small_integers((N, K), -4, 4, seed=2).astype(np.float32)
+    P, _ = oracle.prune_2to4(W)
+    Wh = P.astype(np.float16)
+    vals, meta, viol = oracle.compress(Wh)
+    assert viol == 0
+    ref = X.astype(np.float64) @ Wh.astype(np.float64).T  # exact: all partial sums are small integers
+    d32, d64 = oracle.gemm_fp16_dense(X, Wh)
+    s32, s64 = oracle.spgemm_fp16(X, vals, meta)
+    for a in (d32, d64, s32, s64):
+        assert np.array_equal(a.astype(np.float64), ref)
+    # Gaussian data: fp64 accumulation agrees with numpy's float64 matmul; fp32 sequential sum within K*eps*sum|terms|
+    Xg = synth.activations(M, K, seed=3).astype(np.float16)
+    Wg, _ = oracle.prune_2to4(synth.weights(N, K, seed=3))
+    Wg = Wg.astype(np.float16)
+    vals, meta, _ = oracle.compress(Wg)
+    ref = Xg.astype(np.float64) @ Wg.astype(np.float64).T
+    bound = np.abs(Xg.astype(np.float64)) @ np.abs(Wg.astype(np.float64)).T
+    d32, d64 = oracle.gemm_fp16_dense(Xg, Wg)
+    s32, s64 = oracle.spgemm_fp16(Xg, vals, meta)
+    assert np.abs(d64 - ref).max() <= 1e-13 * bound.max() * K
+    assert np.abs(s64 - ref).max() <= 1e-13 * bound.max() * K
+    assert (np.abs(d32 - ref) <= K * 2.0 ** -24 * bound + 1e-30).all()
+    assert (np.abs(s32 - ref) <= K * 2.0 ** -24 * bound + 1e-30).all()
+
+
+# ------------------------------------------------------------------ a6 epilogue
+def test_epilogue_special_cases_and_gelu_table():
+    cdf = read_golden("normal_cdf.txt")
+    xs = sorted(float(k) for k in cdf)
+    # acc = x * 1024, s_a * s_w = 2^-10 (exact): v = x; GELU(x) = x * Phi(x)
+    acc = np.array([[int(x * 1024) for x in xs]], np.int32)
+    s_w = np.full(len(xs), np.float32(1.0), np.float32)
+    out = oracle.epilogue_int8_f64(acc, 2.0 ** -10, s_w, None, gelu=True)
+    for j, x in enumerate(xs):
+        assert out["ref"][0, j] == pytest.approx(x * cdf[x], rel=2e-9, abs=1e-12)
+    out32 = oracle.epilogue_int8_f32(acc, 2.0 ** -10, s_w, None, gelu=True)
+    for j, x in enumerate(xs):
+        assert out32["v32"][0, j] == pytest.approx(x * cdf[x], rel=1e-7, abs=1e-12)
+    # identity epilogue on exactly representable numbers
+    acc = np.arange(-2048, 2049, dtype=np.int32).reshape(1, -1)
+    one = np.ones(acc.shape[1], np.float32)
+    o = oracle.epilogue_int8_f64(acc, 1.0, one, None, gelu=False)
+    assert np.array_equal(o["y16"].astype(np.int32), acc) and np.array_equal(o["ref"], acc.astype(np.float64))
+    # bias and per-channel scale are applied along n, not m (asymmetric shapes catch a transposed index)
+    acc = np.array([[1, 2, 3], [4, 5, 6]], np.int32)
+    s_w = np.array([1.0, 0.5, 0.25], np.float32); b = np.array([10.0, 20.0, 30.0], np.float32)
+    o = oracle.epilogue_int8_f64(acc, 2.0, s_w, b, gelu=False, out_scale=0.5)
+    assert np.array_equal(o["ref"], np.array([[12.0, 22.0, 31.5], [18.0, 25.0, 33.0]]))
+    assert np.array_equal(o["q8"], np.array([[24, 44, 63], [36, 50, 66]], np.int8))
+    o32 = oracle.epilogue_int8_f32(acc, 2.0, s_w, b, gelu=False, out_scale=0.5)
+    assert np.array_equal(o32["v32"].astype(np.float64), o["ref"]) and np.array_equal(o32["q8"], o["q8"])
+    # GELU limits: GELU(0) = 0, identity for large x, vanishing for very negative x
+    acc = np.array([[0, 8000, -8000]], np.int32)
+    o = oracle.epilogue_int8_f64(acc, 0.001, np.ones(3, np.float32), None, gelu=True)
+    assert o["ref"][0, 0] == 0 and o["ref"][0, 1] == pytest.approx(8.0, rel=1e-6) and abs(o["ref"][0, 2]) < 1e-12
+    # fp16 path: bias added along n
+    o = oracle.epilogue_fp16_f64(np.array([[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]]), b, gelu=False)
+    assert np.array_equal(o["ref"], np.array([[11.0, 22.0, 33.0], [14.0, 25.0, 36.0]]))
+    assert np.array_equal(o["y16"].astype(np.float64), o["ref"])
+
+
+def test_epilogue_fp32_sequence_within_one_fp16_ulp_of_fp64():
+    Xq, s_a, Wq, s_w, vals, meta = _int8_problem(29, 128, 64, seed=21)
+    acc = oracle.spgemm_int8(Xq, vals, meta)
+    b = synth.bias(64, seed=21)
+    for gelu in (False, True):
+        o64 = oracle.epilogue_int8_f64(acc, s_a, s_w, b, gelu=gelu)
+        o32 = oracle.epilogue_int8_f32(acc, s_a, s_w, b, gelu=gelu)
+        assert np.abs(o32["v32"] - o64["ref"]).max() <= 4e-7 * np.abs(o64["ref"]).max()
+        d = np.abs(o32["y16"].view(np.int16).astype(np.int32) - o64["y16"].view(np.int16).astype(np.int32))
+        assert d.max() <= 1
+    # whole-layer helper used for timing = spgemm + fp64 epilogue
+    y = oracle.linear_int8_sparse(Xq, vals, meta, s_a, s_w, b, gelu=True)
+    assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f64(acc, s_a, s_w, b, gelu=True)["y16"].view(np.uint16))
+
+
+def test_end_to_end_dequantised_layer_approximates_the_float_layer():
+    """prune -> quantise -> compress -> sparse GEMM -> dequant reproduces X @ prune(W)^T to quantisation accuracy"""
+    M, K, N = 64, 192, 96
+    X = synth.activations(M, K, "normal_clip4", seed=5)
+    W = synth.weights(N, K, seed=5)
+    P, _ = oracle.prune_2to4(W)
+    Wq, s_w = oracle.quantize_rows_int8(P)
+    Xq, s_a = oracle.quantize_tensor_int8(X)
+    vals, meta, _ = oracle.compress(Wq)
+    acc = oracle.spgemm_int8(Xq, vals, meta)
+    y = oracle.epilogue_int8_f64(acc, s_a, s_w, None)["ref"]
+    ref = X.astype(np.float64) @ P.astype(np.float64).T
+    assert np.abs(y - ref).max() / np.abs(ref).max() < 0.03
+    assert np.corrcoef(y.ravel(), ref.ravel())[0, 1] > 0.999
