@@ -1,0 +1,127 @@
+/*
+ * gpusq.h -- C ABI of libgpusq: 2:4 fine-grained structured-sparse linear layers (FP16 and INT8) for AMD MI355X.
+ *
+ * The library implements the deployment hot path of "Boost Vision Transformer with GPU-Friendly Sparsity and
+ * Quantization" (CVPR 2023): the sparse x dense -> dense GEMM of Sec. 3.1 / Fig. 1 behind the Q/K/V projection,
+ * attention output projection and feed-forward linears named in Sec. 3.2, with the weight-preparation steps
+ * (2:4 pruning, symmetric INT8 quantisation, compression to kept values + 2-bit metadata).
+ *
+ * Notation.  The paper's sparse operand "A" (M x K, 2:4 along K) is the weight matrix W [N][K] here (nn.Linear
+ * layout, K contiguous); the dense operand is the activation matrix X [M][K] (tokens x features, K contiguous);
+ * the result is Y [M][N] = X * W^T (+ bias, + GELU), row-major.
+ *
+ * Conventions for every call.
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library never allocates, frees or keeps
+ *     device memory.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls enqueue work on `stream` and return; they do not synchronise.
+ *   - The return value is a gpusq_status.  Argument errors are detected on the host before anything is launched
+ *     and leave the outputs untouched.  A failed launch returns GPUSQ_ERR_HIP; gpusq_last_hip_error() gives the
+ *     HIP error code.  No exception crosses this boundary.
+ *   - Tensors are dense row-major without padding; all pointers must be 16-byte aligned (GPUSQ_ERR_ALIGN).
+ *   - K must be a multiple of 4 (a row is made of whole groups of 4; GPUSQ_ERR_SHAPE otherwise).  The GEMM entry
+ *     points additionally need K % 16 == 0 and N % 4 == 0 (GPUSQ_ERR_UNSUPPORTED otherwise); M is arbitrary.
+ *     Sizes must be positive and M*N, M*K, N*K below 2^31 elements... see each call.
+ *   - Thread safety: calls on distinct streams may run concurrently; the library holds no mutable global state
+ *     besides the last HIP error code.
+ */
+#ifndef GPUSQ_H
+#define GPUSQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GPUSQ_OK = 0,
+  GPUSQ_ERR_NULL = 1,        /* a required pointer is NULL */
+  GPUSQ_ERR_SHAPE = 2,       /* non-positive size, K % 4 != 0, or a size beyond the supported range */
+  GPUSQ_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned */
+  GPUSQ_ERR_UNSUPPORTED = 4, /* valid for the method but not implemented (dtype, divisibility, epilogue bits) */
+  GPUSQ_ERR_HIP = 5          /* a HIP call or kernel launch failed */
+} gpusq_status;
+
+typedef enum { GPUSQ_F32 = 0, GPUSQ_F16 = 1, GPUSQ_I8 = 2, GPUSQ_I32 = 3 } gpusq_dtype;
+
+/* epilogue bit flags */
+enum { GPUSQ_EPI_NONE = 0, GPUSQ_EPI_BIAS = 1, GPUSQ_EPI_GELU = 2 };
+
+/* quantisation granularity */
+enum { GPUSQ_PER_ROW = 0, GPUSQ_PER_TENSOR = 1 };
+
+const char* gpusq_status_string(gpusq_status s);
+int gpusq_last_hip_error(void);
+int gpusq_version(void);
+
+/* ---- 2:4 pruning [Sec. 1; Sec. 3.1: two of every four contiguous elements on a row of the sparse operand are
+ * zero].  The paper does not print the selection rule; this library keeps the two largest magnitudes of each group
+ * of 4 along K (ties: the lower index is kept) and writes +0 to the other two.
+ *   W_in, W_out : [N][K] of dt (GPUSQ_F32 or GPUSQ_F16); W_out may be the same pointer as W_in.
+ *   mask_out    : optional [N][K/4] bytes; bit i of a byte is set iff element 4g+i of the group was kept. */
+gpusq_status gpusq_prune_2to4(const void* W_in, void* W_out, uint8_t* mask_out, gpusq_dtype dt,
+                              int64_t N, int64_t K, void* stream);
+
+/* ---- symmetric INT8 quantisation with a scale factor [Sec. 2.2; Sec. 3.4].  q = clamp(rint(x / s), -127, 127),
+ * fp32 division, round-half-even; s = max|x| / 127 over a row (GPUSQ_PER_ROW: per output channel, scale has `rows`
+ * floats) or over the whole tensor (GPUSQ_PER_TENSOR: scale has 1 float); an all-zero range gives s = 1.
+ *   X [rows][cols] of dt (GPUSQ_F32 or GPUSQ_F16), Xq [rows][cols] int8, scale: device floats.
+ *   scale_is_input != 0: use the caller's scale(s) (calibrated / learned values) instead of computing them.
+ *   workspace: device scratch of gpusq_quantize_workspace_bytes(mode, rows, cols) bytes (may be NULL when that is 0);
+ *   its previous contents do not matter. */
+size_t gpusq_quantize_workspace_bytes(int mode, int64_t rows, int64_t cols);
+gpusq_status gpusq_quantize_int8(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode,
+                                 int scale_is_input, int64_t rows, int64_t cols, void* workspace, void* stream);
+
+/* ---- compression [Sec. 3.1, Fig. 1 and Fig. 2 captions]: the N x K operand becomes N x K/2 kept values plus
+ * 2 bits of metadata per kept value giving its position in its group of 4.
+ *   W      : [N][K] of dt (GPUSQ_F16 or GPUSQ_I8)
+ *   values : [N][K/2] of dt; the two kept values of group g at 2g, 2g+1, in ascending position order
+ *   meta   : [N][ceil(K/8)] bytes; byte b of a row holds group 2b in bits 0..3 and group 2b+1 in bits 4..7; inside
+ *            a nibble, bits 0..1 = position of the first kept value, bits 2..3 = position of the second (first <
+ *            second).  Positions are chosen by the pruning rule applied to W itself, so the non-zeros of a 2:4
+ *            tensor are always kept and spare slots go to the lowest-index zeros.
+ *   violations : optional device int32, set to the number of groups in which a dropped element was non-zero
+ *            (0 iff W obeys the 2:4 pattern). */
+gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,
+                            int64_t N, int64_t K, void* stream);
+/* inverse: zero-fill W [N][K] and scatter the values to the recorded positions */
+gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt,
+                              int64_t N, int64_t K, void* stream);
+
+/* ---- kernel-native packing of the compressed operand: re-tiles (values, meta) into the per-lane register order
+ * of the gfx950 sparse matrix instructions (v_smfmac_*), rows and K zero-padded to whole tiles.  The packed buffer
+ * is opaque; its size is gpusq_packed_bytes(dt, N, K) bytes (0 for invalid arguments). */
+size_t gpusq_packed_bytes(gpusq_dtype dt, int64_t N, int64_t K);
+gpusq_status gpusq_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt,
+                        int64_t N, int64_t K, void* stream);
+
+/* ---- sparse GEMM with fused epilogue [Sec. 3.1: sparse matrix x dense matrix = dense matrix, the same result as
+ * the dense GEMM on the zero-filled operand, computed over the kept values only].
+ * FP16: Y[m][n] = fp16( act( sum_k X[m][k] * W[n][k]  (fp32 accumulation) + bias[n] ) )
+ *   X [M][K] fp16, Wpacked from gpusq_pack(GPUSQ_F16), bias [N] fp32 (required iff GPUSQ_EPI_BIAS), Y [M][N] fp16;
+ *   act = exact-erf GELU iff GPUSQ_EPI_GELU. */
+gpusq_status gpusq_spgemm_fp16(const void* X, const void* Wpacked, const float* bias, void* Y,
+                               int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
+/* INT8: acc[m][n] = sum_k Xq[m][k] * Wq[n][k] in int32 (exact);
+ *   out_dt = GPUSQ_I32: Y [M][N] int32 = acc (scales, bias, epilogue ignored);
+ *   out_dt = GPUSQ_F16: Y = fp16( act( fma((float)acc, act_scale[0] * w_scale[n], bias[n]) ) );
+ *   out_dt = GPUSQ_I8 : Y = clamp(rint( act(...) / out_scale[0] ), -127, 127) as int8 (re-quantised for the next layer).
+ *   act_scale, out_scale: device pointers to 1 float; w_scale: device [N] floats. */
+gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const float* act_scale, const float* w_scale,
+                               const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale,
+                               int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
+
+/* ---- dense twins: the same computation from the masked but uncompressed W [N][K], on dense matrix instructions,
+ * built the same way; the baseline the sparse kernels are compared with. */
+gpusq_status gpusq_gemm_fp16_dense(const void* X, const void* W, const float* bias, void* Y,
+                                   int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
+gpusq_status gpusq_gemm_int8_dense(const int8_t* Xq, const int8_t* Wq, const float* act_scale, const float* w_scale,
+                                   const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale,
+                                   int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPUSQ_H */

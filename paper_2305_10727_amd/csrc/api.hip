@@ -1,0 +1,167 @@
+// C ABI of libgpusq: argument validation, status codes, dispatch to the kernels.  No computation happens here.
+#include <atomic>
+
+#include "common.h"
+
+namespace gpusq {
+static std::atomic<int> g_last_hip_error{0};
+void set_last_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
+}  // namespace gpusq
+
+using namespace gpusq;
+
+namespace {
+constexpr int64_t kMaxElems = (int64_t)1 << 40;
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+gpusq_status check_nk(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0 || K % 4 != 0) return GPUSQ_ERR_SHAPE;
+  if (N > INT32_MAX || K > INT32_MAX || N * K > kMaxElems) return GPUSQ_ERR_SHAPE;
+  return GPUSQ_OK;
+}
+
+gpusq_status check_gemm(const void* X, const void* W, const float* bias, const void* Y, int64_t M, int64_t N, int64_t K,
+                        int epilogue) {
+  if (!X || !W || !Y) return GPUSQ_ERR_NULL;
+  if ((epilogue & GPUSQ_EPI_BIAS) && !bias) return GPUSQ_ERR_NULL;
+  if (M <= 0) return GPUSQ_ERR_SHAPE;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (M > INT32_MAX || M * N > kMaxElems || M * K > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || (bias && !aligned16(bias))) return GPUSQ_ERR_ALIGN;
+  if (epilogue & ~(GPUSQ_EPI_BIAS | GPUSQ_EPI_GELU)) return GPUSQ_ERR_UNSUPPORTED;
+  if (K % 16 != 0 || N % 4 != 0) return GPUSQ_ERR_UNSUPPORTED;
+  return GPUSQ_OK;
+}
+
+gpusq_status check_int8_extras(const float* act_scale, const float* w_scale, gpusq_dtype out_dt, const float* out_scale) {
+  if (out_dt != GPUSQ_F16 && out_dt != GPUSQ_I32 && out_dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (out_dt != GPUSQ_I32 && (!act_scale || !w_scale)) return GPUSQ_ERR_NULL;
+  if (out_dt == GPUSQ_I8 && !out_scale) return GPUSQ_ERR_NULL;
+  if (w_scale && !aligned16(w_scale)) return GPUSQ_ERR_ALIGN;
+  return GPUSQ_OK;
+}
+}  // namespace
+
+extern "C" {
+
+const char* gpusq_status_string(gpusq_status s) {
+  switch (s) {
+    case GPUSQ_OK: return "ok";
+    case GPUSQ_ERR_NULL: return "a required pointer is NULL";
+    case GPUSQ_ERR_SHAPE: return "invalid shape (sizes must be positive, K a multiple of 4)";
+    case GPUSQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case GPUSQ_ERR_UNSUPPORTED: return "valid request that this build does not implement";
+    case GPUSQ_ERR_HIP: return "HIP runtime or launch failure (see gpusq_last_hip_error)";
+  }
+  return "unknown status";
+}
+
+int gpusq_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int gpusq_version(void) { return 100; }
+
+gpusq_status gpusq_prune_2to4(const void* W_in, void* W_out, uint8_t* mask_out, gpusq_dtype dt, int64_t N, int64_t K,
+                              void* stream) {
+  if (!W_in || !W_out) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (dt != GPUSQ_F32 && dt != GPUSQ_F16) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(W_in) || !aligned16(W_out)) return GPUSQ_ERR_ALIGN;
+  return launch_prune(W_in, W_out, mask_out, dt, N, K, (hipStream_t)stream);
+}
+
+size_t gpusq_quantize_workspace_bytes(int mode, int64_t rows, int64_t cols) {
+  (void)rows;
+  (void)cols;
+  return mode == GPUSQ_PER_TENSOR ? 16 : 0;
+}
+
+gpusq_status gpusq_quantize_int8(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
+                                 int64_t rows, int64_t cols, void* workspace, void* stream) {
+  if (!X || !Xq || !scale) return GPUSQ_ERR_NULL;
+  if (rows <= 0 || cols <= 0 || rows > INT32_MAX || cols > INT32_MAX || rows * cols > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (dt != GPUSQ_F32 && dt != GPUSQ_F16) return GPUSQ_ERR_UNSUPPORTED;
+  if (mode != GPUSQ_PER_ROW && mode != GPUSQ_PER_TENSOR) return GPUSQ_ERR_UNSUPPORTED;
+  if (mode == GPUSQ_PER_TENSOR && !scale_is_input && !workspace) return GPUSQ_ERR_NULL;
+  if (!aligned16(X) || !aligned16(Xq) || (workspace && !aligned16(workspace))) return GPUSQ_ERR_ALIGN;
+  return launch_quantize(X, dt, Xq, scale, mode, scale_is_input, rows, cols, workspace, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt, int64_t N,
+                            int64_t K, void* stream) {
+  if (!W || !values || !meta) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(W) || !aligned16(values) || !aligned16(meta)) return GPUSQ_ERR_ALIGN;
+  return launch_compress(W, values, meta, violations, dt, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt, int64_t N, int64_t K,
+                              void* stream) {
+  if (!W || !values || !meta) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(W) || !aligned16(values) || !aligned16(meta)) return GPUSQ_ERR_ALIGN;
+  return launch_decompress(values, meta, W, dt, N, K, (hipStream_t)stream);
+}
+
+size_t gpusq_packed_bytes(gpusq_dtype dt, int64_t N, int64_t K) {
+  if (check_nk(N, K) != GPUSQ_OK || (dt != GPUSQ_F16 && dt != GPUSQ_I8)) return 0;
+  const bool is_i8 = dt == GPUSQ_I8;
+  const int64_t ksteps = ceil_div(K, step_elems(is_i8));
+  return (size_t)(ceil_div(N, kRowBlock) * ksteps * 4 * frag_bytes(is_i8));
+}
+
+gpusq_status gpusq_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,
+                        void* stream) {
+  if (!values || !meta || !packed) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(values) || !aligned16(meta) || !aligned16(packed)) return GPUSQ_ERR_ALIGN;
+  return launch_pack(values, meta, packed, dt, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_spgemm_fp16(const void* X, const void* Wpacked, const float* bias, void* Y, int64_t M, int64_t N,
+                               int64_t K, int epilogue, void* stream) {
+  gpusq_status st = check_gemm(X, Wpacked, bias, Y, M, N, K, epilogue);
+  if (st != GPUSQ_OK) return st;
+  GemmArgs a{X, Wpacked, nullptr, nullptr, bias, nullptr, Y, (int)M, (int)N, (int)K, epilogue, (int)GPUSQ_F16};
+  return launch_spgemm(false, a, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const float* act_scale, const float* w_scale,
+                               const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale, int64_t M,
+                               int64_t N, int64_t K, int epilogue, void* stream) {
+  gpusq_status st = check_gemm(Xq, Wpacked, bias, Y, M, N, K, epilogue);
+  if (st != GPUSQ_OK) return st;
+  st = check_int8_extras(act_scale, w_scale, out_dt, out_scale);
+  if (st != GPUSQ_OK) return st;
+  GemmArgs a{Xq, Wpacked, act_scale, w_scale, bias, out_scale, Y, (int)M, (int)N, (int)K, epilogue, (int)out_dt};
+  return launch_spgemm(true, a, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_gemm_fp16_dense(const void* X, const void* W, const float* bias, void* Y, int64_t M, int64_t N,
+                                   int64_t K, int epilogue, void* stream) {
+  gpusq_status st = check_gemm(X, W, bias, Y, M, N, K, epilogue);
+  if (st != GPUSQ_OK) return st;
+  GemmArgs a{X, W, nullptr, nullptr, bias, nullptr, Y, (int)M, (int)N, (int)K, epilogue, (int)GPUSQ_F16};
+  return launch_dense(false, a, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_gemm_int8_dense(const int8_t* Xq, const int8_t* Wq, const float* act_scale, const float* w_scale,
+                                   const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale, int64_t M,
+                                   int64_t N, int64_t K, int epilogue, void* stream) {
+  gpusq_status st = check_gemm(Xq, Wq, bias, Y, M, N, K, epilogue);
+  if (st != GPUSQ_OK) return st;
+  st = check_int8_extras(act_scale, w_scale, out_dt, out_scale);
+  if (st != GPUSQ_OK) return st;
+  GemmArgs a{Xq, Wq, act_scale, w_scale, bias, out_scale, Y, (int)M, (int)N, (int)K, epilogue, (int)out_dt};
+  return launch_dense(true, a, (hipStream_t)stream);
+}
+
+}  // extern "C"

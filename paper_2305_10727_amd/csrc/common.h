@@ -1,0 +1,70 @@
+// Internal declarations shared by the HIP translation units of libgpusq (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/gpusq.h"
+
+namespace gpusq {
+
+// ---- geometry of the kernel-native packed weight format (see pack.hip) ----------------------------------------
+// Rows are handled in blocks of 64 output channels = 4 fragments of 16 rows; K in steps of 128 bytes of the dense
+// activation row (128 int8 or 64 fp16 elements), which is the K extent of one gfx950 sparse matrix instruction
+// (v_smfmac_i32_16x16x128_i8 / v_smfmac_f32_16x16x64_f16).
+constexpr int kRowBlock = 64;          // output channels per packed row block
+constexpr int kFragRows = 16;          // rows of one instruction operand
+constexpr int kStepBytes = 128;        // bytes of a dense activation row consumed per K step
+constexpr int kFragValueBytes = 1024;  // 64 lanes x 16 bytes of kept values
+
+__host__ __device__ constexpr int step_elems(bool is_i8) { return is_i8 ? 128 : 64; }
+// index bytes of one fragment: 2 bits per kept value; 16 int8 values (32 bits) or 8 fp16 values (16 bits) per lane
+__host__ __device__ constexpr int frag_index_bytes(bool is_i8) { return is_i8 ? 256 : 128; }
+__host__ __device__ constexpr int frag_bytes(bool is_i8) { return kFragValueBytes + frag_index_bytes(is_i8); }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Row r (0..15) of fragment t (0..3) inside a 64-row block holds output channel
+//   n = 64*blk + 16*(r/4) + 4*t + (r%4).
+// The accumulator of a 16x16 matrix instruction gives lane l the rows 4*(l/16)..4*(l/16)+3 of its column, so with
+// this permutation a lane ends up with 16 consecutive output channels over the 4 fragments of a block and the four
+// lane groups of a wave cover 64 consecutive channels: full 128-byte lines of Y per activation row.
+__host__ __device__ inline int packed_row_to_channel(int t, int r) { return 16 * (r >> 2) + 4 * t + (r & 3); }
+
+void set_last_hip_error(hipError_t e);
+
+struct GemmArgs {
+  const void* X;
+  const void* W;  // packed (sparse) or dense [N][K]
+  const float* act_scale;
+  const float* w_scale;
+  const float* bias;
+  const float* out_scale;
+  void* Y;
+  int M, N, K;
+  int epilogue;
+  int out_dt;
+};
+
+gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s);
+gpusq_status launch_dense(bool is_i8, const GemmArgs& a, hipStream_t s);
+
+gpusq_status launch_prune(const void* Win, void* Wout, uint8_t* mask, gpusq_dtype dt, int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
+                             int64_t rows, int64_t cols, void* workspace, hipStream_t s);
+gpusq_status launch_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,
+                             int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt, int64_t N, int64_t K,
+                               hipStream_t s);
+gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,
+                         hipStream_t s);
+
+inline gpusq_status check_launch() {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_last_hip_error(e);
+    return GPUSQ_ERR_HIP;
+  }
+  return GPUSQ_OK;
+}
+
+}  // namespace gpusq

@@ -1,0 +1,241 @@
+// Dense twin of the sparse GEMM: the same product computed from the masked but uncompressed weights on the dense
+// matrix instructions (v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_f16), with the same tile pipeline, the same
+// fused epilogue and the same output order.  It is the baseline of the "T cycles vs T/2 cycles" comparison of
+// Sec. 3.1; it reads K bytes of W per output channel where the sparse kernel reads K/2 + K/8.
+//
+// Register semantics (measured): A (4 VGPRs) lane l byte i -> row l%32, K index 16*(l/32)+i (8*(l/32)+i for fp16
+// elements); B likewise with column l%32; D (16 VGPRs) lane l register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+#include "common.h"
+
+namespace gpusq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+constexpr int kLdsRowD = kStepBytes + 16;
+
+template <bool IS_I8>
+struct AccD { typedef v16f type; };
+template <>
+struct AccD<true> { typedef v16i type; };
+
+template <bool IS_I8>
+__device__ __forceinline__ typename AccD<IS_I8>::type mfma32(v4i a, v4i b, typename AccD<IS_I8>::type c) {
+  if constexpr (IS_I8)
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float gelu_dense_f32(float v) { return 0.5f * v * erfcf(-0.70710678118654752f * v); }
+
+__device__ __forceinline__ int requantize_dense(float v, float s) {
+  float r = rintf(__fdiv_rn(v, s));
+  r = fminf(fmaxf(r, -127.0f), 127.0f);
+  return (v != v) ? 0 : (int)r;
+}
+
+// LDS row of output channel c (0..63) inside a wavefront's 64-channel block.  Accumulator register r of lane half h
+// in 32-row tile t is tile row 8*(r/4)+4h+r%4; placing channel 32h+16t+r there gives a lane 32 consecutive channels.
+__device__ __forceinline__ int lds_row_of_channel(int c) {
+  const int h = c >> 5, t = (c >> 4) & 1, r = c & 15;
+  return 32 * t + 8 * (r >> 2) + 4 * h + (r & 3);
+}
+
+template <bool IS_I8>
+__device__ __forceinline__ void store_16_dense(const GemmArgs& a, int64_t m, int n, const float (&v)[16], const int (&raw)[16]) {
+  const int N = a.N;
+  const bool full = n + 16 <= N;
+  if (IS_I8 && a.out_dt == GPUSQ_I32) {
+    int* y = (int*)a.Y + m * N + n;
+    if (full) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) *(v4i*)(y + 4 * j) = v4i{raw[4 * j], raw[4 * j + 1], raw[4 * j + 2], raw[4 * j + 3]};
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (n + j < N) y[j] = raw[j];
+    }
+  } else if (IS_I8 && a.out_dt == GPUSQ_I8) {
+    const float so = a.out_scale[0];
+    int8_t* y = (int8_t*)a.Y + m * N + n;
+    int q[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) q[j] = requantize_dense(v[j], so) & 0xFF;
+    if (full && (N & 15) == 0) {
+      v4i pk;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pk[j] = q[4 * j] | (q[4 * j + 1] << 8) | (q[4 * j + 2] << 16) | (q[4 * j + 3] << 24);
+      *(v4i*)y = pk;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (n + j < N) y[j] = (int8_t)q[j];
+    }
+  } else {
+    _Float16* y = (_Float16*)a.Y + m * N + n;
+    if (full && (N & 7) == 0) {
+      v8h lo, hi;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        lo[j] = (_Float16)v[j];
+        hi[j] = (_Float16)v[8 + j];
+      }
+      *(v8h*)y = lo;
+      *(v8h*)(y + 8) = hi;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (n + j < N) y[j] = (_Float16)v[j];
+    }
+  }
+}
+
+// Workgroup = 4 wavefronts WN x WM; a wavefront owns 2 x TM accumulator tiles of 32 x 32 (64 channels x TM*32 rows).
+template <bool IS_I8, int TM, int WN, int WM>
+__global__ void __launch_bounds__(256) dense_kernel(const GemmArgs a, const int tiles_n, const int tiles_total) {
+  static_assert(WN * WM == 4, "4 wavefronts");
+  typedef typename AccD<IS_I8>::type acc_t;
+  constexpr int BN = WN * 64, BM = WM * TM * 32;
+  constexpr int ES = IS_I8 ? 1 : 2;
+  constexpr int XCH = BM / 32, WCH = BN / 32;
+
+  __shared__ __attribute__((aligned(16))) uint8_t Xs[2][BM * kLdsRowD];
+  __shared__ __attribute__((aligned(16))) uint8_t Ws[2][BN * kLdsRowD];
+
+  const int per_xcd = (tiles_total + 7) / 8;
+  const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (tile >= tiles_total) return;
+  const int n_blk = tile % tiles_n, m_blk = tile / tiles_n;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = wave % WN, wm = wave / WN;
+  const int M = a.M, N = a.N;
+  const int64_t k_bytes = (int64_t)a.K * ES;
+  const int ksteps = (int)((k_bytes + kStepBytes - 1) / kStepBytes);
+  const uint8_t* Xg = (const uint8_t*)a.X;
+  const uint8_t* Wg = (const uint8_t*)a.W;
+
+  acc_t acc[2][TM];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+  v4i xr[XCH], wr[WCH];
+  auto load_tiles = [&](int ks) {
+#pragma unroll
+    for (int j = 0; j < XCH; ++j) {
+      const int c = tid + 256 * j;
+      const int64_t m = (int64_t)m_blk * BM + (c >> 3);
+      const int64_t off = (int64_t)ks * kStepBytes + (c & 7) * 16;
+      xr[j] = (m < M && off < k_bytes) ? *(const v4i*)(Xg + m * k_bytes + off) : v4i{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int j = 0; j < WCH; ++j) {
+      const int c = tid + 256 * j;
+      const int64_t n = (int64_t)n_blk * BN + (c >> 3);
+      const int64_t off = (int64_t)ks * kStepBytes + (c & 7) * 16;
+      wr[j] = (n < N && off < k_bytes) ? *(const v4i*)(Wg + n * k_bytes + off) : v4i{0, 0, 0, 0};
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < XCH; ++j) {
+      const int c = tid + 256 * j;
+      *(v4i*)(&Xs[buf][(c >> 3) * kLdsRowD + (c & 7) * 16]) = xr[j];
+    }
+#pragma unroll
+    for (int j = 0; j < WCH; ++j) {
+      const int c = tid + 256 * j;
+      const int ch = c >> 3;  // channel inside the workgroup tile
+      const int row = (ch & ~63) + lds_row_of_channel(ch & 63);
+      *(v4i*)(&Ws[buf][row * kLdsRowD + (c & 7) * 16]) = wr[j];
+    }
+  };
+
+  load_tiles(0);
+  store_tiles(0);
+  __syncthreads();
+
+  const int l32 = lane & 31, h16 = (lane >> 5) * 16;
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const int cur = ks & 1;
+    const bool more = ks + 1 < ksteps;
+    if (more) load_tiles(ks + 1);
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      v4i af[2], bf[TM];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) af[t] = *(const v4i*)(&Ws[cur][(wn * 64 + 32 * t + l32) * kLdsRowD + 32 * sub + h16]);
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) bf[mt] = *(const v4i*)(&Xs[cur][((wm * TM + mt) * 32 + l32) * kLdsRowD + 32 * sub + h16]);
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt) acc[t][mt] = mfma32<IS_I8>(af[t], bf[mt], acc[t][mt]);
+    }
+    if (more) store_tiles(cur ^ 1);
+    __syncthreads();
+  }
+
+  const bool use_bias = (a.epilogue & GPUSQ_EPI_BIAS) != 0, use_gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
+  const bool raw_out = IS_I8 && a.out_dt == GPUSQ_I32;
+  float s_a = 1.0f;
+  if (IS_I8 && !raw_out) s_a = a.act_scale[0];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int n = n_blk * BN + wn * 64 + (lane >> 5) * 32 + 16 * t;
+    if (n >= N) continue;
+    float cs[16], bs[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const bool ok = n + j < N;
+      cs[j] = (IS_I8 && !raw_out && ok) ? s_a * a.w_scale[n + j] : 1.0f;
+      bs[j] = (use_bias && ok && !raw_out) ? a.bias[n + j] : 0.0f;
+    }
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+      const int64_t m = (int64_t)m_blk * BM + (wm * TM + mt) * 32 + l32;
+      if (m >= M) continue;
+      float v[16];
+      int raw[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        if constexpr (IS_I8) {
+          raw[j] = acc[t][mt][j];
+          const float f = (float)raw[j];
+          v[j] = use_bias ? __fmaf_rn(f, cs[j], bs[j]) : f * cs[j];
+        } else {
+          raw[j] = 0;
+          v[j] = acc[t][mt][j] + bs[j];
+        }
+        if (use_gelu) v[j] = gelu_dense_f32(v[j]);
+      }
+      store_16_dense<IS_I8>(a, m, n, v, raw);
+    }
+  }
+}
+
+template <bool IS_I8, int TM, int WN, int WM>
+static gpusq_status launch_cfg(const GemmArgs& a, hipStream_t s) {
+  constexpr int BN = WN * 64, BM = WM * TM * 32;
+  const int tiles_n = (int)ceil_div(a.N, BN), tiles_m = (int)ceil_div(a.M, BM);
+  const int total = tiles_n * tiles_m;
+  const int grid = (int)ceil_div(total, 8) * 8;
+  dense_kernel<IS_I8, TM, WN, WM><<<grid, 256, 0, s>>>(a, tiles_n, total);
+  return check_launch();
+}
+
+gpusq_status launch_dense(bool is_i8, const GemmArgs& a, hipStream_t s) {
+  const int64_t work = (int64_t)a.M * a.N;
+  if (work <= (int64_t)256 * 1024)
+    return is_i8 ? launch_cfg<true, 1, 1, 4>(a, s) : launch_cfg<false, 1, 1, 4>(a, s);  // 64 x 128 tiles
+  return is_i8 ? launch_cfg<true, 2, 2, 2>(a, s) : launch_cfg<false, 2, 2, 2>(a, s);    // 128 x 128 tiles
+}
+
+}  // namespace gpusq

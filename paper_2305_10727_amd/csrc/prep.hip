@@ -1,0 +1,346 @@
+// Weight / activation preparation kernels: 2:4 pruning, symmetric INT8 quantisation, compression to kept values +
+// 2-bit metadata, decompression, and re-tiling into the kernel-native packed format.
+// All of them stream their operands once and are bound by HBM bandwidth; work is laid out wavefront-parallel over
+// groups of 4 (one lane per group or per pair of groups), with 16-byte accesses where the layout allows.
+#include "common.h"
+
+namespace gpusq {
+
+// ------------------------------------------------------------------------------------------------------------
+// Selection rule inside one group of 4 [Sec. 3.1: two of every four contiguous elements are zero; the rule is this
+// library's reading]: element i is kept iff fewer than two elements beat it, where j beats i when |w_j| > |w_i|, or
+// |w_j| == |w_i| and j < i.  Magnitudes are compared as sign-cleared bit patterns (a total order).
+// Returns the 4-bit keep mask (exactly two bits set).
+__device__ __forceinline__ unsigned keep_mask_of_4(unsigned k0, unsigned k1, unsigned k2, unsigned k3) {
+  const unsigned r0 = (k1 > k0) + (k2 > k0) + (k3 > k0);
+  const unsigned r1 = (k0 >= k1) + (k2 > k1) + (k3 > k1);
+  const unsigned r2 = (k0 >= k2) + (k1 >= k2) + (k3 > k2);
+  const unsigned r3 = (k0 >= k3) + (k1 >= k3) + (k2 >= k3);
+  return (r0 < 2u) | ((r1 < 2u) << 1) | ((r2 < 2u) << 2) | ((r3 < 2u) << 3);
+}
+
+// positions of the two set bits of a keep mask, packed as the metadata nibble p0 | p1 << 2 (p0 < p1)
+__device__ __forceinline__ unsigned nibble_of_mask(unsigned m) {
+  const unsigned p0 = __builtin_ctz(m);
+  const unsigned p1 = 31u - __builtin_clz(m);
+  return p0 | (p1 << 2);
+}
+
+// ------------------------------------------------------------------------------------------------------------ prune
+__global__ void __launch_bounds__(256) prune_f32_kernel(const float4* __restrict__ in, float4* __restrict__ out,
+                                                        uint8_t* __restrict__ mask, int64_t groups) {
+  const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= groups) return;
+  const float4 w = in[g];
+  const unsigned m = keep_mask_of_4(__float_as_uint(w.x) & 0x7FFFFFFFu, __float_as_uint(w.y) & 0x7FFFFFFFu,
+                                    __float_as_uint(w.z) & 0x7FFFFFFFu, __float_as_uint(w.w) & 0x7FFFFFFFu);
+  float4 o;
+  o.x = (m & 1u) ? w.x : 0.0f;
+  o.y = (m & 2u) ? w.y : 0.0f;
+  o.z = (m & 4u) ? w.z : 0.0f;
+  o.w = (m & 8u) ? w.w : 0.0f;
+  out[g] = o;
+  if (mask) mask[g] = (uint8_t)m;
+}
+
+__global__ void __launch_bounds__(256) prune_f16_kernel(const uint2* __restrict__ in, uint2* __restrict__ out,
+                                                        uint8_t* __restrict__ mask, int64_t groups) {
+  const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= groups) return;
+  const uint2 w = in[g];
+  const unsigned h0 = w.x & 0xFFFFu, h1 = w.x >> 16, h2 = w.y & 0xFFFFu, h3 = w.y >> 16;
+  const unsigned m = keep_mask_of_4(h0 & 0x7FFFu, h1 & 0x7FFFu, h2 & 0x7FFFu, h3 & 0x7FFFu);
+  uint2 o;
+  o.x = ((m & 1u) ? h0 : 0u) | (((m & 2u) ? h1 : 0u) << 16);
+  o.y = ((m & 4u) ? h2 : 0u) | (((m & 8u) ? h3 : 0u) << 16);
+  out[g] = o;
+  if (mask) mask[g] = (uint8_t)m;
+}
+
+gpusq_status launch_prune(const void* Win, void* Wout, uint8_t* mask, gpusq_dtype dt, int64_t N, int64_t K, hipStream_t s) {
+  const int64_t groups = N * K / 4;
+  const unsigned blocks = (unsigned)ceil_div(groups, 256);
+  if (dt == GPUSQ_F32)
+    prune_f32_kernel<<<blocks, 256, 0, s>>>((const float4*)Win, (float4*)Wout, mask, groups);
+  else
+    prune_f16_kernel<<<blocks, 256, 0, s>>>((const uint2*)Win, (uint2*)Wout, mask, groups);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------------------ quantise
+__device__ __forceinline__ float load_as_f32(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float load_as_f32(const _Float16* p, int64_t i) { return (float)p[i]; }
+
+// q = clamp(rint(x / s)): IEEE fp32 division (not a reciprocal multiply) and round-half-even, so that the integer
+// code is decided exactly as a plain CPU evaluation of the same formula decides it.
+__device__ __forceinline__ int quantize_code(float x, float s) {
+  float r = rintf(__fdiv_rn(x, s));
+  r = fminf(fmaxf(r, -127.0f), 127.0f);  // NaN -> -127 -> handled below
+  return (x != x) ? 0 : (int)r;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// One wavefront per row (= per output channel), 4 rows per workgroup.
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_rows_kernel(const T* __restrict__ X, int8_t* __restrict__ Q,
+                                                            float* __restrict__ scale, int scale_is_input,
+                                                            int64_t rows, int64_t cols) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* x = X + row * cols;
+  float s;
+  if (scale_is_input) {
+    s = scale[row];
+  } else {
+    float amax = 0.0f;
+    for (int64_t c = lane; c < cols; c += 64) amax = fmaxf(amax, fabsf(load_as_f32(x, c)));
+    amax = wave_max(amax);
+    s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
+    if (lane == 0) scale[row] = s;
+  }
+  int8_t* q = Q + row * cols;
+  if ((cols & 3) == 0) {
+    for (int64_t c = (int64_t)lane * 4; c < cols; c += 256) {
+      const int a = quantize_code(load_as_f32(x, c), s), b = quantize_code(load_as_f32(x, c + 1), s);
+      const int cc = quantize_code(load_as_f32(x, c + 2), s), d = quantize_code(load_as_f32(x, c + 3), s);
+      *(uint32_t*)(q + c) = (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(cc & 0xFF) << 16) |
+                            ((uint32_t)(d & 0xFF) << 24);
+    }
+  } else {
+    for (int64_t c = lane; c < cols; c += 64) q[c] = (int8_t)quantize_code(load_as_f32(x, c), s);
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t v) { *p = v; }
+
+// per-tensor max |x|: non-negative floats order like their bit patterns, so the reduction ends in an integer atomic max
+template <typename T>
+__global__ void __launch_bounds__(256) tensor_amax_kernel(const T* __restrict__ X, int64_t n, uint32_t* __restrict__ amax_bits) {
+  float amax = 0.0f;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) amax = fmaxf(amax, fabsf(load_as_f32(X, i)));
+  amax = wave_max(amax);
+  __shared__ float part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = amax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    amax = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+    atomicMax(amax_bits, __float_as_uint(amax));
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_tensor_kernel(const T* __restrict__ X, int8_t* __restrict__ Q,
+                                                              float* __restrict__ scale, const uint32_t* __restrict__ amax_bits,
+                                                              int64_t n) {
+  float s;
+  if (amax_bits) {
+    const float amax = __uint_as_float(*amax_bits);
+    s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
+    if (blockIdx.x == 0 && threadIdx.x == 0) scale[0] = s;
+  } else {
+    s = scale[0];
+  }
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 3 < n) {
+      const int a = quantize_code(load_as_f32(X, i), s), b = quantize_code(load_as_f32(X, i + 1), s);
+      const int c = quantize_code(load_as_f32(X, i + 2), s), d = quantize_code(load_as_f32(X, i + 3), s);
+      *(uint32_t*)(Q + i) = (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) |
+                            ((uint32_t)(d & 0xFF) << 24);
+    } else {
+      for (int64_t j = i; j < n; ++j) Q[j] = (int8_t)quantize_code(load_as_f32(X, j), s);
+    }
+  }
+}
+
+template <typename T>
+static gpusq_status quantize_typed(const T* X, int8_t* Xq, float* scale, int mode, int scale_is_input, int64_t rows,
+                                   int64_t cols, void* workspace, hipStream_t s) {
+  if (mode == GPUSQ_PER_ROW) {
+    quantize_rows_kernel<T><<<(unsigned)ceil_div(rows, 4), 256, 0, s>>>(X, Xq, scale, scale_is_input, rows, cols);
+    return check_launch();
+  }
+  const int64_t n = rows * cols;
+  const unsigned blocks = (unsigned)(ceil_div(n, 256 * 16) < 4096 ? ceil_div(n, 256 * 16) : 4096);
+  uint32_t* amax_bits = nullptr;
+  if (!scale_is_input) {
+    amax_bits = (uint32_t*)workspace;
+    fill_u32_kernel<<<1, 1, 0, s>>>(amax_bits, 0u);
+    tensor_amax_kernel<T><<<blocks, 256, 0, s>>>(X, n, amax_bits);
+  }
+  quantize_tensor_kernel<T><<<blocks, 256, 0, s>>>(X, Xq, scale, amax_bits, n);
+  return check_launch();
+}
+
+gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
+                             int64_t rows, int64_t cols, void* workspace, hipStream_t s) {
+  if (dt == GPUSQ_F32) return quantize_typed<float>((const float*)X, Xq, scale, mode, scale_is_input, rows, cols, workspace, s);
+  return quantize_typed<_Float16>((const _Float16*)X, Xq, scale, mode, scale_is_input, rows, cols, workspace, s);
+}
+
+// ------------------------------------------------------------------------------------------------------------ compress
+// One lane per metadata byte = per pair of groups (the last byte of a row holds one group when K/4 is odd).
+template <typename T>
+__device__ __forceinline__ unsigned magnitude_key(T v);
+template <>
+__device__ __forceinline__ unsigned magnitude_key<uint16_t>(uint16_t v) { return v & 0x7FFFu; }
+template <>
+__device__ __forceinline__ unsigned magnitude_key<int8_t>(int8_t v) { return (unsigned)(v < 0 ? -(int)v : (int)v); }
+
+template <typename T>
+__global__ void __launch_bounds__(256) compress_kernel(const T* __restrict__ W, T* __restrict__ values,
+                                                       uint8_t* __restrict__ meta, int32_t* __restrict__ violations,
+                                                       int64_t N, int64_t K) {
+  const int64_t groups_per_row = K / 4;
+  const int64_t mrb = (groups_per_row + 1) / 2;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int bad = 0;
+  if (id < N * mrb) {
+    const int64_t n = id / mrb, b = id % mrb;
+    unsigned byte = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int64_t g = 2 * b + h;
+      if (g < groups_per_row) {
+        const T* w = W + n * K + 4 * g;
+        const T w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
+        const unsigned k0 = magnitude_key<T>(w0), k1 = magnitude_key<T>(w1), k2 = magnitude_key<T>(w2), k3 = magnitude_key<T>(w3);
+        const unsigned m = keep_mask_of_4(k0, k1, k2, k3);
+        const unsigned nib = nibble_of_mask(m);
+        const unsigned p0 = nib & 3u, p1 = nib >> 2;
+        const T v0 = p0 == 0 ? w0 : (p0 == 1 ? w1 : w2);
+        const T v1 = p1 == 1 ? w1 : (p1 == 2 ? w2 : w3);
+        values[n * (K / 2) + 2 * g] = v0;
+        values[n * (K / 2) + 2 * g + 1] = v1;
+        byte |= nib << (4 * h);
+        bad += (int)(((m & 1u) == 0 && k0 != 0) || ((m & 2u) == 0 && k1 != 0) || ((m & 4u) == 0 && k2 != 0) ||
+                     ((m & 8u) == 0 && k3 != 0));
+      }
+    }
+    meta[n * mrb + b] = (uint8_t)byte;
+  }
+  if (violations) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) bad += __shfl_xor(bad, o, 64);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(violations, bad);
+  }
+}
+
+gpusq_status launch_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,
+                             int64_t N, int64_t K, hipStream_t s) {
+  const int64_t mrb = (K / 4 + 1) / 2;
+  const unsigned blocks = (unsigned)ceil_div(N * mrb, 256);
+  if (violations) fill_u32_kernel<<<1, 1, 0, s>>>((uint32_t*)violations, 0u);
+  if (dt == GPUSQ_F16)
+    compress_kernel<uint16_t><<<blocks, 256, 0, s>>>((const uint16_t*)W, (uint16_t*)values, meta, violations, N, K);
+  else
+    compress_kernel<int8_t><<<blocks, 256, 0, s>>>((const int8_t*)W, (int8_t*)values, meta, violations, N, K);
+  return check_launch();
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) decompress_kernel(const T* __restrict__ values, const uint8_t* __restrict__ meta,
+                                                         T* __restrict__ W, int64_t N, int64_t K) {
+  const int64_t groups_per_row = K / 4;
+  const int64_t mrb = (groups_per_row + 1) / 2;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= N * mrb) return;
+  const int64_t n = id / mrb, b = id % mrb;
+  const unsigned byte = meta[n * mrb + b];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int64_t g = 2 * b + h;
+    if (g < groups_per_row) {
+      const unsigned nib = (byte >> (4 * h)) & 0xFu;
+      const unsigned p0 = nib & 3u, p1 = nib >> 2;
+      const T v0 = values[n * (K / 2) + 2 * g], v1 = values[n * (K / 2) + 2 * g + 1];
+      T* w = W + n * K + 4 * g;
+#pragma unroll
+      for (unsigned i = 0; i < 4; ++i) w[i] = (i == p0) ? v0 : ((i == p1) ? v1 : (T)0);
+    }
+  }
+}
+
+gpusq_status launch_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt, int64_t N, int64_t K,
+                               hipStream_t s) {
+  const int64_t mrb = (K / 4 + 1) / 2;
+  const unsigned blocks = (unsigned)ceil_div(N * mrb, 256);
+  if (dt == GPUSQ_F16)
+    decompress_kernel<uint16_t><<<blocks, 256, 0, s>>>((const uint16_t*)values, meta, (uint16_t*)W, N, K);
+  else
+    decompress_kernel<int8_t><<<blocks, 256, 0, s>>>((const int8_t*)values, meta, (int8_t*)W, N, K);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------------------ pack
+// Packed layout (bytes): fragment f = ((blk * ksteps) + ks) * 4 + t  at  f * frag_bytes; inside a fragment the 64
+// lanes' 16 value bytes come first (lane-major), then the lanes' index words (4 bytes for int8, 2 for fp16).
+// Lane l of a fragment serves row r = l % 16 and the dense K range [ks*E + (l/16)*E/4, +E/4) with E = elements per
+// step; the sparse matrix instruction wants, per lane, the kept values of that range in order (16 bytes) and their
+// 2-bit positions in order starting at bit 0 of the index register.  Both are contiguous byte runs of the canonical
+// arrays: values[n][k0/2 .. k0/2 + kept) and meta[n][k0/8 ..).
+template <bool IS_I8>
+__global__ void __launch_bounds__(256) pack_kernel(const uint8_t* __restrict__ values, const uint8_t* __restrict__ meta,
+                                                   uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps,
+                                                   int64_t total_lanes) {
+  constexpr int E = step_elems(IS_I8);       // dense elements per step
+  constexpr int ES = IS_I8 ? 1 : 2;          // element size
+  constexpr int KL = E / 4;                  // dense elements per lane
+  constexpr int IB = IS_I8 ? 4 : 2;          // index bytes per lane
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= total_lanes) return;
+  const int lane = (int)(id & 63);
+  const int64_t f = id >> 6;
+  const int t = (int)(f & 3);
+  const int64_t ks = (f >> 2) % ksteps, blk = (f >> 2) / ksteps;
+  const int64_t n = blk * kRowBlock + packed_row_to_channel(t, lane & 15);
+  const int64_t k0 = ks * E + (int64_t)(lane >> 4) * KL;  // first dense element of this lane
+  const int64_t mrb = (K / 4 + 1) / 2;
+  uint8_t v[16];
+  uint8_t ix[IB];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int64_t byte = (k0 / 2) * ES + i;  // byte offset inside the row of kept values
+    v[i] = (n < N && byte < (K / 2) * ES) ? values[n * (K / 2) * ES + byte] : (uint8_t)0;
+  }
+#pragma unroll
+  for (int i = 0; i < IB; ++i) {
+    const int64_t byte = k0 / 8 + i;
+    // padding (rows >= N, K beyond the row end) carries zero values; its positions are irrelevant
+    ix[i] = (n < N && byte < mrb) ? meta[n * mrb + byte] : (uint8_t)0;
+  }
+  uint8_t* frag = packed + f * frag_bytes(IS_I8);
+  uint4 vv;
+  vv.x = v[0] | (v[1] << 8) | (v[2] << 16) | ((uint32_t)v[3] << 24);
+  vv.y = v[4] | (v[5] << 8) | (v[6] << 16) | ((uint32_t)v[7] << 24);
+  vv.z = v[8] | (v[9] << 8) | (v[10] << 16) | ((uint32_t)v[11] << 24);
+  vv.w = v[12] | (v[13] << 8) | (v[14] << 16) | ((uint32_t)v[15] << 24);
+  *(uint4*)(frag + lane * 16) = vv;
+  if constexpr (IS_I8)
+    *(uint32_t*)(frag + kFragValueBytes + lane * 4) = ix[0] | (ix[1] << 8) | (ix[2] << 16) | ((uint32_t)ix[3] << 24);
+  else
+    *(uint16_t*)(frag + kFragValueBytes + lane * 2) = (uint16_t)(ix[0] | (ix[1] << 8));
+}
+
+gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,
+                         hipStream_t s) {
+  const bool is_i8 = dt == GPUSQ_I8;
+  const int64_t ksteps = ceil_div(K, step_elems(is_i8));
+  const int64_t frags = ceil_div(N, kRowBlock) * ksteps * 4;
+  const int64_t total_lanes = frags * 64;
+  const unsigned blocks = (unsigned)ceil_div(total_lanes, 256);
+  if (is_i8)
+    pack_kernel<true><<<blocks, 256, 0, s>>>((const uint8_t*)values, meta, (uint8_t*)packed, N, K, ksteps, total_lanes);
+  else
+    pack_kernel<false><<<blocks, 256, 0, s>>>((const uint8_t*)values, meta, (uint8_t*)packed, N, K, ksteps, total_lanes);
+  return check_launch();
+}
+
+}  // namespace gpusq

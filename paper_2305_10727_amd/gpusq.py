@@ -1,0 +1,197 @@
+"""Thin ctypes binding over libgpusq.so (include/gpusq.h).  Argument marshalling only: every step of the path runs
+in the library's HIP kernels.  PyTorch supplies device memory (`torch.empty`) and the current HIP stream.
+
+There is no fallback: if the library has not been built, or no GPU tensor is passed, the calls raise.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgpusq.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED, ERR_HIP = range(6)
+F32, F16, I8, I32 = range(4)
+EPI_NONE, EPI_BIAS, EPI_GELU = 0, 1, 2
+PER_ROW, PER_TENSOR = 0, 1
+
+_TORCH_DT = {torch.float32: F32, torch.float16: F16, torch.int8: I8, torch.int32: I32}
+_DT_TORCH = {v: k for k, v in _TORCH_DT.items()}
+
+EXPORTS = [
+    "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_quantize_workspace_bytes",
+    "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_spgemm_fp16",
+    "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
+]
+
+
+class GpusqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().gpusq_status_string(status).decode()
+        if status == ERR_HIP:
+            msg += " [hip error %d]" % lib().gpusq_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+_lib = None
+
+
+def lib():
+    """Loads libgpusq.so (built by `python -m paper_2305_10727_amd.build`); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libgpusq.so is not built: run `python -m paper_2305_10727_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.gpusq_status_string.restype = ctypes.c_char_p
+        L.gpusq_status_string.argtypes = [ci]
+        L.gpusq_last_hip_error.restype = ci
+        L.gpusq_version.restype = ci
+        L.gpusq_prune_2to4.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_quantize_workspace_bytes.restype = ctypes.c_size_t
+        L.gpusq_quantize_workspace_bytes.argtypes = [ci, i64, i64]
+        L.gpusq_quantize_int8.argtypes = [vp, ci, vp, vp, ci, ci, i64, i64, vp, vp]
+        L.gpusq_compress.argtypes = [vp, vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_decompress.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_packed_bytes.restype = ctypes.c_size_t
+        L.gpusq_packed_bytes.argtypes = [ci, i64, i64]
+        L.gpusq_pack.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_spgemm_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
+        L.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+        L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
+        L.gpusq_gemm_int8_dense.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+        for name in ("gpusq_prune_2to4", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
+                     "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("gpusq works on device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("gpusq needs contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != OK:
+        raise GpusqError(status, where)
+
+
+def meta_row_bytes(K):
+    return (K // 4 + 1) // 2
+
+
+def version():
+    return lib().gpusq_version()
+
+
+def prune_2to4(W, out=None, want_mask=False):
+    """gpusq_prune_2to4: W [N,K] fp32/fp16 -> pruned W (and the [N,K/4] keep-mask bytes if asked)."""
+    N, K = W.shape
+    out = torch.empty_like(W) if out is None else out
+    mask = torch.empty((N, max(K // 4, 1)), dtype=torch.uint8, device=W.device) if want_mask else None
+    _check(lib().gpusq_prune_2to4(_ptr(W), _ptr(out), _ptr(mask), _TORCH_DT[W.dtype], N, K, _stream()), "gpusq_prune_2to4")
+    return (out, mask) if want_mask else out
+
+
+def quantize_int8(X, mode, scale=None):
+    """gpusq_quantize_int8: returns (Xq int8, scale tensor).  mode PER_ROW: scale [rows]; PER_TENSOR: scale [1].
+    Pass `scale` (device fp32 tensor) to quantise with given scales."""
+    rows, cols = X.shape
+    Xq = torch.empty((rows, cols), dtype=torch.int8, device=X.device)
+    given = scale is not None
+    if not given:
+        scale = torch.empty(rows if mode == PER_ROW else 1, dtype=torch.float32, device=X.device)
+    ws_bytes = lib().gpusq_quantize_workspace_bytes(mode, rows, cols)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=X.device)
+    _check(lib().gpusq_quantize_int8(_ptr(X), _TORCH_DT[X.dtype], _ptr(Xq), _ptr(scale), mode, int(given), rows, cols,
+                                     _ptr(ws), _stream()), "gpusq_quantize_int8")
+    return Xq, scale
+
+
+def compress(W, want_violations=False):
+    """gpusq_compress: W [N,K] fp16/int8 -> (values [N,K/2], meta [N,ceil(K/8)] uint8[, violations int32[1]])."""
+    N, K = W.shape
+    values = torch.empty((N, max(K // 2, 1)), dtype=W.dtype, device=W.device)
+    meta = torch.empty((N, max(meta_row_bytes(K), 1)), dtype=torch.uint8, device=W.device)
+    viol = torch.empty(1, dtype=torch.int32, device=W.device) if want_violations else None
+    _check(lib().gpusq_compress(_ptr(W), _ptr(values), _ptr(meta), _ptr(viol), _TORCH_DT[W.dtype], N, K, _stream()),
+           "gpusq_compress")
+    return (values, meta, viol) if want_violations else (values, meta)
+
+
+def decompress(values, meta, K):
+    N = values.shape[0]
+    W = torch.empty((N, K), dtype=values.dtype, device=values.device)
+    _check(lib().gpusq_decompress(_ptr(values), _ptr(meta), _ptr(W), _TORCH_DT[values.dtype], N, K, _stream()),
+           "gpusq_decompress")
+    return W
+
+
+def packed_bytes(dtype, N, K):
+    return lib().gpusq_packed_bytes(_TORCH_DT[dtype], N, K)
+
+
+def pack(values, meta, K):
+    """gpusq_pack: canonical (values, meta) -> opaque kernel-native buffer (uint8 tensor)."""
+    N = values.shape[0]
+    nbytes = packed_bytes(values.dtype, N, K)
+    if nbytes == 0:
+        raise GpusqError(ERR_SHAPE, "gpusq_packed_bytes")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=values.device)
+    _check(lib().gpusq_pack(_ptr(values), _ptr(meta), _ptr(packed), _TORCH_DT[values.dtype], N, K, _stream()), "gpusq_pack")
+    return packed
+
+
+def _epi(bias, gelu):
+    return (EPI_BIAS if bias is not None else 0) | (EPI_GELU if gelu else 0)
+
+
+def spgemm_fp16(X, Wpacked, N, bias=None, gelu=False, out=None):
+    M, K = X.shape
+    Y = torch.empty((M, N), dtype=torch.float16, device=X.device) if out is None else out
+    _check(lib().gpusq_spgemm_fp16(_ptr(X), _ptr(Wpacked), _ptr(bias), _ptr(Y), M, N, K, _epi(bias, gelu), _stream()),
+           "gpusq_spgemm_fp16")
+    return Y
+
+
+def spgemm_int8(Xq, Wpacked, N, act_scale=None, w_scale=None, bias=None, gelu=False, out_dtype=torch.float16,
+                out_scale=None, out=None):
+    M, K = Xq.shape
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
+    _check(lib().gpusq_spgemm_int8(_ptr(Xq), _ptr(Wpacked), _ptr(act_scale), _ptr(w_scale), _ptr(bias), _ptr(Y),
+                                   _TORCH_DT[out_dtype], _ptr(out_scale), M, N, K, _epi(bias, gelu), _stream()),
+           "gpusq_spgemm_int8")
+    return Y
+
+
+def gemm_fp16_dense(X, W, bias=None, gelu=False, out=None):
+    M, K = X.shape
+    N = W.shape[0]
+    Y = torch.empty((M, N), dtype=torch.float16, device=X.device) if out is None else out
+    _check(lib().gpusq_gemm_fp16_dense(_ptr(X), _ptr(W), _ptr(bias), _ptr(Y), M, N, K, _epi(bias, gelu), _stream()),
+           "gpusq_gemm_fp16_dense")
+    return Y
+
+
+def gemm_int8_dense(Xq, Wq, act_scale=None, w_scale=None, bias=None, gelu=False, out_dtype=torch.float16, out_scale=None,
+                    out=None):
+    M, K = Xq.shape
+    N = Wq.shape[0]
+    Y = torch.empty((M, N), dtype=out_dtype, device=Xq.device) if out is None else out
+    _check(lib().gpusq_gemm_int8_dense(_ptr(Xq), _ptr(Wq), _ptr(act_scale), _ptr(w_scale), _ptr(bias), _ptr(Y),
+                                       _TORCH_DT[out_dtype], _ptr(out_scale), M, N, K, _epi(bias, gelu), _stream()),
+           "gpusq_gemm_int8_dense")
+    return Y

@@ -1,0 +1,92 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares, and rejects bad
+arguments before touching the GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "gpusq.h")
+LIB = os.path.join(ROOT, "paper_2305_10727_amd", "libgpusq.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2305_10727_amd import build
+        build.build()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gpusq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2305_10727_amd import gpusq
+    assert sorted(gpusq.EXPORTS) == names
+
+
+def test_status_strings_and_version(lib):
+    lib.gpusq_status_string.restype = ctypes.c_char_p
+    seen = {lib.gpusq_status_string(i) for i in range(6)}
+    assert len(seen) == 6 and lib.gpusq_status_string(0) == b"ok"
+    assert lib.gpusq_version() >= 100
+
+
+def test_argument_errors_are_caught_on_the_host(lib):
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
+    good = vp(0x10000)  # never dereferenced: every call below fails validation first
+    odd = vp(0x10008)
+    lib.gpusq_prune_2to4.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+    assert lib.gpusq_prune_2to4(None, good, None, 0, 4, 8, None) == ERR_NULL
+    assert lib.gpusq_prune_2to4(good, good, None, 0, 4, 6, None) == ERR_SHAPE
+    assert lib.gpusq_prune_2to4(good, good, None, 0, 0, 8, None) == ERR_SHAPE
+    assert lib.gpusq_prune_2to4(good, good, None, 2, 4, 8, None) == ERR_UNSUPPORTED
+    assert lib.gpusq_prune_2to4(odd, good, None, 0, 4, 8, None) == ERR_ALIGN
+    lib.gpusq_compress.argtypes = [vp, vp, vp, vp, ci, i64, i64, vp]
+    assert lib.gpusq_compress(good, good, None, None, 1, 4, 8, None) == ERR_NULL
+    assert lib.gpusq_compress(good, good, good, None, 0, 4, 8, None) == ERR_UNSUPPORTED
+    assert lib.gpusq_compress(good, good, good, None, 1, 4, 10, None) == ERR_SHAPE
+    lib.gpusq_quantize_int8.argtypes = [vp, ci, vp, vp, ci, ci, i64, i64, vp, vp]
+    assert lib.gpusq_quantize_int8(good, 0, good, None, 0, 0, 4, 8, None, None) == ERR_NULL
+    assert lib.gpusq_quantize_int8(good, 0, good, good, 1, 0, 4, 8, None, None) == ERR_NULL  # per-tensor needs workspace
+    assert lib.gpusq_quantize_int8(good, 0, good, good, 7, 0, 4, 8, good, None) == ERR_UNSUPPORTED
+    assert lib.gpusq_quantize_int8(good, 0, good, good, 0, 0, -1, 8, good, None) == ERR_SHAPE
+    lib.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+    assert lib.gpusq_spgemm_int8(good, good, None, None, None, good, 3, None, 8, 8, 24, 0, None) == ERR_UNSUPPORTED  # K % 16
+    assert lib.gpusq_spgemm_int8(good, good, None, None, None, good, 3, None, 8, 6, 32, 0, None) == ERR_UNSUPPORTED  # N % 4
+    assert lib.gpusq_spgemm_int8(good, good, None, None, None, good, 3, None, 8, 8, 30, 0, None) == ERR_SHAPE
+    assert lib.gpusq_spgemm_int8(good, good, None, None, None, good, 1, None, 8, 8, 32, 0, None) == ERR_NULL  # scales
+    assert lib.gpusq_spgemm_int8(good, good, good, good, None, good, 1, None, 8, 8, 32, 1, None) == ERR_NULL  # bias flag
+    assert lib.gpusq_spgemm_int8(good, good, good, good, None, good, 2, None, 8, 8, 32, 0, None) == ERR_NULL  # out_scale
+    assert lib.gpusq_spgemm_int8(good, good, good, good, None, good, 1, None, 8, 8, 32, 8, None) == ERR_UNSUPPORTED
+    lib.gpusq_spgemm_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
+    assert lib.gpusq_spgemm_fp16(good, None, None, good, 8, 8, 32, 0, None) == ERR_NULL
+    assert lib.gpusq_spgemm_fp16(good, good, None, odd, 8, 8, 32, 0, None) == ERR_ALIGN
+    assert lib.gpusq_spgemm_fp16(good, good, None, good, 0, 8, 32, 0, None) == ERR_SHAPE
+    lib.gpusq_packed_bytes.restype = ctypes.c_size_t
+    lib.gpusq_packed_bytes.argtypes = [ci, i64, i64]
+    # 64-row blocks x 128-byte K steps x 4 fragments of (1024 value bytes + index bytes)
+    assert lib.gpusq_packed_bytes(2, 768, 192) == 12 * 2 * 4 * 1280
+    assert lib.gpusq_packed_bytes(1, 768, 192) == 12 * 3 * 4 * 1152
+    assert lib.gpusq_packed_bytes(2, 100, 144) == 2 * 2 * 4 * 1280
+    assert lib.gpusq_packed_bytes(0, 768, 192) == 0 and lib.gpusq_packed_bytes(2, 768, 190) == 0
+    lib.gpusq_quantize_workspace_bytes.restype = ctypes.c_size_t
+    lib.gpusq_quantize_workspace_bytes.argtypes = [ci, i64, i64]
+    assert lib.gpusq_quantize_workspace_bytes(0, 10, 10) == 0 and lib.gpusq_quantize_workspace_bytes(1, 10, 10) >= 4
+
+
+def test_binding_refuses_host_tensors():
+    torch = pytest.importorskip("torch")
+    from paper_2305_10727_amd import gpusq
+    with pytest.raises(ValueError):
+        gpusq.prune_2to4(torch.zeros(4, 8))

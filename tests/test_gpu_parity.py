@@ -1,0 +1,347 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element, on the same seeded inputs.
+
+Bars: bit-exact for masks, metadata, kept values, int8 codes, scales and int32 accumulators; fp16 outputs of the INT8
+path without GELU bit-exact against the oracle's fp32 operation sequence and within 1 fp16 ulp of its fp64 result; GELU
+outputs within 1 fp16 ulp; FP16-path outputs within max relative error 1e-2 (relative to max(|ref|, 1e-3 max|ref|))
+of the fp64-accumulated reference, and exact on small-integer inputs where every partial sum is exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2305_10727_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2305_10727_amd import gpusq
+    gpusq.lib()  # must be built; no fallback
+    return gpusq
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def ulp_diff_f16(a, b):
+    """distance in fp16 units-in-the-last-place between two float16 arrays (monotone integer mapping)"""
+    def key(x):
+        i = x.view(np.int16).astype(np.int32)
+        return np.where(i < 0, -(i & 0x7FFF), i)
+    return np.abs(key(np.ascontiguousarray(a)) - key(np.ascontiguousarray(b)))
+
+
+def rel_err(y, ref):
+    ref = ref.astype(np.float64)
+    floor = 1e-3 * np.abs(ref).max()
+    return (np.abs(y.astype(np.float64) - ref) / np.maximum(np.abs(ref), floor)).max()
+
+
+# ------------------------------------------------------------------------------------------------ a1 prune
+def prune_inputs(dtype):
+    rng = np.random.default_rng(10)
+    tiny = np.finfo(dtype).tiny
+    sub = np.finfo(dtype).smallest_subnormal
+    adversarial = np.array([[0, 0, 0, 0, -0.0, 0.0, -0.0, 0.0, 1, 1, 1, 1, -1, 1, -1, 1, 1, 2, 2, 1, 3, 3, 1, 3, sub, 0, 0, sub,
+                             sub, 2 * sub, tiny, -tiny, np.inf, 1, -np.inf, 2, 0, 0, 0, 5]], dtype=dtype)
+    return [
+        rng.standard_normal((1, 4)).astype(dtype),
+        rng.standard_normal((3, 8)).astype(dtype),
+        adversarial,
+        rng.integers(-2, 3, size=(33, 260)).astype(dtype),  # ties everywhere, ragged sizes
+        synth.weights(768, 192, seed=0).astype(dtype),
+        (synth.weights(257, 1028, seed=1) * 50).astype(dtype),
+    ]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_prune_bit_exact(g, dtype):
+    for W in prune_inputs(dtype):
+        exp, emask = oracle.prune_2to4(W)
+        out, mask = g.prune_2to4(dev(W), want_mask=True)
+        bits = np.uint32 if dtype == np.float32 else np.uint16
+        assert np.array_equal(host(out).view(bits), exp.view(bits))
+        assert np.array_equal(host(mask)[:, :W.shape[1] // 4], emask)
+    # in place, no mask
+    W = synth.weights(64, 64, seed=2).astype(dtype)
+    t = dev(W)
+    g.prune_2to4(t, out=t)
+    assert np.array_equal(host(t), oracle.prune_2to4(W)[0])
+
+
+# ------------------------------------------------------------------------------------------------ a2 / a4 quantise
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_quantize_rows_bit_exact(g, dtype):
+    for (N, K, seed) in [(1, 4, 0), (5, 7, 1), (768, 192, 0), (130, 1030, 3)]:
+        W = (synth.weights(N, K, seed=seed) * (1.0 if dtype == np.float32 else 20.0)).astype(dtype)
+        if N > 4:
+            W[3] = 0  # an all-zero channel: scale 1
+        eq, es = oracle.quantize_rows_int8(W.astype(np.float32))
+        q, s = g.quantize_int8(dev(W), g.PER_ROW)
+        assert np.array_equal(host(s).view(np.uint32), es.view(np.uint32))
+        assert np.array_equal(host(q), eq)
+        # caller-supplied (static) scales, including ones that clamp
+        st = (es * np.float32(0.37)).astype(np.float32)
+        eq2, _ = oracle.quantize_rows_int8(W.astype(np.float32), scale=st)
+        q2, _ = g.quantize_int8(dev(W), g.PER_ROW, scale=dev(st))
+        assert np.array_equal(host(q2), eq2)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_quantize_tensor_bit_exact(g, dtype):
+    cases = [synth.activations(197, 192, "normal_clip4", seed=0), synth.activations(1, 5, seed=1),
+             synth.activations(513, 770, "gelu_normal", seed=2), np.zeros((4, 8), np.float32),
+             np.array([[0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, 127.0]], np.float32)]
+    for X in cases:
+        X = X.astype(dtype)
+        eq, es = oracle.quantize_tensor_int8(X.astype(np.float32))
+        q, s = g.quantize_int8(dev(X), g.PER_TENSOR)
+        assert host(s)[0] == np.float32(es)
+        assert np.array_equal(host(q), eq)
+        eq2, _ = oracle.quantize_tensor_int8(X.astype(np.float32), scale=0.031)
+        q2, _ = g.quantize_int8(dev(X), g.PER_TENSOR, scale=dev(np.array([0.031], np.float32)))
+        assert np.array_equal(host(q2), eq2)
+
+
+# ------------------------------------------------------------------------------------------------ a3 compress
+@pytest.mark.parametrize("dtype", [np.float16, np.int8])
+def test_compress_decompress_bit_exact(g, dtype):
+    rng = np.random.default_rng(3)
+    for (N, K) in [(1, 4), (2, 12), (7, 72), (64, 192), (100, 1028), (768, 768)]:
+        W32 = rng.standard_normal((N, K)).astype(np.float32)
+        P, _ = oracle.prune_2to4(W32)
+        if dtype == np.int8:
+            pruned = np.clip(np.rint(P * 40), -127, 127).astype(np.int8)
+            dense = rng.integers(-3, 4, size=(N, K)).astype(np.int8)
+        else:
+            pruned = P.astype(np.float16)
+            dense = rng.integers(-3, 4, size=(N, K)).astype(np.float16)
+        for W in (pruned, dense):
+            ev, em, eviol = oracle.compress(W)
+            v, m, viol = g.compress(dev(W), want_violations=True)
+            assert np.array_equal(host(v).view(np.uint8), ev.view(np.uint8))
+            assert np.array_equal(host(m), em)
+            assert int(host(viol)[0]) == eviol
+            back = g.decompress(v, m, K)
+            assert np.array_equal(host(back).view(np.uint8), oracle.decompress(ev, em, K).view(np.uint8))
+        v, m = g.compress(dev(pruned))
+        assert np.array_equal(host(g.decompress(v, m, K)).view(np.uint8), pruned.view(np.uint8))  # round trip = identity
+
+
+# ------------------------------------------------------------------------------------------------ GEMM helpers
+class Int8Problem:
+    def __init__(self, M, K, N, seed, dist="normal_clip4", rows=None):
+        self.M, self.K, self.N = M, K, N
+        X = synth.activations(M, K, dist, seed=seed, ids=(7,))
+        W = synth.weights(N, K, seed=seed, ids=(7,))
+        self.bias = synth.bias(N, seed=seed, ids=(7,))
+        self.X32, self.W32 = X, W
+        # oracle side
+        P, _ = oracle.prune_2to4(W)
+        self.Wq, self.s_w = oracle.quantize_rows_int8(P)
+        self.Xq, self.s_a = oracle.quantize_tensor_int8(X)
+        self.vals, self.meta, viol = oracle.compress(self.Wq)
+        assert viol == 0
+
+
+def gpu_prepare_int8(g, W32, X32):
+    """the GPU path from fp32 tensors to packed weights + quantised activations, through the C ABI only"""
+    Wp = g.prune_2to4(dev(W32))
+    Wq, s_w = g.quantize_int8(Wp, g.PER_ROW)
+    vals, meta = g.compress(Wq)
+    packed = g.pack(vals, meta, W32.shape[1])
+    Xq, s_a = g.quantize_int8(dev(X32), g.PER_TENSOR)
+    return dict(Wq=Wq, s_w=s_w, vals=vals, meta=meta, packed=packed, Xq=Xq, s_a=s_a)
+
+
+INT8_SHAPES = [
+    (1, 16, 4, 0), (5, 32, 8, 1), (16, 128, 64, 2), (37, 192, 48, 3), (197, 192, 768, 0), (33, 144, 100, 4),
+    (130, 256, 132, 5), (64, 1024, 64, 6), (600, 384, 512, 7), (1000, 272, 328, 8),
+]
+
+
+@pytest.mark.parametrize("M,K,N,seed", INT8_SHAPES)
+def test_spgemm_int8_accumulators_bit_exact(g, M, K, N, seed):
+    p = Int8Problem(M, K, N, seed)
+    d = gpu_prepare_int8(g, p.W32, p.X32)
+    # the preparation chain itself is bit-exact
+    assert np.array_equal(host(d["Wq"]), p.Wq) and np.array_equal(host(d["Xq"]), p.Xq)
+    assert np.array_equal(host(d["s_w"]), p.s_w) and host(d["s_a"])[0] == np.float32(p.s_a)
+    assert np.array_equal(host(d["vals"]), p.vals) and np.array_equal(host(d["meta"]), p.meta)
+    exp = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
+    acc = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+    assert np.array_equal(host(acc), exp)
+    accd = g.gemm_int8_dense(d["Xq"], d["Wq"], out_dtype=torch.int32)
+    assert np.array_equal(host(accd), exp)
+
+
+@pytest.mark.parametrize("M,K,N,seed", [(197, 192, 768, 0), (37, 192, 48, 3), (130, 256, 132, 5), (600, 384, 512, 7)])
+@pytest.mark.parametrize("kernel", ["sparse", "dense"])
+def test_int8_epilogues(g, M, K, N, seed, kernel):
+    p = Int8Problem(M, K, N, seed)
+    d = gpu_prepare_int8(g, p.W32, p.X32)
+    acc = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
+    bias = dev(p.bias)
+
+    def run(**kw):
+        if kernel == "sparse":
+            return g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], **kw)
+        return g.gemm_int8_dense(d["Xq"], d["Wq"], act_scale=d["s_a"], w_scale=d["s_w"], **kw)
+
+    for use_bias in (False, True):
+        b_np, b_t = (p.bias, bias) if use_bias else (None, None)
+        # dequant (+bias): bit-exact against the fp32 operation sequence, within 1 ulp of the fp64 value
+        y = host(run(bias=b_t))
+        o32 = oracle.epilogue_int8_f32(acc, p.s_a, p.s_w, b_np)
+        o64 = oracle.epilogue_int8_f64(acc, p.s_a, p.s_w, b_np)
+        assert np.array_equal(y.view(np.uint16), o32["y16"].view(np.uint16))
+        assert ulp_diff_f16(y, o64["y16"]).max() <= 1
+        assert rel_err(y, o64["ref"]) <= 1e-3
+        # GELU: library erf differs from libm's in the last bits -> 1 fp16 ulp
+        yg = host(run(bias=b_t, gelu=True))
+        g64 = oracle.epilogue_int8_f64(acc, p.s_a, p.s_w, b_np, gelu=True)
+        assert ulp_diff_f16(yg, g64["y16"]).max() <= 1
+        assert rel_err(yg, g64["ref"]) <= 1e-3
+    # int8 output re-quantised with a static scale: the code is decided in fp32 on both sides
+    so = np.float32(np.abs(oracle.epilogue_int8_f64(acc, p.s_a, p.s_w, p.bias)["ref"]).max() / 127.0)
+    q = host(run(bias=bias, out_dtype=torch.int8, out_scale=dev(np.array([so], np.float32))))
+    assert np.array_equal(q, oracle.epilogue_int8_f32(acc, p.s_a, p.s_w, p.bias, out_scale=float(so))["q8"])
+    qg = host(run(bias=bias, gelu=True, out_dtype=torch.int8, out_scale=dev(np.array([so / 4], np.float32))))
+    eg = oracle.epilogue_int8_f32(acc, p.s_a, p.s_w, p.bias, gelu=True, out_scale=float(so / 4))["q8"]
+    dq = np.abs(qg.astype(np.int32) - eg.astype(np.int32))
+    assert dq.max() <= 1 and (dq != 0).mean() < 1e-3  # a tie broken by the last bit of erf may move one code
+
+
+FP16_SHAPES = [(1, 16, 4, 0), (16, 64, 64, 1), (37, 192, 48, 2), (197, 192, 768, 0), (33, 144, 100, 3), (130, 256, 132, 4),
+               (600, 384, 512, 5), (64, 2048, 64, 6)]
+
+
+def fp16_problem(M, K, N, seed, integers=False):
+    if integers:
+        X = synth.small_integers((M, K), -4, 4, seed=seed, ids=(9,)).astype(np.float16)
+        W = synth.small_integers((N, K), -4, 4, seed=seed, ids=(10,)).astype(np.float32)
+    else:
+        X = synth.activations(M, K, seed=seed, ids=(9,)).astype(np.float16)
+        W = synth.weights(N, K, seed=seed, ids=(9,))
+    P, _ = oracle.prune_2to4(W)  # the mask is decided in fp32, then the kept weights are rounded to fp16
+    Wh = P.astype(np.float16)
+    vals, meta, viol = oracle.compress(Wh)
+    assert viol == 0
+    return X, W, Wh, vals, meta, synth.bias(N, seed=seed, ids=(9,))
+
+
+@pytest.mark.parametrize("M,K,N,seed", FP16_SHAPES)
+def test_spgemm_fp16(g, M, K, N, seed):
+    X, W, Wh, vals, meta, bias = fp16_problem(M, K, N, seed)
+    Wp = g.prune_2to4(dev(W)).to(torch.float16)  # dtype cast of a tensor: plumbing, not a step of the method
+    v, m = g.compress(Wp)
+    assert np.array_equal(host(v).view(np.uint16), vals.view(np.uint16)) and np.array_equal(host(m), meta)
+    packed = g.pack(v, m, K)
+    _, a64 = oracle.spgemm_fp16(X, vals, meta)
+    for b_np, gelu in ((None, False), (bias, False), (bias, True)):
+        ref = oracle.epilogue_fp16_f64(a64, b_np, gelu)["ref"]
+        y = host(g.spgemm_fp16(dev(X), packed, N, bias=None if b_np is None else dev(b_np), gelu=gelu))
+        assert rel_err(y, ref) <= 1e-2
+        assert rel_err(y, ref) <= 2e-3  # what fp32 accumulation + one fp16 rounding actually gives
+        yd = host(g.gemm_fp16_dense(dev(X), Wp, bias=None if b_np is None else dev(b_np), gelu=gelu))
+        assert rel_err(yd, ref) <= 2e-3
+
+
+@pytest.mark.parametrize("M,K,N,seed", [(37, 192, 48, 2), (130, 256, 132, 4), (600, 384, 512, 5)])
+def test_spgemm_fp16_exact_on_small_integers(g, M, K, N, seed):
+    """|x|,|w| <= 4 and K <= 2048: every partial sum is an integer below 2^24, so any summation order is exact"""
+    X, W, Wh, vals, meta, _ = fp16_problem(M, K, N, seed, integers=True)
+    v, m = g.compress(dev(Wh))
+    packed = g.pack(v, m, K)
+    _, a64 = oracle.spgemm_fp16(X, vals, meta)
+    exp = oracle.epilogue_fp16_f64(a64)["y16"]
+    y = host(g.spgemm_fp16(dev(X), packed, N))
+    assert np.array_equal(y.view(np.uint16), exp.view(np.uint16))
+    yd = host(g.gemm_fp16_dense(dev(X), dev(Wh)))
+    assert np.array_equal(yd.view(np.uint16), exp.view(np.uint16))
+
+
+def test_identity_activations_return_the_weights(g):
+    """X = I: the product is the decompressed weight matrix, transposed (pins metadata + packing end to end)"""
+    K, N = 256, 192
+    W = synth.small_integers((N, K), -9, 9, seed=3).astype(np.float32)
+    P, _ = oracle.prune_2to4(W)
+    Wq = P.astype(np.int8)
+    v, m = g.compress(dev(Wq))
+    packed = g.pack(v, m, K)
+    acc = g.spgemm_int8(dev(np.eye(K, dtype=np.int8)), packed, N, out_dtype=torch.int32)
+    assert np.array_equal(host(acc), Wq.T.astype(np.int32))
+
+
+# ------------------------------------------------------------------------------------------------ full-size checks
+def test_c1_full_size_sampled_rows_and_self_consistency(g):
+    """ViT-Base fc1 at batch 64 (M=12608, K=768, N=3072) in the launch configuration the benchmark times: oracle on
+    sampled rows (first 256, last 256 incl. the ragged tail tile, 512 random), sparse == dense bit-exact on all rows,
+    and run-to-run determinism."""
+    M, K, N = 64 * 197, 768, 3072
+    X = synth.activations(M, K, "normal", seed=0, ids=(1, 0))
+    W = synth.weights(N, K, seed=0, ids=(1, 0))
+    bias = synth.bias(N, seed=0, ids=(1, 0))
+    d = gpu_prepare_int8(g, W, X)
+    acc = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+    acc2 = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+    accd = g.gemm_int8_dense(d["Xq"], d["Wq"], out_dtype=torch.int32)
+    assert torch.equal(acc, acc2) and torch.equal(acc, accd)
+    y = g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), gelu=True)
+    y2 = g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), gelu=True)
+    assert torch.equal(y, y2)
+    rows = np.unique(np.concatenate([np.arange(256), np.arange(M - 256, M), np.random.default_rng(0).integers(0, M, 512)]))
+    # oracle on the same tensors
+    P, _ = oracle.prune_2to4(W)
+    Wq, s_w = oracle.quantize_rows_int8(P)
+    Xq, s_a = oracle.quantize_tensor_int8(X)
+    vals, meta, _ = oracle.compress(Wq)
+    assert np.array_equal(host(d["Xq"]), Xq) and np.array_equal(host(d["Wq"]), Wq)
+    exp = oracle.spgemm_int8(Xq[rows], vals, meta)
+    assert np.array_equal(host(acc)[rows], exp)
+    o = oracle.epilogue_int8_f64(exp, s_a, s_w, bias, gelu=True)
+    assert ulp_diff_f16(host(y)[rows], o["y16"]).max() <= 1
+    # fp16 path on the same shape
+    Xh = X.astype(np.float16)
+    Wp = g.prune_2to4(dev(W)).to(torch.float16)
+    v, m = g.compress(Wp)
+    packed = g.pack(v, m, K)
+    yh = g.spgemm_fp16(dev(Xh), packed, N, bias=dev(bias), gelu=True)
+    yhd = g.gemm_fp16_dense(dev(Xh), Wp, bias=dev(bias), gelu=True)
+    vals16, meta16, _ = oracle.compress(P.astype(np.float16))
+    _, a64 = oracle.spgemm_fp16(Xh[rows], vals16, meta16)
+    ref = oracle.epilogue_fp16_f64(a64, bias, True)["ref"]
+    assert rel_err(host(yh)[rows], ref) <= 2e-3
+    assert rel_err(host(yhd)[rows], ref) <= 2e-3
+
+
+# ------------------------------------------------------------------------------------------------ error paths
+def test_error_statuses(g):
+    W = dev(np.zeros((4, 6), np.float32))
+    with pytest.raises(g.GpusqError) as e:
+        g.prune_2to4(W)
+    assert e.value.status == g.ERR_SHAPE
+    X = dev(np.zeros((4, 24), np.int8))
+    Wq = dev(np.zeros((8, 24), np.int8))
+    v, m = g.compress(Wq)
+    packed = g.pack(v, m, 24)
+    with pytest.raises(g.GpusqError) as e:  # K % 16 != 0 is valid for the method but not for the GEMM kernels
+        g.spgemm_int8(X, packed, 8, out_dtype=torch.int32)
+    assert e.value.status == g.ERR_UNSUPPORTED
+    X = dev(np.zeros((4, 32), np.int8))
+    with pytest.raises(g.GpusqError) as e:  # fp16 output needs the scales
+        g.spgemm_int8(X, packed, 8)
+    assert e.value.status == g.ERR_NULL
+    with pytest.raises(g.GpusqError) as e:  # misaligned pointer
+        g.prune_2to4(dev(np.zeros(20, np.float32))[1:17].view(4, 4))
+    assert e.value.status == g.ERR_ALIGN
