@@ -20,7 +20,7 @@
  *   - Tensors are dense row-major without padding; all pointers must be 16-byte aligned (GPUSQ_ERR_ALIGN).
  *   - K must be a multiple of 4 (a row is made of whole groups of 4; GPUSQ_ERR_SHAPE otherwise).  The GEMM entry
  *     points additionally need K % 16 == 0 and N % 4 == 0 (GPUSQ_ERR_UNSUPPORTED otherwise); M is arbitrary.
- *     Sizes must be positive and M*N, M*K, N*K below 2^31 elements... see each call.
+ *     Sizes must be positive, each dimension below 2^31 and each tensor below 2^40 elements (GPUSQ_ERR_SHAPE).
  *   - Thread safety: calls on distinct streams may run concurrently; the library holds no mutable global state
  *     besides the last HIP error code.
  */
@@ -62,6 +62,11 @@ int gpusq_version(void);
  *   mask_out    : optional [N][K/4] bytes; bit i of a byte is set iff element 4g+i of the group was kept. */
 gpusq_status gpusq_prune_2to4(const void* W_in, void* W_out, uint8_t* mask_out, gpusq_dtype dt,
                               int64_t N, int64_t K, void* stream);
+
+/* ---- FP32 -> FP16 rounding (round-to-nearest-even) of n contiguous elements: the step from the pruned FP32
+ * weights to the "2:4 FP16 sparse" model that the paper's pipeline produces first [Sec. 3.1, last sentence of the
+ * storage-format paragraph].  Also usable for activations. */
+gpusq_status gpusq_cast_f16(const float* in, void* out, int64_t n, void* stream);
 
 /* ---- symmetric INT8 quantisation with a scale factor [Sec. 2.2; Sec. 3.4].  q = clamp(rint(x / s), -127, 127),
  * fp32 division, round-half-even; s = max|x| / 127 over a row (GPUSQ_PER_ROW: per output channel, scale has `rows`

@@ -72,6 +72,13 @@ gpusq_status gpusq_prune_2to4(const void* W_in, void* W_out, uint8_t* mask_out, 
   return launch_prune(W_in, W_out, mask_out, dt, N, K, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_cast_f16(const float* in, void* out, int64_t n, void* stream) {
+  if (!in || !out) return GPUSQ_ERR_NULL;
+  if (n <= 0 || n > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(in) || !aligned16(out)) return GPUSQ_ERR_ALIGN;
+  return launch_cast_f16(in, out, n, (hipStream_t)stream);
+}
+
 size_t gpusq_quantize_workspace_bytes(int mode, int64_t rows, int64_t cols) {
   (void)rows;
   (void)cols;

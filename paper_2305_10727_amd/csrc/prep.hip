@@ -67,6 +67,26 @@ gpusq_status launch_prune(const void* Win, void* Wout, uint8_t* mask, gpusq_dtyp
   return check_launch();
 }
 
+// ------------------------------------------------------------------------------------------------------------ cast
+__global__ void __launch_bounds__(256) cast_f16_kernel(const float* __restrict__ in, _Float16* __restrict__ out, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 3 < n) {
+      const float4 v = *(const float4*)(in + i);
+      typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+      *(h4*)(out + i) = h4{(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
+    } else {
+      for (int64_t j = i; j < n; ++j) out[j] = (_Float16)in[j];
+    }
+  }
+}
+
+gpusq_status launch_cast_f16(const float* in, void* out, int64_t n, hipStream_t s) {
+  const int64_t want = ceil_div(n, 256 * 4);
+  cast_f16_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>(in, (_Float16*)out, n);
+  return check_launch();
+}
+
 // ------------------------------------------------------------------------------------------------------------ quantise
 __device__ __forceinline__ float load_as_f32(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_as_f32(const _Float16* p, int64_t i) { return (float)p[i]; }

@@ -20,7 +20,8 @@ _TORCH_DT = {torch.float32: F32, torch.float16: F16, torch.int8: I8, torch.int32
 _DT_TORCH = {v: k for k, v in _TORCH_DT.items()}
 
 EXPORTS = [
-    "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_quantize_workspace_bytes",
+    "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
+    "gpusq_quantize_workspace_bytes",
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
 ]
@@ -51,6 +52,7 @@ def lib():
         L.gpusq_last_hip_error.restype = ci
         L.gpusq_version.restype = ci
         L.gpusq_prune_2to4.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_cast_f16.argtypes = [vp, vp, i64, vp]
         L.gpusq_quantize_workspace_bytes.restype = ctypes.c_size_t
         L.gpusq_quantize_workspace_bytes.argtypes = [ci, i64, i64]
         L.gpusq_quantize_int8.argtypes = [vp, ci, vp, vp, ci, ci, i64, i64, vp, vp]
@@ -63,7 +65,7 @@ def lib():
         L.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_int8_dense.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
-        for name in ("gpusq_prune_2to4", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
+        for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
                      "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
             getattr(L, name).restype = ci
         _lib = L
@@ -104,6 +106,13 @@ def prune_2to4(W, out=None, want_mask=False):
     mask = torch.empty((N, max(K // 4, 1)), dtype=torch.uint8, device=W.device) if want_mask else None
     _check(lib().gpusq_prune_2to4(_ptr(W), _ptr(out), _ptr(mask), _TORCH_DT[W.dtype], N, K, _stream()), "gpusq_prune_2to4")
     return (out, mask) if want_mask else out
+
+
+def cast_f16(X, out=None):
+    """gpusq_cast_f16: fp32 tensor -> fp16 tensor of the same shape (round-to-nearest-even)."""
+    out = torch.empty(X.shape, dtype=torch.float16, device=X.device) if out is None else out
+    _check(lib().gpusq_cast_f16(_ptr(X), _ptr(out), X.numel(), _stream()), "gpusq_cast_f16")
+    return out
 
 
 def quantize_int8(X, mode, scale=None):

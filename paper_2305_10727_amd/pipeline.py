@@ -1,0 +1,97 @@
+"""One linear layer's full path with preallocated device buffers: prune -> quantise -> compress -> pack (weight
+side), quantise activations, sparse GEMM with fused epilogue.  Every step is one call into libgpusq through ctypes;
+this class only owns the buffers and passes pointers (PyTorch = device memory + current stream).
+"""
+import ctypes
+
+import torch
+
+from . import gpusq as G
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+class SparseLinear:
+    """Buffers and call sequence for Y = act(X W^T + b) with 2:4-pruned W [N,K].
+
+    precision 'int8': per-output-channel int8 weights, per-tensor int8 activations, int32 accumulation.
+    precision 'fp16': fp16 weights and activations, fp32 accumulation.
+    x_dtype: dtype of the activations handed in (fp16, or fp32 for the int8 path)."""
+
+    def __init__(self, M, K, N, precision="int8", gelu=False, bias=True, out_dtype=torch.float16, x_dtype=torch.float16,
+                 device="cuda"):
+        assert precision in ("int8", "fp16")
+        self.M, self.K, self.N, self.precision, self.gelu = M, K, N, precision, gelu
+        self.out_dtype = out_dtype if precision == "int8" else torch.float16
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=device)
+        self.W_pruned = e((N, K), torch.float32)
+        self.epilogue = (G.EPI_BIAS if bias else 0) | (G.EPI_GELU if gelu else 0)
+        wdt = torch.int8 if precision == "int8" else torch.float16
+        self.W_low = e((N, K), wdt)  # quantised (int8) or rounded (fp16) masked weights: also the dense twin's operand
+        self.values = e((N, K // 2), wdt)
+        self.meta = e((N, G.meta_row_bytes(K)), torch.uint8)
+        self.packed = e((G.packed_bytes(wdt, N, K),), torch.uint8)
+        self.Y = e((M, N), self.out_dtype)
+        if precision == "int8":
+            self.w_scale = e((N,), torch.float32)
+            self.act_scale = e((1,), torch.float32)
+            self.Xq = e((M, K), torch.int8)
+            self.workspace = e((max(G.lib().gpusq_quantize_workspace_bytes(G.PER_TENSOR, M, K), 16),), torch.uint8)
+        self.x_dtype = x_dtype
+
+    # ---- weight side (a1, a2, a3 + packing) -------------------------------------------------------------------
+    def prepare_weights(self, W):
+        L, s = G.lib(), G._stream()
+        N, K = self.N, self.K
+        G._check(L.gpusq_prune_2to4(_p(W), _p(self.W_pruned), None, G.F32, N, K, s), "gpusq_prune_2to4")
+        if self.precision == "int8":
+            G._check(L.gpusq_quantize_int8(_p(self.W_pruned), G.F32, _p(self.W_low), _p(self.w_scale), G.PER_ROW, 0, N, K,
+                                           None, s), "gpusq_quantize_int8")
+            dt = G.I8
+        else:
+            G._check(L.gpusq_cast_f16(_p(self.W_pruned), _p(self.W_low), N * K, s), "gpusq_cast_f16")
+            dt = G.F16
+        G._check(L.gpusq_compress(_p(self.W_low), _p(self.values), _p(self.meta), None, dt, N, K, s), "gpusq_compress")
+        G._check(L.gpusq_pack(_p(self.values), _p(self.meta), _p(self.packed), dt, N, K, s), "gpusq_pack")
+
+    # ---- activation side + GEMM (a4, a5, a6) --------------------------------------------------------------------
+    def quantize_activations(self, X):
+        G._check(G.lib().gpusq_quantize_int8(_p(X), G._TORCH_DT[X.dtype], _p(self.Xq), _p(self.act_scale), G.PER_TENSOR, 0,
+                                             self.M, self.K, _p(self.workspace), G._stream()), "gpusq_quantize_int8")
+
+    def gemm(self, X, bias, out_scale=None):
+        L, s = G.lib(), G._stream()
+        M, N, K = self.M, self.N, self.K
+        if self.precision == "int8":
+            G._check(L.gpusq_spgemm_int8(_p(self.Xq), _p(self.packed), _p(self.act_scale), _p(self.w_scale), _p(bias),
+                                         _p(self.Y), G._TORCH_DT[self.out_dtype], _p(out_scale), M, N, K, self.epilogue, s),
+                     "gpusq_spgemm_int8")
+        else:
+            G._check(L.gpusq_spgemm_fp16(_p(X), _p(self.packed), _p(bias), _p(self.Y), M, N, K, self.epilogue, s),
+                     "gpusq_spgemm_fp16")
+        return self.Y
+
+    def gemm_dense(self, X, bias, out_scale=None):
+        """the dense twin on the same masked weights"""
+        L, s = G.lib(), G._stream()
+        M, N, K = self.M, self.N, self.K
+        if self.precision == "int8":
+            G._check(L.gpusq_gemm_int8_dense(_p(self.Xq), _p(self.W_low), _p(self.act_scale), _p(self.w_scale), _p(bias),
+                                             _p(self.Y), G._TORCH_DT[self.out_dtype], _p(out_scale), M, N, K, self.epilogue,
+                                             s), "gpusq_gemm_int8_dense")
+        else:
+            G._check(L.gpusq_gemm_fp16_dense(_p(X), _p(self.W_low), _p(bias), _p(self.Y), M, N, K, self.epilogue, s),
+                     "gpusq_gemm_fp16_dense")
+        return self.Y
+
+    def forward(self, X, bias, out_scale=None):
+        if self.precision == "int8":
+            self.quantize_activations(X)
+        return self.gemm(X, bias, out_scale)
+
+    def full_path(self, W, X, bias, out_scale=None):
+        """all steps of the path in order, as one benchmark step times them"""
+        self.prepare_weights(W)
+        return self.forward(X, bias, out_scale)

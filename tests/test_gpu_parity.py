@@ -79,6 +79,14 @@ def test_prune_bit_exact(g, dtype):
     assert np.array_equal(host(t), oracle.prune_2to4(W)[0])
 
 
+def test_cast_f16_matches_round_to_nearest_even(g):
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.standard_normal(5003).astype(np.float32) * np.float32(10.0) ** rng.integers(-9, 6, 5003).astype(np.float32),
+                        np.array([65504, 65519.99, 65520, 1e9, 6.1e-5, 5.96e-8, 2.98e-8, 2.9802322e-8, 1.00048828125, -0.0], np.float32)])
+    exp = np.array([oracle.f32_to_f16(v) for v in x], np.uint16)
+    assert np.array_equal(host(g.cast_f16(dev(x))).view(np.uint16), exp)
+
+
 # ------------------------------------------------------------------------------------------------ a2 / a4 quantise
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
 def test_quantize_rows_bit_exact(g, dtype):
@@ -243,7 +251,7 @@ def fp16_problem(M, K, N, seed, integers=False):
 @pytest.mark.parametrize("M,K,N,seed", FP16_SHAPES)
 def test_spgemm_fp16(g, M, K, N, seed):
     X, W, Wh, vals, meta, bias = fp16_problem(M, K, N, seed)
-    Wp = g.prune_2to4(dev(W)).to(torch.float16)  # dtype cast of a tensor: plumbing, not a step of the method
+    Wp = g.cast_f16(g.prune_2to4(dev(W)))
     v, m = g.compress(Wp)
     assert np.array_equal(host(v).view(np.uint16), vals.view(np.uint16)) and np.array_equal(host(m), meta)
     packed = g.pack(v, m, K)
@@ -313,7 +321,7 @@ def test_c1_full_size_sampled_rows_and_self_consistency(g):
     assert ulp_diff_f16(host(y)[rows], o["y16"]).max() <= 1
     # fp16 path on the same shape
     Xh = X.astype(np.float16)
-    Wp = g.prune_2to4(dev(W)).to(torch.float16)
+    Wp = g.cast_f16(g.prune_2to4(dev(W)))
     v, m = g.compress(Wp)
     packed = g.pack(v, m, K)
     yh = g.spgemm_fp16(dev(Xh), packed, N, bias=dev(bias), gelu=True)
