@@ -120,7 +120,7 @@ size_t gpusq_packed_bytes(gpusq_dtype dt, int64_t N, int64_t K) {
   if (check_nk(N, K) != GPUSQ_OK || (dt != GPUSQ_F16 && dt != GPUSQ_I8)) return 0;
   const bool is_i8 = dt == GPUSQ_I8;
   const int64_t ksteps = ceil_div(K, step_elems(is_i8));
-  return (size_t)(ceil_div(N, kRowBlock) * ksteps * 4 * frag_bytes(is_i8));
+  return (size_t)(ceil_div(N, kTileRows) * ksteps * tile_bytes(is_i8));
 }
 
 gpusq_status gpusq_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,

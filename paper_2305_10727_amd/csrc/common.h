@@ -7,28 +7,35 @@
 
 namespace gpusq {
 
-// ---- geometry of the kernel-native packed weight format (see pack.hip) ----------------------------------------
-// Rows are handled in blocks of 64 output channels = 4 fragments of 16 rows; K in steps of 128 bytes of the dense
-// activation row (128 int8 or 64 fp16 elements), which is the K extent of one gfx950 sparse matrix instruction
-// (v_smfmac_i32_16x16x128_i8 / v_smfmac_f32_16x16x64_f16).
-constexpr int kRowBlock = 64;          // output channels per packed row block
-constexpr int kFragRows = 16;          // rows of one instruction operand
+// ---- geometry of the kernel-native packed weight format (written by pack.hip, read by the GEMM kernels) ----------
+// K advances in steps of 128 bytes of the dense activation row (128 int8 or 64 fp16 elements), the K extent of one
+// gfx950 sparse matrix instruction (v_smfmac_i32_16x16x128_i8 / v_smfmac_f32_16x16x64_f16).  Output channels are
+// grouped in tiles of 256 = 4 blocks of 64 = 16 fragments of 16 rows.  The packed buffer is an array of tiles
+// [ceil(N/256)][ksteps]; one tile holds, for its 256 channels and one K step,
+//     16 fragments x 1024 bytes of kept values   (fragment f, lane l: 16 bytes at f*1024 + l*16)
+//   + 16 fragments x 64 lanes of index bits      (4 bytes per lane for int8, 2 for fp16), starting at byte 16384,
+// so that a workgroup fetches a tile with whole 1 KB wavefront-wide copies and a wavefront reads a fragment with one
+// 16-byte and one 4-byte (2-byte) access per lane.
+constexpr int kRowBlock = 64;          // output channels whose fragments interleave (see packed_row_to_channel)
+constexpr int kTileRows = 256;         // output channels per packed tile
 constexpr int kStepBytes = 128;        // bytes of a dense activation row consumed per K step
 constexpr int kFragValueBytes = 1024;  // 64 lanes x 16 bytes of kept values
+constexpr int kTileValueBytes = 16 * kFragValueBytes;
 
 __host__ __device__ constexpr int step_elems(bool is_i8) { return is_i8 ? 128 : 64; }
 // index bytes of one fragment: 2 bits per kept value; 16 int8 values (32 bits) or 8 fp16 values (16 bits) per lane
 __host__ __device__ constexpr int frag_index_bytes(bool is_i8) { return is_i8 ? 256 : 128; }
-__host__ __device__ constexpr int frag_bytes(bool is_i8) { return kFragValueBytes + frag_index_bytes(is_i8); }
+__host__ __device__ constexpr int tile_bytes(bool is_i8) { return kTileValueBytes + 16 * frag_index_bytes(is_i8); }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Row r (0..15) of fragment t (0..3) inside a 64-row block holds output channel
-//   n = 64*blk + 16*(r/4) + 4*t + (r%4).
+//   n = 64*blk + 32*(t/2) + 8*(r/4) + 4*(t%2) + (r%4).
 // The accumulator of a 16x16 matrix instruction gives lane l the rows 4*(l/16)..4*(l/16)+3 of its column, so with
-// this permutation a lane ends up with 16 consecutive output channels over the 4 fragments of a block and the four
-// lane groups of a wave cover 64 consecutive channels: full 128-byte lines of Y per activation row.
-__host__ __device__ inline int packed_row_to_channel(int t, int r) { return 16 * (r >> 2) + 4 * t + (r & 3); }
+// this permutation a lane ends up, over fragments 0 and 1, with the 8 consecutive channels 8*(l/16)..+7 of one
+// activation row (16 bytes of fp16 output) and the four lane groups of a wavefront write 64 contiguous bytes of that
+// row in one store; fragments 2 and 3 give the next 32 channels the same way.
+__host__ __device__ inline int packed_row_to_channel(int t, int r) { return 32 * (t >> 1) + 8 * (r >> 2) + 4 * (t & 1) + (r & 3); }
 
 void set_last_hip_error(hipError_t e);
 

@@ -6,6 +6,7 @@
 // Register semantics (measured): A (4 VGPRs) lane l byte i -> row l%32, K index 16*(l/32)+i (8*(l/32)+i for fp16
 // elements); B likewise with column l%32; D (16 VGPRs) lane l register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 #include "common.h"
+#include "epilogue.h"
 
 namespace gpusq {
 
@@ -29,68 +30,13 @@ __device__ __forceinline__ typename AccD<IS_I8>::type mfma32(v4i a, v4i b, typen
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float gelu_dense_f32(float v) { return 0.5f * v * erfcf(-0.70710678118654752f * v); }
-
-__device__ __forceinline__ int requantize_dense(float v, float s) {
-  float r = rintf(__fdiv_rn(v, s));
-  r = fminf(fmaxf(r, -127.0f), 127.0f);
-  return (v != v) ? 0 : (int)r;
-}
-
 // LDS row of output channel c (0..63) inside a wavefront's 64-channel block.  Accumulator register r of lane half h
-// in 32-row tile t is tile row 8*(r/4)+4h+r%4; placing channel 32h+16t+r there gives a lane 32 consecutive channels.
+// in 32-row tile t is tile row 8*(r/4)+4h+r%4; placing channel 32t + 8*(r/4) + 4h... is the natural order, and we
+// want instead that lane half h holds, in registers 8u..8u+7 of tile t, the 8 consecutive channels
+// 32t + 16u + 8h .. +7: then a store of 8 channels per lane writes 16 contiguous bytes and the two lane halves 32.
 __device__ __forceinline__ int lds_row_of_channel(int c) {
-  const int h = c >> 5, t = (c >> 4) & 1, r = c & 15;
+  const int t = c >> 5, u = (c >> 4) & 1, h = (c >> 3) & 1, r = 8 * u + (c & 7);
   return 32 * t + 8 * (r >> 2) + 4 * h + (r & 3);
-}
-
-template <bool IS_I8>
-__device__ __forceinline__ void store_16_dense(const GemmArgs& a, int64_t m, int n, const float (&v)[16], const int (&raw)[16]) {
-  const int N = a.N;
-  const bool full = n + 16 <= N;
-  if (IS_I8 && a.out_dt == GPUSQ_I32) {
-    int* y = (int*)a.Y + m * N + n;
-    if (full) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) *(v4i*)(y + 4 * j) = v4i{raw[4 * j], raw[4 * j + 1], raw[4 * j + 2], raw[4 * j + 3]};
-    } else {
-#pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (n + j < N) y[j] = raw[j];
-    }
-  } else if (IS_I8 && a.out_dt == GPUSQ_I8) {
-    const float so = a.out_scale[0];
-    int8_t* y = (int8_t*)a.Y + m * N + n;
-    int q[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) q[j] = requantize_dense(v[j], so) & 0xFF;
-    if (full && (N & 15) == 0) {
-      v4i pk;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) pk[j] = q[4 * j] | (q[4 * j + 1] << 8) | (q[4 * j + 2] << 16) | (q[4 * j + 3] << 24);
-      *(v4i*)y = pk;
-    } else {
-#pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (n + j < N) y[j] = (int8_t)q[j];
-    }
-  } else {
-    _Float16* y = (_Float16*)a.Y + m * N + n;
-    if (full && (N & 7) == 0) {
-      v8h lo, hi;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        lo[j] = (_Float16)v[j];
-        hi[j] = (_Float16)v[8 + j];
-      }
-      *(v8h*)y = lo;
-      *(v8h*)(y + 8) = hi;
-    } else {
-#pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (n + j < N) y[j] = (_Float16)v[j];
-    }
-  }
 }
 
 // Workgroup = 4 wavefronts WN x WM; a wavefront owns 2 x TM accumulator tiles of 32 x 32 (64 channels x TM*32 rows).
@@ -104,6 +50,8 @@ __global__ void __launch_bounds__(256) dense_kernel(const GemmArgs a, const int 
 
   __shared__ __attribute__((aligned(16))) uint8_t Xs[2][BM * kLdsRowD];
   __shared__ __attribute__((aligned(16))) uint8_t Ws[2][BN * kLdsRowD];
+  __shared__ __attribute__((aligned(16))) float cs[BN];
+  __shared__ __attribute__((aligned(16))) float bs[BN];
 
   const int per_xcd = (tiles_total + 7) / 8;
   const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
@@ -117,6 +65,11 @@ __global__ void __launch_bounds__(256) dense_kernel(const GemmArgs a, const int 
   const int ksteps = (int)((k_bytes + kStepBytes - 1) / kStepBytes);
   const uint8_t* Xg = (const uint8_t*)a.X;
   const uint8_t* Wg = (const uint8_t*)a.W;
+  if (tid < BN) {
+    ChannelParams prm;
+    prm.fetch<IS_I8>(a, n_blk * BN + tid);
+    prm.publish(cs, bs, tid);  // made visible by the barriers of the main loop
+  }
 
   acc_t acc[2][TM];
 #pragma unroll
@@ -183,42 +136,38 @@ __global__ void __launch_bounds__(256) dense_kernel(const GemmArgs a, const int 
     __syncthreads();
   }
 
-  const bool use_bias = (a.epilogue & GPUSQ_EPI_BIAS) != 0, use_gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
-  const bool raw_out = IS_I8 && a.out_dt == GPUSQ_I32;
-  float s_a = 1.0f;
-  if (IS_I8 && !raw_out) s_a = a.act_scale[0];
+  // epilogue: lane half h holds, in registers 8u..8u+7 of tile t, channels n_wave + 32t + 16u + 8h .. +7
+  const bool use_gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int n = n_blk * BN + wn * 64 + (lane >> 5) * 32 + 16 * t;
-    if (n >= N) continue;
-    float cs[16], bs[16];
+  for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const bool ok = n + j < N;
-      cs[j] = (IS_I8 && !raw_out && ok) ? s_a * a.w_scale[n + j] : 1.0f;
-      bs[j] = (use_bias && ok && !raw_out) ? a.bias[n + j] : 0.0f;
-    }
+    for (int u = 0; u < 2; ++u) {
+      const int n = n_blk * BN + wn * 64 + 32 * t + 16 * u + (lane >> 5) * 8;
+      float c8[8], b8[8];
 #pragma unroll
-    for (int mt = 0; mt < TM; ++mt) {
-      const int64_t m = (int64_t)m_blk * BM + (wm * TM + mt) * 32 + l32;
-      if (m >= M) continue;
-      float v[16];
-      int raw[16];
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        if constexpr (IS_I8) {
-          raw[j] = acc[t][mt][j];
-          const float f = (float)raw[j];
-          v[j] = use_bias ? __fmaf_rn(f, cs[j], bs[j]) : f * cs[j];
-        } else {
-          raw[j] = 0;
-          v[j] = acc[t][mt][j] + bs[j];
-        }
-        if (use_gelu) v[j] = gelu_dense_f32(v[j]);
+      for (int j = 0; j < 8; j += 4) {
+        const float4 cc = *(const float4*)(cs + (n - n_blk * BN) + j), bb = *(const float4*)(bs + (n - n_blk * BN) + j);
+        c8[j] = cc.x; c8[j + 1] = cc.y; c8[j + 2] = cc.z; c8[j + 3] = cc.w;
+        b8[j] = bb.x; b8[j + 1] = bb.y; b8[j + 2] = bb.z; b8[j + 3] = bb.w;
       }
-      store_16_dense<IS_I8>(a, m, n, v, raw);
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
+        const int64_t m = (int64_t)m_blk * BM + (wm * TM + mt) * 32 + l32;
+        float v[8];
+        int raw[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          if constexpr (IS_I8) {
+            raw[j] = acc[t][mt][8 * u + j];
+            v[j] = epilogue_value<true>(raw[j], 0.0f, c8[j], b8[j], use_gelu);
+          } else {
+            raw[j] = 0;
+            v[j] = epilogue_value<false>(0, acc[t][mt][8 * u + j], c8[j], b8[j], use_gelu);
+          }
+        }
+        if (m < M) store_8<IS_I8>(a, m, n, v, raw);
+      }
     }
-  }
 }
 
 template <bool IS_I8, int TM, int WN, int WM>

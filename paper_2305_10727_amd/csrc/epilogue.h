@@ -1,0 +1,110 @@
+// Fused epilogue shared by the sparse and dense GEMM kernels: dequantise, bias, GELU, convert, store.
+#pragma once
+#include "common.h"
+
+namespace gpusq {
+
+typedef int ep_v4i __attribute__((ext_vector_type(4)));
+typedef int ep_v2i __attribute__((ext_vector_type(2)));
+typedef _Float16 ep_v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 ep_v4h __attribute__((ext_vector_type(4)));
+
+// Exact-erf GELU, GELU(x) = x * Phi(x), evaluated as  max(x, 0) - t * Phi(-t),  t = min(|x|, 6.5), with
+// Phi(-t) = 2^P(t) and P a degree-5 polynomial fitted to log2 Phi(-t) on [0, 6.5] (weighted so that the result is
+// within 0.15 fp16 ulp of the exact value everywhere, including the negative tail down to fp16 subnormals).
+// One transcendental (v_exp_f32) and eight full-rate VALU operations per element: the fp32 epilogue of a GEMM
+// whose output is written in fp16 is VALU-limited on this chip, so the library erf (dozens of operations) is not
+// an option.  For t > 6.5 the subtracted term is below 3e-10.  NaN inputs give 0.
+__device__ __forceinline__ float gelu_f32(float x) {
+  const float t = fminf(fabsf(x), 6.5f);
+  float p = __fmaf_rn(t, -0.0003336848458275199f, 0.005954924505203962f);
+  p = __fmaf_rn(p, t, -0.04866418614983559f);
+  p = __fmaf_rn(p, t, -0.46354809403419495f);
+  p = __fmaf_rn(p, t, -1.149438738822937f);
+  p = __fmaf_rn(p, t, -1.0001022815704346f);
+  const float q = __builtin_amdgcn_exp2f(p);
+  return __fmaf_rn(-t, q, fmaxf(x, 0.0f));
+}
+
+// q = clamp(rint(v / s), -127, 127): the same IEEE division + round-half-even as the quantiser of the activations
+__device__ __forceinline__ int requantize_code(float v, float s) {
+  float r = rintf(__fdiv_rn(v, s));
+  r = fminf(fmaxf(r, -127.0f), 127.0f);
+  return (v != v) ? 0 : (int)r;
+}
+
+// Per-channel epilogue constants of a workgroup's output channels, staged in LDS: c[n] = act_scale * w_scale[n]
+// (1 on the FP16 path) and b[n] = bias[n] (0 when there is no bias, which leaves fma(x, c, 0) == x * c and
+// acc + 0 == acc bit for bit).  fetch() issues the global loads early (one channel per thread), publish() writes
+// them to LDS; the caller puts a barrier between publish() and the first read.
+struct ChannelParams {
+  float c, b;
+  template <bool IS_I8>
+  __device__ __forceinline__ void fetch(const GemmArgs& a, int n) {
+    const bool ok = n < a.N;
+    const bool raw_out = IS_I8 && a.out_dt == GPUSQ_I32;
+    c = 1.0f;
+    b = 0.0f;
+    if (IS_I8 && !raw_out && ok) c = a.act_scale[0] * a.w_scale[n];
+    if ((a.epilogue & GPUSQ_EPI_BIAS) && !raw_out && ok) b = a.bias[n];
+  }
+  __device__ __forceinline__ void publish(float* cs, float* bs, int i) const {
+    cs[i] = c;
+    bs[i] = b;
+  }
+};
+
+// INT8 path: v = fma((float)acc, c, b); FP16 path: v = acc + b.  Then optional GELU.
+template <bool IS_I8>
+__device__ __forceinline__ float epilogue_value(int raw, float accf, float c, float b, bool use_gelu) {  // use_gelu: uniform
+  float v;
+  if constexpr (IS_I8)
+    v = __fmaf_rn((float)raw, c, b);
+  else
+    v = accf + b;
+  return use_gelu ? gelu_f32(v) : v;
+}
+
+// Converts and stores 8 consecutive output channels [n, n+8) of activation row m held by one lane.
+// N % 4 == 0 is guaranteed by the host, so each half of 4 channels is entirely inside or outside the matrix and
+// 4-channel stores are naturally aligned; with N % 8 == 0 the 8 channels go out in one store.
+// OUT: output dtype fixed at compile time (a gpusq_dtype value), or -1 to take it from the arguments at run time.
+template <bool IS_I8, int OUT = -1>
+__device__ __forceinline__ void store_8(const GemmArgs& a, int64_t m, int n, const float (&v)[8], const int (&raw)[8]) {
+  const int N = a.N;
+  const int out_dt = OUT >= 0 ? OUT : a.out_dt;
+  if (n >= N) return;
+  const bool whole = (N & 7) == 0;  // then n + 8 <= N as well, because n is a multiple of 8
+  const bool second = n + 8 <= N;
+  if (IS_I8 && out_dt == GPUSQ_I32) {
+    int* y = (int*)a.Y + m * N + n;
+    *(ep_v4i*)y = ep_v4i{raw[0], raw[1], raw[2], raw[3]};
+    if (second) *(ep_v4i*)(y + 4) = ep_v4i{raw[4], raw[5], raw[6], raw[7]};
+  } else if (IS_I8 && out_dt == GPUSQ_I8) {
+    const float so = a.out_scale[0];
+    int8_t* y = (int8_t*)a.Y + m * N + n;
+    int q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = requantize_code(v[j], so) & 0xFF;
+    const int lo = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24), hi = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+    if (whole) {
+      *(ep_v2i*)y = ep_v2i{lo, hi};
+    } else {
+      *(int*)y = lo;
+      if (second) *(int*)(y + 4) = hi;
+    }
+  } else {
+    _Float16* y = (_Float16*)a.Y + m * N + n;
+    if (whole) {
+      ep_v8h h;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) h[j] = (_Float16)v[j];
+      *(ep_v8h*)y = h;
+    } else {
+      *(ep_v4h*)y = ep_v4h{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+      if (second) *(ep_v4h*)(y + 4) = ep_v4h{(_Float16)v[4], (_Float16)v[5], (_Float16)v[6], (_Float16)v[7]};
+    }
+  }
+}
+
+}  // namespace gpusq

@@ -300,27 +300,27 @@ gpusq_status launch_decompress(const void* values, const uint8_t* meta, void* W,
 }
 
 // ------------------------------------------------------------------------------------------------------------ pack
-// Packed layout (bytes): fragment f = ((blk * ksteps) + ks) * 4 + t  at  f * frag_bytes; inside a fragment the 64
-// lanes' 16 value bytes come first (lane-major), then the lanes' index words (4 bytes for int8, 2 for fp16).
-// Lane l of a fragment serves row r = l % 16 and the dense K range [ks*E + (l/16)*E/4, +E/4) with E = elements per
-// step; the sparse matrix instruction wants, per lane, the kept values of that range in order (16 bytes) and their
-// 2-bit positions in order starting at bit 0 of the index register.  Both are contiguous byte runs of the canonical
-// arrays: values[n][k0/2 .. k0/2 + kept) and meta[n][k0/8 ..).
+// Re-tiles the canonical (values, meta) arrays into the packed tile format described in common.h.
+// Lane l of fragment f (0..15) of tile (nb, ks) serves output channel nb*256 + 64*(f/4) + packed_row_to_channel(f%4,
+// l%16) and the dense K range [ks*E + (l/16)*E/4, +E/4) with E = elements per step; the sparse matrix instruction
+// wants, per lane, the kept values of that range in order (16 bytes) and their 2-bit positions in order starting at
+// bit 0 of the index register.  Both are contiguous byte runs of the canonical arrays:
+// values[n][k0/2 .. k0/2 + kept) and meta[n][k0/8 ..).  Rows >= N and K beyond the row end are zero-filled.
 template <bool IS_I8>
 __global__ void __launch_bounds__(256) pack_kernel(const uint8_t* __restrict__ values, const uint8_t* __restrict__ meta,
                                                    uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps,
                                                    int64_t total_lanes) {
-  constexpr int E = step_elems(IS_I8);       // dense elements per step
-  constexpr int ES = IS_I8 ? 1 : 2;          // element size
-  constexpr int KL = E / 4;                  // dense elements per lane
-  constexpr int IB = IS_I8 ? 4 : 2;          // index bytes per lane
+  constexpr int E = step_elems(IS_I8);  // dense elements per step
+  constexpr int ES = IS_I8 ? 1 : 2;     // element size
+  constexpr int KL = E / 4;             // dense elements per lane
+  constexpr int IB = IS_I8 ? 4 : 2;     // index bytes per lane
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= total_lanes) return;
   const int lane = (int)(id & 63);
-  const int64_t f = id >> 6;
-  const int t = (int)(f & 3);
-  const int64_t ks = (f >> 2) % ksteps, blk = (f >> 2) / ksteps;
-  const int64_t n = blk * kRowBlock + packed_row_to_channel(t, lane & 15);
+  const int f = (int)((id >> 6) & 15);
+  const int64_t tile = id >> 10;
+  const int64_t ks = tile % ksteps, nb = tile / ksteps;
+  const int64_t n = nb * kTileRows + (f >> 2) * kRowBlock + packed_row_to_channel(f & 3, lane & 15);
   const int64_t k0 = ks * E + (int64_t)(lane >> 4) * KL;  // first dense element of this lane
   const int64_t mrb = (K / 4 + 1) / 2;
   uint8_t v[16];
@@ -336,25 +336,26 @@ __global__ void __launch_bounds__(256) pack_kernel(const uint8_t* __restrict__ v
     // padding (rows >= N, K beyond the row end) carries zero values; its positions are irrelevant
     ix[i] = (n < N && byte < mrb) ? meta[n * mrb + byte] : (uint8_t)0;
   }
-  uint8_t* frag = packed + f * frag_bytes(IS_I8);
+  uint8_t* t = packed + tile * tile_bytes(IS_I8);
   uint4 vv;
   vv.x = v[0] | (v[1] << 8) | (v[2] << 16) | ((uint32_t)v[3] << 24);
   vv.y = v[4] | (v[5] << 8) | (v[6] << 16) | ((uint32_t)v[7] << 24);
   vv.z = v[8] | (v[9] << 8) | (v[10] << 16) | ((uint32_t)v[11] << 24);
   vv.w = v[12] | (v[13] << 8) | (v[14] << 16) | ((uint32_t)v[15] << 24);
-  *(uint4*)(frag + lane * 16) = vv;
+  *(uint4*)(t + f * kFragValueBytes + lane * 16) = vv;
+  uint8_t* ip = t + kTileValueBytes + f * frag_index_bytes(IS_I8);
   if constexpr (IS_I8)
-    *(uint32_t*)(frag + kFragValueBytes + lane * 4) = ix[0] | (ix[1] << 8) | (ix[2] << 16) | ((uint32_t)ix[3] << 24);
+    *(uint32_t*)(ip + lane * 4) = ix[0] | (ix[1] << 8) | (ix[2] << 16) | ((uint32_t)ix[3] << 24);
   else
-    *(uint16_t*)(frag + kFragValueBytes + lane * 2) = (uint16_t)(ix[0] | (ix[1] << 8));
+    *(uint16_t*)(ip + lane * 2) = (uint16_t)(ix[0] | (ix[1] << 8));
 }
 
 gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,
                          hipStream_t s) {
   const bool is_i8 = dt == GPUSQ_I8;
   const int64_t ksteps = ceil_div(K, step_elems(is_i8));
-  const int64_t frags = ceil_div(N, kRowBlock) * ksteps * 4;
-  const int64_t total_lanes = frags * 64;
+  const int64_t tiles = ceil_div(N, kTileRows) * ksteps;
+  const int64_t total_lanes = tiles * 16 * 64;
   const unsigned blocks = (unsigned)ceil_div(total_lanes, 256);
   if (is_i8)
     pack_kernel<true><<<blocks, 256, 0, s>>>((const uint8_t*)values, meta, (uint8_t*)packed, N, K, ksteps, total_lanes);

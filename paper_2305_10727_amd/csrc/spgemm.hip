@@ -13,7 +13,14 @@
 //                 (fp16: 16 bits, the half selected by ABID);
 //   B (8 VGPRs): lane l, byte i -> column l%16, K index 64*(i/16) + 16*(l/16) + i%16 (two half-K operands back to back);
 //   D (4 VGPRs): lane l, register r -> row 4*(l/16)+r, column l%16.
+//
+// Two kernels:
+//   spgemm_tile_kernel  256 n x 128 m workgroup tile, operands brought into LDS by direct global->LDS copies
+//                       (no staging registers), two LDS stages, two workgroups per CU so that one workgroup's
+//                       epilogue (VALU + stores) overlaps the other's matrix instructions.  Needs K*elemsize % 128 == 0.
+//   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
 #include "common.h"
+#include "epilogue.h"
 
 namespace gpusq {
 
@@ -22,8 +29,6 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v16h __attribute__((ext_vector_type(16)));
-
-constexpr int kLdsRow = kStepBytes + 16;  // 144-byte row pitch: 16 rows x 16-byte reads hit 16 distinct bank groups
 
 template <bool IS_I8>
 struct AccT { typedef v4f type; };
@@ -38,91 +43,233 @@ __device__ __forceinline__ typename AccT<IS_I8>::type smfmac(v4i a, v8i b, typen
     return __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v16h, b), c, idx, 0, 0);
 }
 
-// exact-erf GELU, written with erfc so that the negative tail keeps its relative accuracy
-__device__ __forceinline__ float gelu_f32(float v) { return 0.5f * v * erfcf(-0.70710678118654752f * v); }
-
-__device__ __forceinline__ int requantize_code(float v, float s) {
-  float r = rintf(__fdiv_rn(v, s));
-  r = fminf(fmaxf(r, -127.0f), 127.0f);
-  return (v != v) ? 0 : (int)r;
+// XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them, each with its own L2), so give
+// every XCD one contiguous run of tiles; tiles that share an X slab (same m block) then share an L2.
+__device__ __forceinline__ int xcd_tile(int tiles_total) {
+  const int per_xcd = (tiles_total + 7) / 8;
+  return (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
 }
 
-// Converts and stores the 16 consecutive output channels [n, n+16) a lane holds for activation row m.
-template <bool IS_I8>
-__device__ __forceinline__ void store_16(const GemmArgs& a, int64_t m, int n, const float (&v)[16], const int (&raw)[16]) {
-  const int N = a.N;
-  const bool full = n + 16 <= N;
-  if (IS_I8 && a.out_dt == GPUSQ_I32) {
-    int* y = (int*)a.Y + m * N + n;
-    if (full) {  // N % 4 == 0 is checked on the host, so the row start is 16-byte aligned
+// Epilogue of one wavefront: TN fragments x TM column tiles of accumulators -> Y.
+// Lane (q = lane/16, c = lane%16) holds, for 64-row block b and tile mt, the 16 channels
+// n = n_wave + 64*b + 16*q + 4*t + r (t = fragment in block, r = register) of activation row m = m_wave + 16*mt + c.
+// cs/bs: the workgroup's per-channel constants in LDS, indexed by channel - n_tile (see ChannelParams).
+// GELU / OUT: compile-time epilogue choice, or -1 to read it from the arguments.
+template <bool IS_I8, int TN, int TM, int GELU = -1, int OUT = -1>
+__device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[TN][TM],
+                                              const float* cs, const float* bs, int n_tile, int n_wave, int64_t m_wave,
+                                              int lane) {
+  const bool use_gelu = GELU >= 0 ? (GELU != 0) : ((a.epilogue & GPUSQ_EPI_GELU) != 0);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) *(v4i*)(y + 4 * j) = v4i{raw[4 * j], raw[4 * j + 1], raw[4 * j + 2], raw[4 * j + 3]};
-    } else {
+  for (int g = 0; g < TN / 2; ++g) {  // pairs of fragments = 32 channels; this lane holds 8 of them
+    const int n = n_wave + (g >> 1) * kRowBlock + (g & 1) * 32 + (lane >> 4) * 8;
+    float c8[8], b8[8];
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (n + j < N) y[j] = raw[j];
+    for (int j = 0; j < 8; j += 4) {
+      const float4 cc = *(const float4*)(cs + (n - n_tile) + j), bb = *(const float4*)(bs + (n - n_tile) + j);
+      c8[j] = cc.x; c8[j + 1] = cc.y; c8[j + 2] = cc.z; c8[j + 3] = cc.w;
+      b8[j] = bb.x; b8[j + 1] = bb.y; b8[j + 2] = bb.z; b8[j + 3] = bb.w;
     }
-  } else if (IS_I8 && a.out_dt == GPUSQ_I8) {
-    const float so = a.out_scale[0];
-    int8_t* y = (int8_t*)a.Y + m * N + n;
-    int q[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) q[j] = requantize_code(v[j], so) & 0xFF;
-    if (full && (N & 15) == 0) {
-      v4i pk;
+    for (int mt = 0; mt < TM; ++mt) {
+      const int64_t m = m_wave + mt * 16 + (lane & 15);
+      float v[8];
+      int raw[8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) pk[j] = q[4 * j] | (q[4 * j + 1] << 8) | (q[4 * j + 2] << 16) | (q[4 * j + 3] << 24);
-      *(v4i*)y = pk;
-    } else {
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (n + j < N) y[j] = (int8_t)q[j];
-    }
-  } else {
-    _Float16* y = (_Float16*)a.Y + m * N + n;
-    if (full && (N & 7) == 0) {
-      v8h lo, hi;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        lo[j] = (_Float16)v[j];
-        hi[j] = (_Float16)v[8 + j];
-      }
-      *(v8h*)y = lo;
-      *(v8h*)(y + 8) = hi;
-    } else {
-#pragma unroll
-      for (int j = 0; j < 16; ++j)
-        if (n + j < N) y[j] = (_Float16)v[j];
+        for (int r = 0; r < 4; ++r) {
+          const int j = 4 * t + r;
+          if constexpr (IS_I8) {
+            raw[j] = acc[2 * g + t][mt][r];
+            v[j] = epilogue_value<true>(raw[j], 0.0f, c8[j], b8[j], use_gelu);
+          } else {
+            raw[j] = 0;
+            v[j] = epilogue_value<false>(0, acc[2 * g + t][mt][r], c8[j], b8[j], use_gelu);
+          }
+        }
+      if (m < a.M) store_8<IS_I8, OUT>(a, m, n, v, raw);
     }
   }
 }
 
+// ------------------------------------------------------------------------------------------------ large-tile kernel
+#define GPUSQ_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define GPUSQ_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int kBigBN = 256, kBigBM = 128, kBigTM = 4;
+constexpr int kXStageBytes = kBigBM * kStepBytes;  // 16 KB: 128 rows x 128 bytes, 16-byte chunks XOR-swizzled per row
+
+// One wavefront's share of the copies that bring K step `ks` into an LDS stage: the 16 KB X slab, 16 fragments of
+// kept values and 4 KB (fp16: 2 KB) of index words are moved in 1 KB pieces dealt round-robin to the NW wavefronts.
+// Each copy instruction moves 64 lanes x 16 bytes from per-lane global addresses to 1 KB of consecutive LDS.
+// The X slab is stored row-major with the 16-byte chunk c of row r at chunk position c ^ ((r >> 1) & 7), so that the
+// 16 rows a quarter-wavefront reads at the same K offset fall in 16 different 16-byte bank groups; the swizzle is
+// applied by choosing which global chunk each lane fetches.
+template <bool IS_I8, int NW>
+__device__ __forceinline__ void issue_stage_copies(uint8_t* stage, const uint8_t* Xg, const uint8_t* Wtile, int64_t k_bytes,
+                                                   int64_t m0, int M, int ks, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 16 / NW; ++i) {
+    const int j = wave + i * NW;           // 1 KB block = 8 rows
+    const int r = 8 * j + (lane >> 3);     // row inside the slab
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    int64_t m = m0 + r;
+    m = m < M ? m : (int64_t)M - 1;        // rows past the end re-read the last row; their results are never stored
+    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Xg + m * k_bytes + (int64_t)ks * kStepBytes + c * 16),
+                                     GPUSQ_LPTR(stage + j * 1024), 16, 0, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < 16 / NW; ++i) {
+    const int f = wave + i * NW;
+    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Wtile + f * kFragValueBytes + lane * 16),
+                                     GPUSQ_LPTR(stage + kXStageBytes + f * kFragValueBytes), 16, 0, 0);
+  }
+  if (wave < (IS_I8 ? 4 : 2))
+    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Wtile + kTileValueBytes + wave * 1024 + lane * 16),
+                                     GPUSQ_LPTR(stage + kXStageBytes + kTileValueBytes + wave * 1024), 16, 0, 0);
+}
+
+// All matrix instructions of one K step for one wavefront (TN*16 n x 64 m): TN fragments of A, 4 slabs of B.
+template <bool IS_I8, int TN>
+__device__ __forceinline__ void compute_stage(const uint8_t* stage, typename AccT<IS_I8>::type (&acc)[TN][kBigTM], int wn,
+                                              int wm, int lane) {
+  const uint8_t* Ws = stage + kXStageBytes;
+  const int sw = (lane & 15) >> 1;  // (row >> 1) & 7: tile and wavefront offsets are multiples of 16 rows
+  const int q = lane >> 4;
+  const uint8_t* xrow = stage + (wm * kBigTM * 16 + (lane & 15)) * kStepBytes;
+  const uint8_t* xlo = xrow + (q ^ sw) * 16;
+  const uint8_t* xhi = xrow + ((4 + q) ^ sw) * 16;
+  const uint8_t* abase = Ws + wn * TN * kFragValueBytes + lane * 16;
+  const uint8_t* ibase = Ws + kTileValueBytes + wn * TN * frag_index_bytes(IS_I8) + lane * (IS_I8 ? 4 : 2);
+  v4i lo = *(const v4i*)xlo, hi = *(const v4i*)xhi;
+  v4i av[TN];
+  int ai[TN];
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    av[tn] = *(const v4i*)(abase + tn * kFragValueBytes);
+    if constexpr (IS_I8)
+      ai[tn] = *(const int*)(ibase + tn * 256);
+    else
+      ai[tn] = (int)*(const uint16_t*)(ibase + tn * 128);
+  }
+#pragma unroll
+  for (int mt = 0; mt < kBigTM; ++mt) {
+    const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    if (mt + 1 < kBigTM) {  // next slab of B is requested before this slab's matrix instructions are issued
+      lo = *(const v4i*)(xlo + (mt + 1) * 16 * kStepBytes);
+      hi = *(const v4i*)(xhi + (mt + 1) * 16 * kStepBytes);
+    }
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[tn], b, acc[tn][mt], ai[tn]);
+  }
+}
+
+// s_waitcnt vmcnt(0) lgkmcnt(0) (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]): the
+// wavefront's own global->LDS copies have landed and its LDS reads of the stage it leaves have returned, so after
+// the barrier that follows every stage may be read, and the stage just left may be overwritten.
+#define GPUSQ_WAIT_COPIES_AND_LDS() __builtin_amdgcn_s_waitcnt(0x0070)
+
+// TN = 8: 4 wavefronts (2 x 2), 128 n x 64 m each, 2 wavefronts per SIMD.  TN = 4: 8 wavefronts (4 x 2), 64 n x 64 m
+// each, 4 wavefronts per SIMD.  Two workgroups per CU in both cases.
+//
+// Persistent: the grid holds (at most) two workgroups per CU and every workgroup walks over tiles with a fixed
+// stride, so the output stores of one tile drain while the next tile is being computed, and the two workgroups of a
+// CU drift out of phase (one in its VALU/store epilogue while the other owns the matrix pipe).
+// Tile order: workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x takes the contiguous
+// run of tiles [x*per_xcd, (x+1)*per_xcd) and its workgroups take them in order; tiles that share an X slab (same m
+// block, n fastest) are then computed close in time on one L2.
+template <bool IS_I8, int GELU, int OUT, int TN>
+__global__ void __launch_bounds__(2048 / TN, TN == 8 ? 2 : 4) spgemm_tile_kernel(const GemmArgs a, const int tiles_n, const int tiles_total) {
+  typedef typename AccT<IS_I8>::type acc_t;
+  constexpr int WNB = 16 / TN, NW = 2 * WNB;
+  constexpr int ES = IS_I8 ? 1 : 2;
+  constexpr int STAGE = kXStageBytes + tile_bytes(IS_I8);
+  __shared__ __attribute__((aligned(1024))) uint8_t S0[STAGE];
+  __shared__ __attribute__((aligned(1024))) uint8_t S1[STAGE];
+  __shared__ __attribute__((aligned(16))) float cs[kBigBN];
+  __shared__ __attribute__((aligned(16))) float bs[kBigBN];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = wave % WNB, wm = wave / WNB;
+  const int64_t k_bytes = (int64_t)a.K * ES;
+  const int ksteps = (int)(k_bytes / kStepBytes);
+  const uint8_t* Xg = (const uint8_t*)a.X;
+  const int per_xcd = (tiles_total + 7) / 8;
+  const int xcd = (int)(blockIdx.x & 7), wgs_per_xcd = (int)(gridDim.x >> 3);
+  const int tile_end = min((xcd + 1) * per_xcd, tiles_total);
+
+  for (int tile = xcd * per_xcd + (int)(blockIdx.x >> 3); tile < tile_end; tile += wgs_per_xcd) {
+    const int n_blk = tile % tiles_n, m_blk = tile / tiles_n;
+    const uint8_t* Wt = (const uint8_t*)a.W + (int64_t)n_blk * ksteps * tile_bytes(IS_I8);
+    const int64_t m0 = (int64_t)m_blk * kBigBM;
+
+    // both stages are free here: the previous tile's last reads of them completed before its final barrier
+    issue_stage_copies<IS_I8, NW>(S0, Xg, Wt, k_bytes, m0, a.M, 0, wave, lane);
+    ChannelParams prm;
+    if (tid < kBigBN) prm.fetch<IS_I8>(a, n_blk * kBigBN + tid);
+
+    acc_t acc[TN][kBigTM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < kBigTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+
+    GPUSQ_WAIT_COPIES_AND_LDS();  // also: the previous tile's epilogue reads of cs/bs have returned
+    __builtin_amdgcn_s_barrier();
+    if (tid < kBigBN) prm.publish(cs, bs, tid);  // read only after the barriers of the main loop
+    for (int ks = 0; ks < ksteps; ks += 2) {
+      // stage 1 was last read before the barrier that ended the previous trip, so it may be overwritten now
+      if (ks + 1 < ksteps) issue_stage_copies<IS_I8, NW>(S1, Xg, Wt + (int64_t)(ks + 1) * tile_bytes(IS_I8), k_bytes, m0, a.M, ks + 1, wave, lane);
+      compute_stage<IS_I8, TN>(S0, acc, wn, wm, lane);
+      GPUSQ_WAIT_COPIES_AND_LDS();
+      __builtin_amdgcn_s_barrier();
+      if (ks + 1 < ksteps) {
+        if (ks + 2 < ksteps) issue_stage_copies<IS_I8, NW>(S0, Xg, Wt + (int64_t)(ks + 2) * tile_bytes(IS_I8), k_bytes, m0, a.M, ks + 2, wave, lane);
+        compute_stage<IS_I8, TN>(S1, acc, wn, wm, lane);
+        GPUSQ_WAIT_COPIES_AND_LDS();
+        __builtin_amdgcn_s_barrier();
+      }
+    }
+    wave_epilogue<IS_I8, TN, kBigTM, GELU, OUT>(a, acc, cs, bs, n_blk * kBigBN, n_blk * kBigBN + wn * TN * 16,
+                                                m0 + wm * kBigTM * 16, lane);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ small / generic kernel
+constexpr int kLdsRow = kStepBytes + 16;  // 144-byte row pitch: 16 rows x 16-byte reads hit 16 distinct bank groups
+
 // Workgroup = 4 wavefronts arranged WN (along n) x WM (along m); a wavefront owns TN x TM accumulator tiles.
-// Workgroup tile: BN = WN*TN*16 output channels x BM = WM*TM*16 activation rows.
+// Workgroup tile: BN = WN*TN*16 output channels x BM = WM*TM*16 activation rows.  X goes global -> registers -> LDS
+// (zero-filled past the row end and past M), the weight fragments go straight from global memory to registers.
 template <bool IS_I8, int TN, int TM, int WN, int WM>
-__global__ void __launch_bounds__(256) spgemm_kernel(const GemmArgs a, const int tiles_n, const int tiles_total) {
+__global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, const int tiles_n, const int tiles_total) {
   static_assert(WN * WM == 4 && TN % 4 == 0, "4 wavefronts; a wavefront spans whole 64-row blocks");
   typedef typename AccT<IS_I8>::type acc_t;
   constexpr int BN = WN * TN * 16, BM = WM * TM * 16;
   constexpr int ES = IS_I8 ? 1 : 2;
-  constexpr int FB = frag_bytes(IS_I8);
+  constexpr int IB = frag_index_bytes(IS_I8);
   constexpr int XCH = BM / 32;  // 16-byte chunks of the X slab each thread moves per K step
 
   __shared__ __attribute__((aligned(16))) uint8_t Xs[2][BM * kLdsRow];
+  __shared__ __attribute__((aligned(16))) float cs[BN];
+  __shared__ __attribute__((aligned(16))) float bs[BN];
 
-  // XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them, each with its own L2), so
-  // give every XCD one contiguous run of tiles; tiles that share an X slab (same m block) then share an L2.
-  const int per_xcd = (tiles_total + 7) / 8;
-  const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  const int tile = xcd_tile(tiles_total);
   if (tile >= tiles_total) return;
   const int n_blk = tile % tiles_n, m_blk = tile / tiles_n;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn = wave % WN, wm = wave / WN;
   const int M = a.M, N = a.N;
+  if (tid < BN) {
+    ChannelParams prm;
+    prm.fetch<IS_I8>(a, n_blk * BN + tid);
+    prm.publish(cs, bs, tid);  // made visible by the barriers of the main loop
+  }
   const int64_t k_bytes = (int64_t)a.K * ES;
   const int ksteps = (int)((k_bytes + kStepBytes - 1) / kStepBytes);
-  const int row_blocks = (N + kRowBlock - 1) / kRowBlock;
+  const int row_blocks = ((N + kTileRows - 1) / kTileRows) * 4;  // the packed buffer is padded to whole 256-row tiles
   const int rb0 = (n_blk * BN + wn * TN * 16) / kRowBlock;
   const uint8_t* Xg = (const uint8_t*)a.X;
   const uint8_t* Wg = (const uint8_t*)a.W;
@@ -159,12 +306,13 @@ __global__ void __launch_bounds__(256) spgemm_kernel(const GemmArgs a, const int
     for (int tn = 0; tn < TN; ++tn) {
       const int rb = rb0 + tn / 4;
       if (rb < row_blocks) {
-        const uint8_t* f = Wg + (((int64_t)rb * ksteps + ks) * 4 + (tn & 3)) * FB;
-        av[slot][tn] = *(const v4i*)(f + lane * 16);
+        const uint8_t* t = Wg + ((int64_t)(rb >> 2) * ksteps + ks) * tile_bytes(IS_I8);
+        const int f = (rb & 3) * 4 + (tn & 3);
+        av[slot][tn] = *(const v4i*)(t + f * kFragValueBytes + lane * 16);
         if constexpr (IS_I8)
-          ai[slot][tn] = *(const int*)(f + kFragValueBytes + lane * 4);
+          ai[slot][tn] = *(const int*)(t + kTileValueBytes + f * IB + lane * 4);
         else
-          ai[slot][tn] = (int)*(const uint16_t*)(f + kFragValueBytes + lane * 2);
+          ai[slot][tn] = (int)*(const uint16_t*)(t + kTileValueBytes + f * IB + lane * 2);
       } else {
         av[slot][tn] = v4i{0, 0, 0, 0};
         ai[slot][tn] = 0;
@@ -197,65 +345,64 @@ __global__ void __launch_bounds__(256) spgemm_kernel(const GemmArgs a, const int
     if (more) store_x(cur ^ 1);
     __syncthreads();
   }
-
-  // ---- epilogue: dequantise, bias, GELU, convert, store.  Lane (q = lane/16, c = lane%16) holds, for 64-row block
-  // b and tile mt, the 16 channels n = n_wave + 64*b + 16*q + 4*t + r of activation row m = m_wave + 16*mt + c.
-  const bool use_bias = (a.epilogue & GPUSQ_EPI_BIAS) != 0, use_gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
-  const bool raw_out = IS_I8 && a.out_dt == GPUSQ_I32;
-  float s_a = 1.0f;
-  if (IS_I8 && !raw_out) s_a = a.act_scale[0];
-#pragma unroll
-  for (int b = 0; b < TN / 4; ++b) {
-    const int n = n_blk * BN + wn * TN * 16 + b * kRowBlock + (lane >> 4) * 16;
-    if (n >= N) continue;
-    float cs[16], bs[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const bool ok = n + j < N;
-      cs[j] = (IS_I8 && !raw_out && ok) ? s_a * a.w_scale[n + j] : 1.0f;
-      bs[j] = (use_bias && ok && !raw_out) ? a.bias[n + j] : 0.0f;
-    }
-#pragma unroll
-    for (int mt = 0; mt < TM; ++mt) {
-      const int64_t m = (int64_t)m_blk * BM + (wm * TM + mt) * 16 + (lane & 15);
-      if (m >= M) continue;
-      float v[16];
-      int raw[16];
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int j = 4 * t + r;
-          if constexpr (IS_I8) {
-            raw[j] = acc[4 * b + t][mt][r];
-            const float f = (float)raw[j];
-            v[j] = use_bias ? __fmaf_rn(f, cs[j], bs[j]) : f * cs[j];
-          } else {
-            raw[j] = 0;
-            v[j] = acc[4 * b + t][mt][r] + bs[j];
-          }
-          if (use_gelu) v[j] = gelu_f32(v[j]);
-        }
-      store_16<IS_I8>(a, m, n, v, raw);
-    }
-  }
+  wave_epilogue<IS_I8, TN, TM>(a, acc, cs, bs, n_blk * BN, n_blk * BN + wn * TN * 16, (int64_t)m_blk * BM + wm * TM * 16, lane);
 }
 
 template <bool IS_I8, int TN, int TM, int WN, int WM>
-static gpusq_status launch_cfg(const GemmArgs& a, hipStream_t s) {
+static gpusq_status launch_small(const GemmArgs& a, hipStream_t s) {
   constexpr int BN = WN * TN * 16, BM = WM * TM * 16;
   const int tiles_n = (int)ceil_div(a.N, BN), tiles_m = (int)ceil_div(a.M, BM);
   const int total = tiles_n * tiles_m;
   const int grid = (int)ceil_div(total, 8) * 8;  // whole rounds over the 8 XCDs; surplus workgroups exit at once
-  spgemm_kernel<IS_I8, TN, TM, WN, WM><<<grid, 256, 0, s>>>(a, tiles_n, total);
+  spgemm_small_kernel<IS_I8, TN, TM, WN, WM><<<grid, 256, 0, s>>>(a, tiles_n, total);
   return check_launch();
 }
+
+static int num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cus = n;
+  }
+  return cus;
+}
+
+#ifndef GPUSQ_TILE_TN
+#define GPUSQ_TILE_TN 8
+#endif
+constexpr int kTileTN = GPUSQ_TILE_TN;
 
 template <bool IS_I8>
 static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int64_t work = (int64_t)a.M * a.N;
-  if (work <= (int64_t)256 * 1024) return launch_cfg<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
-  return launch_cfg<IS_I8, 4, 4, 2, 2>(a, s);                                  // 128 x 128 tiles
+  const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
+  if (work <= (int64_t)256 * 1024) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
+  if (k_bytes % kStepBytes != 0) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);    // ragged K: zero-filling path
+  const int tiles_n = (int)ceil_div(a.N, kBigBN), tiles_m = (int)ceil_div(a.M, kBigBM);
+  const int total = tiles_n * tiles_m;
+  // persistent grid: two workgroups per CU (the LDS footprint allows no more), never more workgroups than tiles
+  const int resident = 2 * num_cus();
+  const dim3 grid((unsigned)(ceil_div(total < resident ? total : resident, 8) * 8));
+  const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
+  if constexpr (IS_I8) {
+    if (a.out_dt == GPUSQ_I32)
+      spgemm_tile_kernel<true, 0, GPUSQ_I32, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+    else if (a.out_dt == GPUSQ_I8 && gelu)
+      spgemm_tile_kernel<true, 1, GPUSQ_I8, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+    else if (a.out_dt == GPUSQ_I8)
+      spgemm_tile_kernel<true, 0, GPUSQ_I8, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+    else if (gelu)
+      spgemm_tile_kernel<true, 1, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+    else
+      spgemm_tile_kernel<true, 0, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+  } else {
+    if (gelu)
+      spgemm_tile_kernel<false, 1, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+    else
+      spgemm_tile_kernel<false, 0, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+  }
+  return check_launch();
 }
 
 gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s) {

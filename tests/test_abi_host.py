@@ -75,10 +75,10 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_spgemm_fp16(good, good, None, good, 0, 8, 32, 0, None) == ERR_SHAPE
     lib.gpusq_packed_bytes.restype = ctypes.c_size_t
     lib.gpusq_packed_bytes.argtypes = [ci, i64, i64]
-    # 64-row blocks x 128-byte K steps x 4 fragments of (1024 value bytes + index bytes)
-    assert lib.gpusq_packed_bytes(2, 768, 192) == 12 * 2 * 4 * 1280
-    assert lib.gpusq_packed_bytes(1, 768, 192) == 12 * 3 * 4 * 1152
-    assert lib.gpusq_packed_bytes(2, 100, 144) == 2 * 2 * 4 * 1280
+    # tiles of 256 channels x one 128-byte K step: 16 fragments of 1024 value bytes + 16 x 64 lanes of index bytes
+    assert lib.gpusq_packed_bytes(2, 768, 192) == 3 * 2 * (16384 + 4096)
+    assert lib.gpusq_packed_bytes(1, 768, 192) == 3 * 3 * (16384 + 2048)
+    assert lib.gpusq_packed_bytes(2, 100, 144) == 1 * 2 * (16384 + 4096)
     assert lib.gpusq_packed_bytes(0, 768, 192) == 0 and lib.gpusq_packed_bytes(2, 768, 190) == 0
     lib.gpusq_quantize_workspace_bytes.restype = ctypes.c_size_t
     lib.gpusq_quantize_workspace_bytes.argtypes = [ci, i64, i64]

@@ -227,7 +227,7 @@ def test_int8_epilogues(g, M, K, N, seed, kernel):
     qg = host(run(bias=bias, gelu=True, out_dtype=torch.int8, out_scale=dev(np.array([so / 4], np.float32))))
     eg = oracle.epilogue_int8_f32(acc, p.s_a, p.s_w, p.bias, gelu=True, out_scale=float(so / 4))["q8"]
     dq = np.abs(qg.astype(np.int32) - eg.astype(np.int32))
-    assert dq.max() <= 1 and (dq != 0).mean() < 1e-3  # a tie broken by the last bit of erf may move one code
+    assert dq.max() <= 1 and (dq != 0).mean() < 5e-3  # the GELU fit is within 0.15 fp16 ulp: a near-tie may move one code
 
 
 FP16_SHAPES = [(1, 16, 4, 0), (16, 64, 64, 1), (37, 192, 48, 2), (197, 192, 768, 0), (33, 144, 100, 3), (130, 256, 132, 4),
