@@ -102,6 +102,17 @@ size_t gpusq_packed_bytes(gpusq_dtype dt, int64_t N, int64_t K);
 gpusq_status gpusq_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt,
                         int64_t N, int64_t K, void* stream);
 
+/* ---- the whole weight-side preparation in one launch: prune 2:4 -> (dt = GPUSQ_I8: per-output-channel INT8
+ * quantisation | dt = GPUSQ_F16: rounding to FP16) -> compress -> pack, the order the paper gives ("first compress as
+ * 2:4 FP16 sparse, then further quantize", Sec. 3.1).  Results are bit-identical to calling gpusq_prune_2to4,
+ * gpusq_quantize_int8(GPUSQ_PER_ROW) / gpusq_cast_f16, gpusq_compress and gpusq_pack in turn.
+ *   W [N][K] fp32 (input);  packed: gpusq_packed_bytes(dt, N, K) bytes (required);  w_scale [N] (required for I8).
+ *   Optional outputs (NULL to skip): W_pruned [N][K] fp32, W_low [N][K] of dt (the masked low-precision weights, the
+ *   dense twins' operand), values [N][K/2] of dt, meta [N][ceil(K/8)].
+ *   K is limited to 16384 (GPUSQ_ERR_UNSUPPORTED beyond): one fp32 row is staged in LDS. */
+gpusq_status gpusq_prepare_weights(const float* W, gpusq_dtype dt, float* W_pruned, void* W_low, float* w_scale,
+                                   void* values, uint8_t* meta, void* packed, int64_t N, int64_t K, void* stream);
+
 /* ---- sparse GEMM with fused epilogue [Sec. 3.1: sparse matrix x dense matrix = dense matrix, the same result as
  * the dense GEMM on the zero-filled operand, computed over the kept values only].
  * FP16: Y[m][n] = fp16( act( sum_k X[m][k] * W[n][k]  (fp32 accumulation) + bias[n] ) )

@@ -82,7 +82,7 @@ gpusq_status gpusq_cast_f16(const float* in, void* out, int64_t n, void* stream)
 size_t gpusq_quantize_workspace_bytes(int mode, int64_t rows, int64_t cols) {
   (void)rows;
   (void)cols;
-  return mode == GPUSQ_PER_TENSOR ? 16 : 0;
+  return mode == GPUSQ_PER_TENSOR ? 4096 : 0;  // per-workgroup partial maxima of the first pass
 }
 
 gpusq_status gpusq_quantize_int8(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
@@ -131,6 +131,20 @@ gpusq_status gpusq_pack(const void* values, const uint8_t* meta, void* packed, g
   if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
   if (!aligned16(values) || !aligned16(meta) || !aligned16(packed)) return GPUSQ_ERR_ALIGN;
   return launch_pack(values, meta, packed, dt, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_prepare_weights(const float* W, gpusq_dtype dt, float* W_pruned, void* W_low, float* w_scale, void* values,
+                                   uint8_t* meta, void* packed, int64_t N, int64_t K, void* stream) {
+  if (!W || !packed) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (dt == GPUSQ_I8 && !w_scale) return GPUSQ_ERR_NULL;
+  if (K * (int64_t)sizeof(float) > 64 * 1024) return GPUSQ_ERR_UNSUPPORTED;  // one fp32 row is staged in LDS
+  if (!aligned16(W) || !aligned16(packed) || (W_pruned && !aligned16(W_pruned)) || (W_low && !aligned16(W_low)) ||
+      (values && !aligned16(values)) || (meta && !aligned16(meta)))
+    return GPUSQ_ERR_ALIGN;
+  return launch_prepare_weights(W, dt, W_pruned, W_low, w_scale, values, meta, packed, N, K, (hipStream_t)stream);
 }
 
 gpusq_status gpusq_spgemm_fp16(const void* X, const void* Wpacked, const float* bias, void* Y, int64_t M, int64_t N,

@@ -66,6 +66,9 @@ gpusq_status launch_decompress(const void* values, const uint8_t* meta, void* W,
 gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,
                          hipStream_t s);
 
+gpusq_status launch_prepare_weights(const float* W, gpusq_dtype dt, float* Wp, void* Wlow, float* w_scale, void* values,
+                                    uint8_t* meta, void* packed, int64_t N, int64_t K, hipStream_t s);
+
 inline gpusq_status check_launch() {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {

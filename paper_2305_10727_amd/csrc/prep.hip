@@ -139,41 +139,74 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const T* __restrict_
 
 __global__ void fill_u32_kernel(uint32_t* p, uint32_t v) { *p = v; }
 
-// per-tensor max |x|: non-negative floats order like their bit patterns, so the reduction ends in an integer atomic max
-template <typename T>
-__global__ void __launch_bounds__(256) tensor_amax_kernel(const T* __restrict__ X, int64_t n, uint32_t* __restrict__ amax_bits) {
-  float amax = 0.0f;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) amax = fmaxf(amax, fabsf(load_as_f32(X, i)));
-  amax = wave_max(amax);
+constexpr int kAmaxMaxBlocks = 1024;  // per-block partial maxima kept in the caller's workspace (4 KB)
+
+// 8 consecutive elements as fp32, one 16-byte (fp16) or two 16-byte (fp32) loads
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const _Float16* p, float (&v)[8]) {
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  const h8 a = *(const h8*)p;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = (float)a[j];
+}
+
+__device__ __forceinline__ float block_max(float v) {
   __shared__ float part[4];
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = amax;
+  v = wave_max(v);
+  __syncthreads();  // a previous use of part[] has been read
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    amax = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
-    atomicMax(amax_bits, __float_as_uint(amax));
+  return fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+}
+
+// per-tensor max |x|, first pass: every workgroup streams its share with 16-byte loads and leaves one partial
+// maximum in the workspace; the quantising pass folds the partials (no atomics, nothing to clear beforehand)
+template <typename T>
+__global__ void __launch_bounds__(256) tensor_amax_kernel(const T* __restrict__ X, int64_t n, float* __restrict__ partial) {
+  float amax = 0.0f;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 8;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < n; i += stride) {
+    if (i + 8 <= n) {
+      float v[8];
+      load8(X + i, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(v[j]));
+    } else {
+      for (int64_t j = i; j < n; ++j) amax = fmaxf(amax, fabsf(load_as_f32(X, j)));
+    }
   }
+  amax = block_max(amax);
+  if (threadIdx.x == 0) partial[blockIdx.x] = amax;
 }
 
 template <typename T>
 __global__ void __launch_bounds__(256) quantize_tensor_kernel(const T* __restrict__ X, int8_t* __restrict__ Q,
-                                                              float* __restrict__ scale, const uint32_t* __restrict__ amax_bits,
-                                                              int64_t n) {
+                                                              float* __restrict__ scale, const float* __restrict__ partial,
+                                                              int npartial, int64_t n) {
   float s;
-  if (amax_bits) {
-    const float amax = __uint_as_float(*amax_bits);
+  if (partial) {
+    float amax = 0.0f;
+    for (int i = threadIdx.x; i < npartial; i += 256) amax = fmaxf(amax, partial[i]);
+    amax = block_max(amax);
     s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
     if (blockIdx.x == 0 && threadIdx.x == 0) scale[0] = s;
   } else {
     s = scale[0];
   }
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
-  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
-    if (i + 3 < n) {
-      const int a = quantize_code(load_as_f32(X, i), s), b = quantize_code(load_as_f32(X, i + 1), s);
-      const int c = quantize_code(load_as_f32(X, i + 2), s), d = quantize_code(load_as_f32(X, i + 3), s);
-      *(uint32_t*)(Q + i) = (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) |
-                            ((uint32_t)(d & 0xFF) << 24);
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 8;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < n; i += stride) {
+    if (i + 8 <= n) {
+      float v[8];
+      load8(X + i, v);
+      uint32_t w[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        w[h] = (uint32_t)(quantize_code(v[4 * h], s) & 0xFF) | ((uint32_t)(quantize_code(v[4 * h + 1], s) & 0xFF) << 8) |
+               ((uint32_t)(quantize_code(v[4 * h + 2], s) & 0xFF) << 16) | ((uint32_t)(quantize_code(v[4 * h + 3], s) & 0xFF) << 24);
+      *(uint2*)(Q + i) = uint2{w[0], w[1]};
     } else {
       for (int64_t j = i; j < n; ++j) Q[j] = (int8_t)quantize_code(load_as_f32(X, j), s);
     }
@@ -188,14 +221,15 @@ static gpusq_status quantize_typed(const T* X, int8_t* Xq, float* scale, int mod
     return check_launch();
   }
   const int64_t n = rows * cols;
-  const unsigned blocks = (unsigned)(ceil_div(n, 256 * 16) < 4096 ? ceil_div(n, 256 * 16) : 4096);
-  uint32_t* amax_bits = nullptr;
+  const int64_t want = ceil_div(n, 256 * 8 * 2);  // two 8-element vectors per thread
+  const unsigned blocks_q = (unsigned)(want < 8192 ? want : 8192);
+  const unsigned blocks_a = (unsigned)(want < kAmaxMaxBlocks ? want : kAmaxMaxBlocks);
+  const float* partial = nullptr;
   if (!scale_is_input) {
-    amax_bits = (uint32_t*)workspace;
-    fill_u32_kernel<<<1, 1, 0, s>>>(amax_bits, 0u);
-    tensor_amax_kernel<T><<<blocks, 256, 0, s>>>(X, n, amax_bits);
+    tensor_amax_kernel<T><<<blocks_a, 256, 0, s>>>(X, n, (float*)workspace);
+    partial = (const float*)workspace;
   }
-  quantize_tensor_kernel<T><<<blocks, 256, 0, s>>>(X, Xq, scale, amax_bits, n);
+  quantize_tensor_kernel<T><<<blocks_q, 256, 0, s>>>(X, Xq, scale, partial, (int)blocks_a, n);
   return check_launch();
 }
 
@@ -361,6 +395,165 @@ gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, 
     pack_kernel<true><<<blocks, 256, 0, s>>>((const uint8_t*)values, meta, (uint8_t*)packed, N, K, ksteps, total_lanes);
   else
     pack_kernel<false><<<blocks, 256, 0, s>>>((const uint8_t*)values, meta, (uint8_t*)packed, N, K, ksteps, total_lanes);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------------------ fused
+// prune -> (INT8: per-output-channel quantise | FP16: round) -> compress -> pack for one weight matrix in one launch.
+// One workgroup per output channel.  Phase 1 streams the fp32 row into LDS and reduces max|w| (pruning never removes
+// the row maximum, so this is also the maximum of the pruned row).  Phase 2 gives each thread one "lane unit" of the
+// packed format: the 32 (INT8) or 16 (FP16) consecutive dense elements whose kept values fill one lane's 16 value
+// bytes and 4 (2) index bytes; the thread prunes its groups of 4, quantises or rounds them, applies the compression
+// rule to the low-precision group, and writes the unit to every requested output.  All arithmetic is the same
+// sequence of operations as the separate kernels above, so the results are bit-identical to running them in turn.
+template <bool IS_I8>
+__global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __restrict__ W, float* __restrict__ Wp,
+                                                              uint8_t* __restrict__ Wlow, float* __restrict__ w_scale,
+                                                              uint8_t* __restrict__ values, uint8_t* __restrict__ meta,
+                                                              uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps) {
+  extern __shared__ float row[];
+  constexpr int E = step_elems(IS_I8), ES = IS_I8 ? 1 : 2, KL = E / 4, IB = IS_I8 ? 4 : 2;
+  const int64_t n = blockIdx.x;
+  const float* w = W + n * K;
+  float amax = 0.0f;
+  for (int64_t k = (int64_t)threadIdx.x * 4; k < K; k += 1024) {
+    const float4 v = *(const float4*)(w + k);
+    *(float4*)(row + k) = v;
+    amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+  }
+  float s = 1.0f;
+  if constexpr (IS_I8) {
+    amax = block_max(amax);  // contains the barrier that publishes row[]
+    s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
+    if (threadIdx.x == 0) w_scale[n] = s;
+  } else {
+    __syncthreads();
+  }
+  const int64_t mrb = (K / 4 + 1) / 2;
+  const int64_t units = (K + KL - 1) / KL;
+  // packed position of this channel: tile nb, fragment f, row r of the fragment
+  const int64_t nb = n / kTileRows;
+  const int in_tile = (int)(n % kTileRows), blk = in_tile / kRowBlock, c64 = in_tile % kRowBlock;
+  // inverse of packed_row_to_channel: c64 = 32*(t/2) + 8*(r/4) + 4*(t%2) + r%4
+  const int t = 2 * (c64 >> 5) + ((c64 >> 2) & 1), r = 4 * ((c64 >> 3) & 3) + (c64 & 3);
+  const int f = blk * 4 + t;
+  for (int64_t u = threadIdx.x; u < units; u += 256) {
+    const int64_t k0 = u * KL;
+    uint8_t vbytes[16];
+    uint8_t ibytes[IB];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vbytes[i] = 0;
+#pragma unroll
+    for (int i = 0; i < IB; ++i) ibytes[i] = 0;
+#pragma unroll
+    for (int g = 0; g < KL / 4; ++g) {
+      const int64_t k = k0 + 4 * g;
+      if (k < K) {
+        const float4 x = *(const float4*)(row + k);
+        const unsigned m = keep_mask_of_4(__float_as_uint(x.x) & 0x7FFFFFFFu, __float_as_uint(x.y) & 0x7FFFFFFFu,
+                                          __float_as_uint(x.z) & 0x7FFFFFFFu, __float_as_uint(x.w) & 0x7FFFFFFFu);
+        float4 p;
+        p.x = (m & 1u) ? x.x : 0.0f; p.y = (m & 2u) ? x.y : 0.0f; p.z = (m & 4u) ? x.z : 0.0f; p.w = (m & 8u) ? x.w : 0.0f;
+        if (Wp) *(float4*)(Wp + n * K + k) = p;
+        unsigned nib;
+        if constexpr (IS_I8) {
+          const int q0 = quantize_code(p.x, s), q1 = quantize_code(p.y, s), q2 = quantize_code(p.z, s), q3 = quantize_code(p.w, s);
+          if (Wlow) *(uint32_t*)(Wlow + n * K + k) = (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) | ((uint32_t)(q3 & 0xFF) << 24);
+          const unsigned mq = keep_mask_of_4((unsigned)abs(q0), (unsigned)abs(q1), (unsigned)abs(q2), (unsigned)abs(q3));
+          nib = nibble_of_mask(mq);
+          const unsigned p0 = nib & 3u, p1 = nib >> 2;
+          vbytes[2 * g] = (uint8_t)(p0 == 0 ? q0 : (p0 == 1 ? q1 : q2));
+          vbytes[2 * g + 1] = (uint8_t)(p1 == 1 ? q1 : (p1 == 2 ? q2 : q3));
+        } else {
+          const _Float16 h0 = (_Float16)p.x, h1 = (_Float16)p.y, h2 = (_Float16)p.z, h3 = (_Float16)p.w;
+          const unsigned b0 = __builtin_bit_cast(unsigned short, h0), b1 = __builtin_bit_cast(unsigned short, h1);
+          const unsigned b2 = __builtin_bit_cast(unsigned short, h2), b3 = __builtin_bit_cast(unsigned short, h3);
+          if (Wlow) *(uint2*)(Wlow + (n * K + k) * 2) = uint2{b0 | (b1 << 16), b2 | (b3 << 16)};
+          const unsigned mq = keep_mask_of_4(b0 & 0x7FFFu, b1 & 0x7FFFu, b2 & 0x7FFFu, b3 & 0x7FFFu);
+          nib = nibble_of_mask(mq);
+          const unsigned p0 = nib & 3u, p1 = nib >> 2;
+          const unsigned v0 = p0 == 0 ? b0 : (p0 == 1 ? b1 : b2), v1 = p1 == 1 ? b1 : (p1 == 2 ? b2 : b3);
+          vbytes[4 * g] = (uint8_t)v0; vbytes[4 * g + 1] = (uint8_t)(v0 >> 8);
+          vbytes[4 * g + 2] = (uint8_t)v1; vbytes[4 * g + 3] = (uint8_t)(v1 >> 8);
+        }
+        ibytes[g >> 1] |= (uint8_t)(nib << (4 * (g & 1)));
+      }
+    }
+    uint4 vv;
+    vv.x = vbytes[0] | (vbytes[1] << 8) | (vbytes[2] << 16) | ((uint32_t)vbytes[3] << 24);
+    vv.y = vbytes[4] | (vbytes[5] << 8) | (vbytes[6] << 16) | ((uint32_t)vbytes[7] << 24);
+    vv.z = vbytes[8] | (vbytes[9] << 8) | (vbytes[10] << 16) | ((uint32_t)vbytes[11] << 24);
+    vv.w = vbytes[12] | (vbytes[13] << 8) | (vbytes[14] << 16) | ((uint32_t)vbytes[15] << 24);
+    const bool whole = k0 + KL <= K;
+    if (values) {
+      uint8_t* dst = values + (n * (K / 2) + k0 / 2) * ES;
+      if (whole && ((K / 2) * ES) % 16 == 0) {  // rows of the values array are 16-byte aligned
+        *(uint4*)dst = vv;
+      } else {
+        const int64_t nbytes = whole ? 16 : ((K - k0) / 2) * ES;
+        for (int64_t i = 0; i < nbytes; ++i) dst[i] = vbytes[i];
+      }
+    }
+    if (meta) {
+      uint8_t* dst = meta + n * mrb + k0 / 8;
+      const int64_t nbytes = whole ? IB : (mrb - k0 / 8);
+      for (int64_t i = 0; i < nbytes; ++i) dst[i] = ibytes[i];
+    }
+    const int64_t ks = k0 / E;
+    const int lane = r + 16 * (int)((k0 % E) / KL);
+    uint8_t* tp = packed + (nb * ksteps + ks) * tile_bytes(IS_I8);
+    *(uint4*)(tp + f * kFragValueBytes + lane * 16) = vv;
+    uint8_t* ip = tp + kTileValueBytes + f * frag_index_bytes(IS_I8);
+    if constexpr (IS_I8)
+      *(uint32_t*)(ip + lane * 4) = ibytes[0] | (ibytes[1] << 8) | (ibytes[2] << 16) | ((uint32_t)ibytes[3] << 24);
+    else
+      *(uint16_t*)(ip + lane * 2) = (uint16_t)(ibytes[0] | (ibytes[1] << 8));
+  }
+}
+
+// zero-fills the part of the packed buffer that no real channel / K range writes (rows >= N, K beyond the row end)
+template <bool IS_I8>
+__global__ void __launch_bounds__(256) clear_packed_padding_kernel(uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps,
+                                                                   int64_t total_lanes) {
+  constexpr int E = step_elems(IS_I8), KL = E / 4, IB = IS_I8 ? 4 : 2;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= total_lanes) return;
+  const int lane = (int)(id & 63);
+  const int f = (int)((id >> 6) & 15);
+  const int64_t tile = id >> 10;
+  const int64_t ks = tile % ksteps, nb = tile / ksteps;
+  const int64_t n = nb * kTileRows + (f >> 2) * kRowBlock + packed_row_to_channel(f & 3, lane & 15);
+  const int64_t k0 = ks * E + (int64_t)(lane >> 4) * KL;
+  if (n < N && k0 < K) return;  // written by prepare_weights_kernel
+  uint8_t* t = packed + tile * tile_bytes(IS_I8);
+  *(uint4*)(t + f * kFragValueBytes + lane * 16) = uint4{0, 0, 0, 0};
+  uint8_t* ip = t + kTileValueBytes + f * frag_index_bytes(IS_I8);
+  if constexpr (IS_I8)
+    *(uint32_t*)(ip + lane * 4) = 0u;
+  else
+    *(uint16_t*)(ip + lane * IB) = (uint16_t)0;
+}
+
+gpusq_status launch_prepare_weights(const float* W, gpusq_dtype dt, float* Wp, void* Wlow, float* w_scale, void* values,
+                                    uint8_t* meta, void* packed, int64_t N, int64_t K, hipStream_t s) {
+  const bool is_i8 = dt == GPUSQ_I8;
+  const int64_t ksteps = ceil_div(K, step_elems(is_i8));
+  const size_t lds = (size_t)K * sizeof(float);
+  const bool padded = (N % kTileRows) != 0 || (K % step_elems(is_i8)) != 0;
+  if (padded) {
+    const int64_t total_lanes = ceil_div(N, kTileRows) * ksteps * 16 * 64;
+    const unsigned blocks = (unsigned)ceil_div(total_lanes, 256);
+    if (is_i8)
+      clear_packed_padding_kernel<true><<<blocks, 256, 0, s>>>((uint8_t*)packed, N, K, ksteps, total_lanes);
+    else
+      clear_packed_padding_kernel<false><<<blocks, 256, 0, s>>>((uint8_t*)packed, N, K, ksteps, total_lanes);
+  }
+  if (is_i8)
+    prepare_weights_kernel<true><<<(unsigned)N, 256, lds, s>>>(W, Wp, (uint8_t*)Wlow, w_scale, (uint8_t*)values, meta,
+                                                               (uint8_t*)packed, N, K, ksteps);
+  else
+    prepare_weights_kernel<false><<<(unsigned)N, 256, lds, s>>>(W, Wp, (uint8_t*)Wlow, w_scale, (uint8_t*)values, meta,
+                                                                (uint8_t*)packed, N, K, ksteps);
   return check_launch();
 }
 

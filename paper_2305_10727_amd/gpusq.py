@@ -22,7 +22,7 @@ _DT_TORCH = {v: k for k, v in _TORCH_DT.items()}
 EXPORTS = [
     "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
     "gpusq_quantize_workspace_bytes",
-    "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_spgemm_fp16",
+    "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
 ]
 
@@ -61,6 +61,8 @@ def lib():
         L.gpusq_packed_bytes.restype = ctypes.c_size_t
         L.gpusq_packed_bytes.argtypes = [ci, i64, i64]
         L.gpusq_pack.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_prepare_weights.argtypes = [vp, ci, vp, vp, vp, vp, vp, vp, i64, i64, vp]
+        L.gpusq_prepare_weights.restype = ci
         L.gpusq_spgemm_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
@@ -162,6 +164,27 @@ def pack(values, meta, K):
     packed = torch.empty(nbytes, dtype=torch.uint8, device=values.device)
     _check(lib().gpusq_pack(_ptr(values), _ptr(meta), _ptr(packed), _TORCH_DT[values.dtype], N, K, _stream()), "gpusq_pack")
     return packed
+
+
+def prepare_weights(W, dtype, want_intermediates=False):
+    """gpusq_prepare_weights: fp32 W [N,K] -> packed buffer (+ w_scale for int8) in one launch.
+    With want_intermediates also returns W_pruned, W_low, values, meta."""
+    N, K = W.shape
+    dt = _TORCH_DT[dtype]
+    packed = torch.empty(packed_bytes(dtype, N, K), dtype=torch.uint8, device=W.device)
+    w_scale = torch.empty(N, dtype=torch.float32, device=W.device) if dtype == torch.int8 else None
+    Wp = Wl = values = meta = None
+    if want_intermediates:
+        Wp = torch.empty_like(W)
+        Wl = torch.empty((N, K), dtype=dtype, device=W.device)
+        values = torch.empty((N, K // 2), dtype=dtype, device=W.device)
+        meta = torch.empty((N, meta_row_bytes(K)), dtype=torch.uint8, device=W.device)
+    _check(lib().gpusq_prepare_weights(_ptr(W), dt, _ptr(Wp), _ptr(Wl), _ptr(w_scale), _ptr(values), _ptr(meta), _ptr(packed),
+                                       N, K, _stream()), "gpusq_prepare_weights")
+    out = dict(packed=packed, w_scale=w_scale)
+    if want_intermediates:
+        out.update(W_pruned=Wp, W_low=Wl, values=values, meta=meta)
+    return out
 
 
 def _epi(bias, gelu):

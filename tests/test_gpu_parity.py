@@ -146,6 +146,30 @@ def test_compress_decompress_bit_exact(g, dtype):
         assert np.array_equal(host(g.decompress(v, m, K)).view(np.uint8), pruned.view(np.uint8))  # round trip = identity
 
 
+@pytest.mark.parametrize("N,K", [(1, 4), (3, 36), (64, 192), (100, 144), (257, 1028), (768, 768), (512, 2048)])
+def test_fused_weight_preparation_bit_exact(g, N, K):
+    """gpusq_prepare_weights == prune -> quantise/round -> compress -> pack, against the oracle and the separate calls"""
+    W = synth.weights(N, K, seed=N + K)
+    W[0, :4] = 0  # an all-zero group
+    P, _ = oracle.prune_2to4(W)
+    # INT8
+    Wq, s_w = oracle.quantize_rows_int8(P)
+    vals, meta, _ = oracle.compress(Wq)
+    o = g.prepare_weights(dev(W), torch.int8, want_intermediates=True)
+    assert np.array_equal(host(o["W_pruned"]).view(np.uint32), P.view(np.uint32))
+    assert np.array_equal(host(o["W_low"]), Wq) and np.array_equal(host(o["w_scale"]).view(np.uint32), s_w.view(np.uint32))
+    assert np.array_equal(host(o["values"]), vals) and np.array_equal(host(o["meta"]), meta)
+    assert torch.equal(o["packed"], g.pack(dev(vals), dev(meta), K))
+    assert torch.equal(g.prepare_weights(dev(W), torch.int8)["packed"], o["packed"])  # optional outputs skipped
+    # FP16
+    Wh = P.astype(np.float16)
+    vals, meta, _ = oracle.compress(Wh)
+    o = g.prepare_weights(dev(W), torch.float16, want_intermediates=True)
+    assert np.array_equal(host(o["W_low"]).view(np.uint16), Wh.view(np.uint16))
+    assert np.array_equal(host(o["values"]).view(np.uint16), vals.view(np.uint16)) and np.array_equal(host(o["meta"]), meta)
+    assert torch.equal(o["packed"], g.pack(dev(vals), dev(meta), K))
+
+
 # ------------------------------------------------------------------------------------------------ GEMM helpers
 class Int8Problem:
     def __init__(self, M, K, N, seed, dist="normal_clip4", rows=None):
