@@ -1,0 +1,105 @@
+"""Turns rocprofv3 CSV output of `bench.py --profile-mode` into the short summaries kept under profiles/.
+
+    python -m paper_2305_10727_amd.profiling --stats DIR --fetch DIR --write DIR --out-prefix PREFIX
+
+--stats: output directory of `rocprofv3 --kernel-trace --stats --output-format csv`
+--fetch / --write: output directories of `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` (one counter per run).
+HBM traffic per launch = counter value of the kernel x (known bytes of the calibration kernel / its counter value);
+the calibration kernel is the fp32->fp16 streaming kernel on 2^26 elements (reads 256 MiB, writes 128 MiB).
+"""
+import argparse
+import csv
+import glob
+import json
+import os
+from collections import defaultdict
+
+CALIB_KERNEL = "cast_f16_kernel"
+CALIB_READ = 4 << 26
+CALIB_WRITE = 2 << 26
+
+
+def _rows(directory, suffix):
+    files = glob.glob(os.path.join(directory, "**", "*" + suffix), recursive=True)
+    for f in files:
+        with open(f, newline="") as fh:
+            for row in csv.DictReader(fh):
+                yield row
+
+
+def kernel_stats(directory):
+    durs = defaultdict(list)
+    for r in _rows(directory, "kernel_trace.csv"):
+        durs[r["Kernel_Name"]].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    total = sum(sum(v) for v in durs.values()) or 1
+    out = []
+    for k, v in sorted(durs.items(), key=lambda kv: -sum(kv[1])):
+        out.append(dict(kernel=k, calls=len(v), total_ns=sum(v), avg_ns=sum(v) / len(v), min_ns=min(v), max_ns=max(v),
+                        percent=100.0 * sum(v) / total))
+    return out
+
+
+def counter_per_kernel(directory, counter):
+    vals = defaultdict(list)
+    for r in _rows(directory, "counter_collection.csv"):
+        if r["Counter_Name"] == counter:
+            vals[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    return {k: sum(v) / len(v) for k, v in vals.items()}
+
+
+def short(name, n=70):
+    return name if len(name) <= n else name[:n - 3] + "..."
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--stats")
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
+    ap.add_argument("--out-prefix", required=True)
+    ap.add_argument("--command", default="", help="the profiling command line, recorded in the summary")
+    a = ap.parse_args()
+    lines = []
+    if a.command:
+        lines += ["command: " + a.command, ""]
+    result = {}
+    if a.stats:
+        st = kernel_stats(a.stats)
+        lines.append("%-72s %6s %12s %10s %10s %10s %6s" % ("kernel", "calls", "total_us", "avg_us", "min_us", "max_us", "%"))
+        for r in st:
+            lines.append("%-72s %6d %12.1f %10.2f %10.2f %10.2f %6.1f" % (short(r["kernel"]), r["calls"], r["total_ns"] / 1e3,
+                                                                      r["avg_ns"] / 1e3, r["min_ns"] / 1e3, r["max_ns"] / 1e3,
+                                                                      r["percent"]))
+        result["kernel_avg_us"] = {r["kernel"]: r["avg_ns"] / 1e3 for r in st}
+    if a.fetch and a.write:
+        fetch = counter_per_kernel(a.fetch, "FETCH_SIZE")
+        write = counter_per_kernel(a.write, "WRITE_SIZE")
+        cf = [v for k, v in fetch.items() if CALIB_KERNEL in k]
+        cw = [v for k, v in write.items() if CALIB_KERNEL in k]
+        if cf and cw:
+            f_scale = CALIB_READ / cf[0]   # bytes per counter unit
+            w_scale = CALIB_WRITE / cw[0]
+            lines += ["", "FETCH_SIZE / WRITE_SIZE per launch, scaled by the calibration kernel (%s: %d B read -> counter %.1f, "
+                      "%d B written -> counter %.1f; bytes per unit %.1f / %.1f)" % (CALIB_KERNEL, CALIB_READ, cf[0], CALIB_WRITE,
+                                                                                   cw[0], f_scale, w_scale),
+                      "%-72s %14s %14s %14s" % ("kernel", "read_MB", "written_MB", "total_MB")]
+            traffic = {}
+            for k in sorted(set(fetch) | set(write)):
+                rb, wb = fetch.get(k, 0.0) * f_scale, write.get(k, 0.0) * w_scale
+                traffic[k] = dict(read_bytes=rb, write_bytes=wb)
+                lines.append("%-72s %14.2f %14.2f %14.2f" % (short(k), rb / 1e6, wb / 1e6, (rb + wb) / 1e6))
+            result["traffic"] = traffic
+            gemm = [v for k, v in traffic.items() if "spgemm_tile_kernel" in k]
+            if gemm:
+                result["hbm_bytes_per_launch"] = gemm[0]["read_bytes"] + gemm[0]["write_bytes"]
+                result["fetch_scale_bytes_per_unit"] = f_scale
+                result["write_scale_bytes_per_unit"] = w_scale
+    with open(a.out_prefix + ".txt", "w") as fh:
+        fh.write("\n".join(lines) + "\n")
+    with open(a.out_prefix + ".json", "w") as fh:
+        json.dump(result, fh, indent=1)
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    main()
