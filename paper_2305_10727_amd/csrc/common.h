@@ -13,7 +13,8 @@ namespace gpusq {
 // grouped in tiles of 256 = 4 blocks of 64 = 16 fragments of 16 rows.  The packed buffer is an array of tiles
 // [ceil(N/256)][ksteps]; one tile holds, for its 256 channels and one K step,
 //     16 fragments x 1024 bytes of kept values   (fragment f, lane l: 16 bytes at f*1024 + l*16)
-//   + 16 fragments x 64 lanes of index bits      (4 bytes per lane for int8, 2 for fp16), starting at byte 16384,
+//   + 16 fragments x 64 lanes of index bits      (4 bytes per lane for int8, 2 for fp16), starting at byte 16384
+//     (see index_offset),
 // so that a workgroup fetches a tile with whole 1 KB wavefront-wide copies and a wavefront reads a fragment with one
 // 16-byte and one 4-byte (2-byte) access per lane.
 constexpr int kRowBlock = 64;          // output channels whose fragments interleave (see packed_row_to_channel)
@@ -26,6 +27,14 @@ __host__ __device__ constexpr int step_elems(bool is_i8) { return is_i8 ? 128 : 
 // index bytes of one fragment: 2 bits per kept value; 16 int8 values (32 bits) or 8 fp16 values (16 bits) per lane
 __host__ __device__ constexpr int frag_index_bytes(bool is_i8) { return is_i8 ? 256 : 128; }
 __host__ __device__ constexpr int tile_bytes(bool is_i8) { return kTileValueBytes + 16 * frag_index_bytes(is_i8); }
+// Byte offset, inside a tile, of the index word of lane l of fragment f.  The index words are grouped per half tile
+// (fragments 0..7 / 8..15 = the 128 channels one wavefront of the large-tile kernel owns) and, inside a half, per
+// lane: a lane finds the index words of its 8 fragments in 32 (int8) or 16 (fp16) consecutive bytes and fetches them
+// with two (one) 16-byte LDS reads instead of eight small ones.
+__host__ __device__ constexpr int index_offset(bool is_i8, int f, int l) {
+  const int ib = is_i8 ? 4 : 2;
+  return kTileValueBytes + (f >> 3) * (64 * 8 * ib) + l * (8 * ib) + (f & 7) * ib;
+}
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

@@ -377,11 +377,11 @@ __global__ void __launch_bounds__(256) pack_kernel(const uint8_t* __restrict__ v
   vv.z = v[8] | (v[9] << 8) | (v[10] << 16) | ((uint32_t)v[11] << 24);
   vv.w = v[12] | (v[13] << 8) | (v[14] << 16) | ((uint32_t)v[15] << 24);
   *(uint4*)(t + f * kFragValueBytes + lane * 16) = vv;
-  uint8_t* ip = t + kTileValueBytes + f * frag_index_bytes(IS_I8);
+  uint8_t* ip = t + index_offset(IS_I8, f, lane);
   if constexpr (IS_I8)
-    *(uint32_t*)(ip + lane * 4) = ix[0] | (ix[1] << 8) | (ix[2] << 16) | ((uint32_t)ix[3] << 24);
+    *(uint32_t*)ip = ix[0] | (ix[1] << 8) | (ix[2] << 16) | ((uint32_t)ix[3] << 24);
   else
-    *(uint16_t*)(ip + lane * 2) = (uint16_t)(ix[0] | (ix[1] << 8));
+    *(uint16_t*)ip = (uint16_t)(ix[0] | (ix[1] << 8));
 }
 
 gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, gpusq_dtype dt, int64_t N, int64_t K,
@@ -503,11 +503,11 @@ __global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __res
     const int lane = r + 16 * (int)((k0 % E) / KL);
     uint8_t* tp = packed + (nb * ksteps + ks) * tile_bytes(IS_I8);
     *(uint4*)(tp + f * kFragValueBytes + lane * 16) = vv;
-    uint8_t* ip = tp + kTileValueBytes + f * frag_index_bytes(IS_I8);
+    uint8_t* ip = tp + index_offset(IS_I8, f, lane);
     if constexpr (IS_I8)
-      *(uint32_t*)(ip + lane * 4) = ibytes[0] | (ibytes[1] << 8) | (ibytes[2] << 16) | ((uint32_t)ibytes[3] << 24);
+      *(uint32_t*)ip = ibytes[0] | (ibytes[1] << 8) | (ibytes[2] << 16) | ((uint32_t)ibytes[3] << 24);
     else
-      *(uint16_t*)(ip + lane * 2) = (uint16_t)(ibytes[0] | (ibytes[1] << 8));
+      *(uint16_t*)ip = (uint16_t)(ibytes[0] | (ibytes[1] << 8));
   }
 }
 
@@ -527,11 +527,11 @@ __global__ void __launch_bounds__(256) clear_packed_padding_kernel(uint8_t* __re
   if (n < N && k0 < K) return;  // written by prepare_weights_kernel
   uint8_t* t = packed + tile * tile_bytes(IS_I8);
   *(uint4*)(t + f * kFragValueBytes + lane * 16) = uint4{0, 0, 0, 0};
-  uint8_t* ip = t + kTileValueBytes + f * frag_index_bytes(IS_I8);
+  uint8_t* ip = t + index_offset(IS_I8, f, lane);
   if constexpr (IS_I8)
-    *(uint32_t*)(ip + lane * 4) = 0u;
+    *(uint32_t*)ip = 0u;
   else
-    *(uint16_t*)(ip + lane * IB) = (uint16_t)0;
+    *(uint16_t*)ip = (uint16_t)0;
 }
 
 gpusq_status launch_prepare_weights(const float* W, gpusq_dtype dt, float* Wp, void* Wlow, float* w_scale, void* values,

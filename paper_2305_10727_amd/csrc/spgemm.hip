@@ -58,7 +58,7 @@ __device__ __forceinline__ int xcd_tile(int tiles_total) {
 template <bool IS_I8, int TN, int TM, int GELU = -1, int OUT = -1>
 __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[TN][TM],
                                               const float* cs, const float* bs, int n_tile, int n_wave, int64_t m_wave,
-                                              int lane) {
+                                              int lane, int tm_active = TM) {
   const bool use_gelu = GELU >= 0 ? (GELU != 0) : ((a.epilogue & GPUSQ_EPI_GELU) != 0);
 #pragma unroll
   for (int g = 0; g < TN / 2; ++g) {  // pairs of fragments = 32 channels; this lane holds 8 of them
@@ -72,6 +72,7 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename 
     }
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
+      if (mt >= tm_active) break;
       const int64_t m = m_wave + mt * 16 + (lane & 15);
       float v[8];
       int raw[8];
@@ -97,31 +98,75 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename 
 #define GPUSQ_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define GPUSQ_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-constexpr int kBigBN = 256, kBigBM = 128, kBigTM = 4;
+constexpr int kBigBN = 256, kBigBM = 128, kBigTN = 8, kBigTM = 4;
 constexpr int kXStageBytes = kBigBM * kStepBytes;  // 16 KB: 128 rows x 128 bytes, 16-byte chunks XOR-swizzled per row
 
-// One wavefront's share of the copies that bring K step `ks` into an LDS stage: the 16 KB X slab, 16 fragments of
-// kept values and 4 KB (fp16: 2 KB) of index words are moved in 1 KB pieces dealt round-robin to the NW wavefronts.
-// Each copy instruction moves 64 lanes x 16 bytes from per-lane global addresses to 1 KB of consecutive LDS.
-// The X slab is stored row-major with the 16-byte chunk c of row r at chunk position c ^ ((r >> 1) & 7), so that the
-// 16 rows a quarter-wavefront reads at the same K offset fall in 16 different 16-byte bank groups; the swizzle is
-// applied by choosing which global chunk each lane fetches.
-template <bool IS_I8, int NW>
+// The list of tiles of one launch.  The first `full_tiles` tiles are 256 channels x 128 rows (n fastest); the rows that
+// are left over after the last whole round of tiles over the resident workgroups are cut into shorter tiles of
+// 32*tail_tm rows, so that the last round costs a fraction of a full round instead of a whole one.
+struct TilePlan {
+  int tiles_n;      // 256-channel blocks
+  int full_tiles;   // = full_chunks * tiles_n
+  int full_chunks;  // 128-row chunks covered by full tiles
+  int tail_tm;      // 1..4: a tail tile has 32*tail_tm rows (slabs per wavefront)
+  int total;        // full + tail tiles
+};
+
+struct Tile {
+  int n_blk;
+  int tm;      // 16-row slabs per wavefront (2 wavefronts along m): the tile has 32*tm rows
+  int64_t m0;
+};
+
+// Item i of the list of XCD x: the XCD's share of the full tiles (a contiguous run, so tiles that share an X slab
+// meet in one L2), then its share of the tail tiles.
+__device__ __forceinline__ int xcd_items(const TilePlan& p, int x, int& f0, int& nf, int& t0) {
+  const int tail = p.total - p.full_tiles;
+  f0 = (int)((int64_t)x * p.full_tiles / 8);
+  nf = (int)((int64_t)(x + 1) * p.full_tiles / 8) - f0;
+  t0 = p.full_tiles + (int)((int64_t)x * tail / 8);
+  return nf + (int)((int64_t)(x + 1) * tail / 8) - (int)((int64_t)x * tail / 8);
+}
+
+__device__ __forceinline__ Tile decode_tile(const TilePlan& p, int idx) {
+  Tile t;
+  if (idx < p.full_tiles) {
+    t.n_blk = idx % p.tiles_n;
+    t.m0 = (int64_t)(idx / p.tiles_n) * kBigBM;
+    t.tm = kBigTM;
+  } else {
+    const int j = idx - p.full_tiles;
+    t.n_blk = j % p.tiles_n;
+    t.m0 = (int64_t)p.full_chunks * kBigBM + (int64_t)(j / p.tiles_n) * 32 * p.tail_tm;
+    t.tm = p.tail_tm;
+  }
+  return t;
+}
+
+// One wavefront's share of the copies that bring K step `ks` of a tile into an LDS stage: the X slab (up to 16 KB),
+// 16 fragments of kept values and 4 KB (fp16: 2 KB) of index words are moved in 1 KB pieces dealt round-robin to the
+// 4 wavefronts.  Each copy instruction moves 64 lanes x 16 bytes from per-lane global addresses to 1 KB of
+// consecutive LDS.  The X slab is stored row-major with the 16-byte chunk c of row r at chunk position
+// c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the same K offset fall in 16 different 16-byte
+// bank groups; the swizzle is applied by choosing which global chunk each lane fetches.
+template <bool IS_I8>
 __device__ __forceinline__ void issue_stage_copies(uint8_t* stage, const uint8_t* Xg, const uint8_t* Wtile, int64_t k_bytes,
-                                                   int64_t m0, int M, int ks, int wave, int lane) {
+                                                   const Tile& t, int M, int ks, int wave, int lane) {
 #pragma unroll
-  for (int i = 0; i < 16 / NW; ++i) {
-    const int j = wave + i * NW;           // 1 KB block = 8 rows
-    const int r = 8 * j + (lane >> 3);     // row inside the slab
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    int64_t m = m0 + r;
-    m = m < M ? m : (int64_t)M - 1;        // rows past the end re-read the last row; their results are never stored
-    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Xg + m * k_bytes + (int64_t)ks * kStepBytes + c * 16),
-                                     GPUSQ_LPTR(stage + j * 1024), 16, 0, 0);
+  for (int i = 0; i < 4; ++i) {
+    const int j = wave + i * 4;            // 1 KB block = 8 rows
+    if (j < 4 * t.tm) {                    // the tile has 32*tm rows
+      const int r = 8 * j + (lane >> 3);   // row inside the slab
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      int64_t m = t.m0 + r;
+      m = m < M ? m : (int64_t)M - 1;      // rows past the end re-read the last row; their results are never stored
+      __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Xg + m * k_bytes + (int64_t)ks * kStepBytes + c * 16),
+                                       GPUSQ_LPTR(stage + j * 1024), 16, 0, 0);
+    }
   }
 #pragma unroll
-  for (int i = 0; i < 16 / NW; ++i) {
-    const int f = wave + i * NW;
+  for (int i = 0; i < 4; ++i) {
+    const int f = wave + i * 4;
     __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Wtile + f * kFragValueBytes + lane * 16),
                                      GPUSQ_LPTR(stage + kXStageBytes + f * kFragValueBytes), 16, 0, 0);
   }
@@ -130,59 +175,85 @@ __device__ __forceinline__ void issue_stage_copies(uint8_t* stage, const uint8_t
                                      GPUSQ_LPTR(stage + kXStageBytes + kTileValueBytes + wave * 1024), 16, 0, 0);
 }
 
-// All matrix instructions of one K step for one wavefront (TN*16 n x 64 m): TN fragments of A, 4 slabs of B.
-template <bool IS_I8, int TN>
-__device__ __forceinline__ void compute_stage(const uint8_t* stage, typename AccT<IS_I8>::type (&acc)[TN][kBigTM], int wn,
-                                              int wm, int lane) {
+// All matrix instructions of one K step for one wavefront (128 n x 16*tm m): 8 fragments of A, tm slabs of B.
+template <bool IS_I8>
+__device__ __forceinline__ void compute_stage(const uint8_t* stage, typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM], int wn,
+                                              int wm, int tm, int lane) {
   const uint8_t* Ws = stage + kXStageBytes;
-  const int sw = (lane & 15) >> 1;  // (row >> 1) & 7: tile and wavefront offsets are multiples of 16 rows
+  const int sw = (lane & 15) >> 1;  // (row >> 1) & 7: slab and wavefront offsets are multiples of 16 rows
   const int q = lane >> 4;
-  const uint8_t* xrow = stage + (wm * kBigTM * 16 + (lane & 15)) * kStepBytes;
+  const uint8_t* xrow = stage + (wm * tm * 16 + (lane & 15)) * kStepBytes;
   const uint8_t* xlo = xrow + (q ^ sw) * 16;
   const uint8_t* xhi = xrow + ((4 + q) ^ sw) * 16;
-  const uint8_t* abase = Ws + wn * TN * kFragValueBytes + lane * 16;
-  const uint8_t* ibase = Ws + kTileValueBytes + wn * TN * frag_index_bytes(IS_I8) + lane * (IS_I8 ? 4 : 2);
-  v4i lo = *(const v4i*)xlo, hi = *(const v4i*)xhi;
-  v4i av[TN];
-  int ai[TN];
-#pragma unroll
-  for (int tn = 0; tn < TN; ++tn) {
-    av[tn] = *(const v4i*)(abase + tn * kFragValueBytes);
-    if constexpr (IS_I8)
-      ai[tn] = *(const int*)(ibase + tn * 256);
-    else
-      ai[tn] = (int)*(const uint16_t*)(ibase + tn * 128);
-  }
+  const uint8_t* abase = Ws + wn * kBigTN * kFragValueBytes + lane * 16;
+  const uint8_t* ibase = Ws + index_offset(IS_I8, wn * kBigTN, lane);  // this lane's 8 index words, consecutive
+  // B slabs first, then the A fragments in the order they are consumed: LDS returns data in request order, so the
+  // matrix instructions of fragment 0 can start while the remaining fragments stream in
+  // (a short tail tile still runs all four slabs: the surplus slabs read stale rows of the stage and their
+  // accumulators are never stored; the matrix pipe is not what limits a K step)
+  v8i b[kBigTM];
 #pragma unroll
   for (int mt = 0; mt < kBigTM; ++mt) {
-    const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    if (mt + 1 < kBigTM) {  // next slab of B is requested before this slab's matrix instructions are issued
-      lo = *(const v4i*)(xlo + (mt + 1) * 16 * kStepBytes);
-      hi = *(const v4i*)(xhi + (mt + 1) * 16 * kStepBytes);
-    }
+    const v4i lo = *(const v4i*)(xlo + mt * 16 * kStepBytes), hi = *(const v4i*)(xhi + mt * 16 * kStepBytes);
+    b[mt] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  }
+  int ai[kBigTN];
+  if constexpr (IS_I8) {
+    const v4i i0 = *(const v4i*)ibase, i1 = *(const v4i*)(ibase + 16);
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[tn], b, acc[tn][mt], ai[tn]);
+    for (int j = 0; j < 4; ++j) {
+      ai[j] = i0[j];
+      ai[4 + j] = i1[j];
+    }
+  } else {
+    const v4i i0 = *(const v4i*)ibase;  // 8 x 16 bits
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      ai[2 * j] = i0[j] & 0xFFFF;
+      ai[2 * j + 1] = (int)((unsigned)i0[j] >> 16);
+    }
+  }
+  v4i av[kBigTN];
+#pragma unroll
+  for (int tn = 0; tn < kBigTN; ++tn) av[tn] = *(const v4i*)(abase + tn * kFragValueBytes);
+#pragma unroll
+  for (int tn = 0; tn < kBigTN; ++tn)
+#pragma unroll
+    for (int mt = 0; mt < kBigTM; ++mt) acc[tn][mt] = smfmac<IS_I8>(av[tn], b[mt], acc[tn][mt], ai[tn]);
+  // Issue order within the K step: the 8 reads of B, the index words and the first three A fragments up front, then
+  // four matrix instructions per fragment with the read of the fragment three ahead in between, so that an LDS round
+  // trip is covered by 12 matrix instructions and at most 4 fragments are live.
+  __builtin_amdgcn_sched_group_barrier(0x100, 8 + (IS_I8 ? 2 : 1) + 3, 0);
+#pragma unroll
+  for (int tn = 0; tn < kBigTN; ++tn) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    if (tn + 3 < kBigTN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
   }
 }
 
 // s_waitcnt vmcnt(0) lgkmcnt(0) (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]): the
 // wavefront's own global->LDS copies have landed and its LDS reads of the stage it leaves have returned, so after
 // the barrier that follows every stage may be read, and the stage just left may be overwritten.
-#define GPUSQ_WAIT_COPIES_AND_LDS() __builtin_amdgcn_s_waitcnt(0x0070)
+// The scheduling barrier in front keeps the compiler from hoisting the wait (and the s_barrier after it) above the
+// matrix instructions of the K step, which would expose the copy latency instead of hiding it behind them.
+#define GPUSQ_WAIT_COPIES_AND_LDS()       \
+  do {                                    \
+    __builtin_amdgcn_sched_barrier(0);    \
+    __builtin_amdgcn_s_waitcnt(0x0070);   \
+  } while (0)
 
-// TN = 8: 4 wavefronts (2 x 2), 128 n x 64 m each, 2 wavefronts per SIMD.  TN = 4: 8 wavefronts (4 x 2), 64 n x 64 m
-// each, 4 wavefronts per SIMD.  Two workgroups per CU in both cases.
+// Workgroup = 4 wavefronts (2 along n x 2 along m), 128 channels x 64 rows each, 128 accumulator registers, two
+// wavefronts per SIMD = two workgroups per CU (the LDS footprint, 2 stages of 36 KB, allows no more).
 //
-// Persistent: the grid holds (at most) two workgroups per CU and every workgroup walks over tiles with a fixed
-// stride, so the output stores of one tile drain while the next tile is being computed, and the two workgroups of a
-// CU drift out of phase (one in its VALU/store epilogue while the other owns the matrix pipe).
-// Tile order: workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x takes the contiguous
-// run of tiles [x*per_xcd, (x+1)*per_xcd) and its workgroups take them in order; tiles that share an X slab (same m
-// block, n fastest) are then computed close in time on one L2.
-template <bool IS_I8, int GELU, int OUT, int TN>
-__global__ void __launch_bounds__(2048 / TN, TN == 8 ? 2 : 4) spgemm_tile_kernel(const GemmArgs a, const int tiles_n, const int tiles_total) {
+// Persistent: the grid holds two workgroups per CU and every workgroup walks over tiles with a fixed stride, so the
+// output stores of one tile drain while the next tile is being computed; the first K step of the next tile is
+// requested before the epilogue of the current one starts, which hides its latency behind the epilogue.
+// Tile order: workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2); XCD x takes an eighth of the
+// full tiles as one contiguous run plus an eighth of the tail tiles, and its workgroups take them in order, so tiles
+// that share an X slab (same rows, n fastest) are computed close in time on one L2.
+template <bool IS_I8, int GELU, int OUT>
+__global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, const TilePlan plan) {
   typedef typename AccT<IS_I8>::type acc_t;
-  constexpr int WNB = 16 / TN, NW = 2 * WNB;
   constexpr int ES = IS_I8 ? 1 : 2;
   constexpr int STAGE = kXStageBytes + tile_bytes(IS_I8);
   __shared__ __attribute__((aligned(1024))) uint8_t S0[STAGE];
@@ -191,48 +262,60 @@ __global__ void __launch_bounds__(2048 / TN, TN == 8 ? 2 : 4) spgemm_tile_kernel
   __shared__ __attribute__((aligned(16))) float bs[kBigBN];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wn = wave % WNB, wm = wave / WNB;
+  const int wn = wave & 1, wm = wave >> 1;
   const int64_t k_bytes = (int64_t)a.K * ES;
   const int ksteps = (int)(k_bytes / kStepBytes);
   const uint8_t* Xg = (const uint8_t*)a.X;
-  const int per_xcd = (tiles_total + 7) / 8;
+  const uint8_t* Wg = (const uint8_t*)a.W;
+  const int64_t w_col_bytes = (int64_t)ksteps * tile_bytes(IS_I8);  // packed bytes of one 256-channel block
   const int xcd = (int)(blockIdx.x & 7), wgs_per_xcd = (int)(gridDim.x >> 3);
-  const int tile_end = min((xcd + 1) * per_xcd, tiles_total);
+  int f0, nf, t0;
+  const int items = xcd_items(plan, xcd, f0, nf, t0);
+  int item = (int)(blockIdx.x >> 3);
+  if (item >= items) return;
+  Tile t = decode_tile(plan, item < nf ? f0 + item : t0 + item - nf);
+  issue_stage_copies<IS_I8>(S0, Xg, Wg + t.n_blk * w_col_bytes, k_bytes, t, a.M, 0, wave, lane);
+  ChannelParams prm;
+  prm.fetch<IS_I8>(a, t.n_blk * kBigBN + tid);
 
-  for (int tile = xcd * per_xcd + (int)(blockIdx.x >> 3); tile < tile_end; tile += wgs_per_xcd) {
-    const int n_blk = tile % tiles_n, m_blk = tile / tiles_n;
-    const uint8_t* Wt = (const uint8_t*)a.W + (int64_t)n_blk * ksteps * tile_bytes(IS_I8);
-    const int64_t m0 = (int64_t)m_blk * kBigBM;
-
-    // both stages are free here: the previous tile's last reads of them completed before its final barrier
-    issue_stage_copies<IS_I8, NW>(S0, Xg, Wt, k_bytes, m0, a.M, 0, wave, lane);
-    ChannelParams prm;
-    if (tid < kBigBN) prm.fetch<IS_I8>(a, n_blk * kBigBN + tid);
-
-    acc_t acc[TN][kBigTM];
+  while (true) {
+    const uint8_t* Wt = Wg + t.n_blk * w_col_bytes;
+    acc_t acc[kBigTN][kBigTM];
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int i = 0; i < kBigTN; ++i)
 #pragma unroll
       for (int j = 0; j < kBigTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
 
-    GPUSQ_WAIT_COPIES_AND_LDS();  // also: the previous tile's epilogue reads of cs/bs have returned
+    GPUSQ_WAIT_COPIES_AND_LDS();  // stage 0 of this tile has landed; the previous tile's reads of cs/bs have returned
     __builtin_amdgcn_s_barrier();
-    if (tid < kBigBN) prm.publish(cs, bs, tid);  // read only after the barriers of the main loop
+    prm.publish(cs, bs, tid);     // read in the epilogue, after the barriers of the main loop
     for (int ks = 0; ks < ksteps; ks += 2) {
       // stage 1 was last read before the barrier that ended the previous trip, so it may be overwritten now
-      if (ks + 1 < ksteps) issue_stage_copies<IS_I8, NW>(S1, Xg, Wt + (int64_t)(ks + 1) * tile_bytes(IS_I8), k_bytes, m0, a.M, ks + 1, wave, lane);
-      compute_stage<IS_I8, TN>(S0, acc, wn, wm, lane);
+      if (ks + 1 < ksteps) issue_stage_copies<IS_I8>(S1, Xg, Wt + (int64_t)(ks + 1) * tile_bytes(IS_I8), k_bytes, t, a.M, ks + 1, wave, lane);
+      compute_stage<IS_I8>(S0, acc, wn, wm, t.tm, lane);
       GPUSQ_WAIT_COPIES_AND_LDS();
       __builtin_amdgcn_s_barrier();
       if (ks + 1 < ksteps) {
-        if (ks + 2 < ksteps) issue_stage_copies<IS_I8, NW>(S0, Xg, Wt + (int64_t)(ks + 2) * tile_bytes(IS_I8), k_bytes, m0, a.M, ks + 2, wave, lane);
-        compute_stage<IS_I8, TN>(S1, acc, wn, wm, lane);
+        if (ks + 2 < ksteps) issue_stage_copies<IS_I8>(S0, Xg, Wt + (int64_t)(ks + 2) * tile_bytes(IS_I8), k_bytes, t, a.M, ks + 2, wave, lane);
+        compute_stage<IS_I8>(S1, acc, wn, wm, t.tm, lane);
         GPUSQ_WAIT_COPIES_AND_LDS();
         __builtin_amdgcn_s_barrier();
       }
     }
-    wave_epilogue<IS_I8, TN, kBigTM, GELU, OUT>(a, acc, cs, bs, n_blk * kBigBN, n_blk * kBigBN + wn * TN * 16,
-                                                m0 + wm * kBigTM * 16, lane);
+    // both stages are free now (every wavefront passed the last barrier after its last reads): request the first
+    // K step of the next tile before the epilogue
+    const int cur_n = t.n_blk, cur_tm = t.tm;
+    const int64_t cur_m0 = t.m0;
+    item += wgs_per_xcd;
+    const bool more = item < items;
+    if (more) {
+      t = decode_tile(plan, item < nf ? f0 + item : t0 + item - nf);
+      issue_stage_copies<IS_I8>(S0, Xg, Wg + t.n_blk * w_col_bytes, k_bytes, t, a.M, 0, wave, lane);
+      prm.fetch<IS_I8>(a, t.n_blk * kBigBN + tid);
+    }
+    wave_epilogue<IS_I8, kBigTN, kBigTM, GELU, OUT>(a, acc, cs, bs, cur_n * kBigBN, cur_n * kBigBN + wn * kBigTN * 16,
+                                                    cur_m0 + wm * cur_tm * 16, lane, cur_tm);
+    if (!more) break;
   }
 }
 
@@ -248,7 +331,6 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   typedef typename AccT<IS_I8>::type acc_t;
   constexpr int BN = WN * TN * 16, BM = WM * TM * 16;
   constexpr int ES = IS_I8 ? 1 : 2;
-  constexpr int IB = frag_index_bytes(IS_I8);
   constexpr int XCH = BM / 32;  // 16-byte chunks of the X slab each thread moves per K step
 
   __shared__ __attribute__((aligned(16))) uint8_t Xs[2][BM * kLdsRow];
@@ -310,9 +392,9 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
         const int f = (rb & 3) * 4 + (tn & 3);
         av[slot][tn] = *(const v4i*)(t + f * kFragValueBytes + lane * 16);
         if constexpr (IS_I8)
-          ai[slot][tn] = *(const int*)(t + kTileValueBytes + f * IB + lane * 4);
+          ai[slot][tn] = *(const int*)(t + index_offset(true, f, lane));
         else
-          ai[slot][tn] = (int)*(const uint16_t*)(t + kTileValueBytes + f * IB + lane * 2);
+          ai[slot][tn] = (int)*(const uint16_t*)(t + index_offset(false, f, lane));
       } else {
         av[slot][tn] = v4i{0, 0, 0, 0};
         ai[slot][tn] = 0;
@@ -368,10 +450,30 @@ static int num_cus() {
   return cus;
 }
 
-#ifndef GPUSQ_TILE_TN
-#define GPUSQ_TILE_TN 8
-#endif
-constexpr int kTileTN = GPUSQ_TILE_TN;
+// Full 128-row tiles for as many whole rounds over the resident workgroups as the problem has; the remaining rows in
+// shorter tiles, as tall as still fits them in one more round.
+static TilePlan make_plan(int M, int N, int resident) {
+  TilePlan p;
+  p.tiles_n = (int)ceil_div(N, kBigBN);
+  const int chunks = (int)ceil_div(M, kBigBM);
+  const int all_tiles = chunks * p.tiles_n;
+  int full_chunks = chunks;
+  if (all_tiles > resident && all_tiles % resident != 0) full_chunks = (all_tiles / resident) * resident / p.tiles_n;
+  p.full_chunks = full_chunks;
+  p.full_tiles = full_chunks * p.tiles_n;
+  const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * kBigBM;
+  p.tail_tm = kBigTM;
+  int tail_tiles = 0;
+  if (rows_left > 0) {
+    for (int tm = kBigTM; tm >= 1; --tm) {
+      p.tail_tm = tm;
+      tail_tiles = (int)ceil_div(rows_left, 32 * tm) * p.tiles_n;
+      if (tm > 1 && (int)ceil_div(rows_left, 32 * (tm - 1)) * p.tiles_n > resident) break;  // a shorter tile would need a second round
+    }
+  }
+  p.total = p.full_tiles + tail_tiles;
+  return p;
+}
 
 template <bool IS_I8>
 static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
@@ -379,28 +481,27 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
   if (work <= (int64_t)256 * 1024) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
   if (k_bytes % kStepBytes != 0) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);    // ragged K: zero-filling path
-  const int tiles_n = (int)ceil_div(a.N, kBigBN), tiles_m = (int)ceil_div(a.M, kBigBM);
-  const int total = tiles_n * tiles_m;
   // persistent grid: two workgroups per CU (the LDS footprint allows no more), never more workgroups than tiles
   const int resident = 2 * num_cus();
-  const dim3 grid((unsigned)(ceil_div(total < resident ? total : resident, 8) * 8));
+  const TilePlan plan = make_plan(a.M, a.N, resident);
+  const dim3 grid((unsigned)(ceil_div(plan.total < resident ? plan.total : resident, 8) * 8));
   const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
   if constexpr (IS_I8) {
     if (a.out_dt == GPUSQ_I32)
-      spgemm_tile_kernel<true, 0, GPUSQ_I32, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<true, 0, GPUSQ_I32><<<grid, 256, 0, s>>>(a, plan);
     else if (a.out_dt == GPUSQ_I8 && gelu)
-      spgemm_tile_kernel<true, 1, GPUSQ_I8, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<true, 1, GPUSQ_I8><<<grid, 256, 0, s>>>(a, plan);
     else if (a.out_dt == GPUSQ_I8)
-      spgemm_tile_kernel<true, 0, GPUSQ_I8, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<true, 0, GPUSQ_I8><<<grid, 256, 0, s>>>(a, plan);
     else if (gelu)
-      spgemm_tile_kernel<true, 1, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<true, 1, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
     else
-      spgemm_tile_kernel<true, 0, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<true, 0, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
   } else {
     if (gelu)
-      spgemm_tile_kernel<false, 1, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<false, 1, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
     else
-      spgemm_tile_kernel<false, 0, GPUSQ_F16, kTileTN><<<grid, 2048 / kTileTN, 0, s>>>(a, tiles_n, total);
+      spgemm_tile_kernel<false, 0, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
   }
   return check_launch();
 }
