@@ -149,30 +149,40 @@ __device__ __forceinline__ Tile decode_tile(const TilePlan& p, int idx) {
 // consecutive LDS.  The X slab is stored row-major with the 16-byte chunk c of row r at chunk position
 // c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the same K offset fall in 16 different 16-byte
 // bank groups; the swizzle is applied by choosing which global chunk each lane fetches.
+// Addresses are a wavefront-uniform 64-bit base (scalar registers, advanced per K step by scalar adds) plus a 32-bit
+// per-lane offset fixed for the whole tile (`xoff`), so a K step costs no vector ALU work for addressing.
 template <bool IS_I8>
-__device__ __forceinline__ void issue_stage_copies(uint8_t* stage, const uint8_t* Xg, const uint8_t* Wtile, int64_t k_bytes,
-                                                   const Tile& t, int M, int ks, int wave, int lane) {
+__device__ __forceinline__ void issue_stage_copies(uint8_t* stage, const uint8_t* Xtile_ks, const uint8_t* Wtile,
+                                                   const uint32_t (&xoff)[4], int tm, int wave, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int j = wave + i * 4;            // 1 KB block = 8 rows
-    if (j < 4 * t.tm) {                    // the tile has 32*tm rows
-      const int r = 8 * j + (lane >> 3);   // row inside the slab
-      const int c = (lane & 7) ^ ((r >> 1) & 7);
-      int64_t m = t.m0 + r;
-      m = m < M ? m : (int64_t)M - 1;      // rows past the end re-read the last row; their results are never stored
-      __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Xg + m * k_bytes + (int64_t)ks * kStepBytes + c * 16),
-                                       GPUSQ_LPTR(stage + j * 1024), 16, 0, 0);
-    }
+    const int j = wave + i * 4;  // 1 KB block = 8 rows; the tile has 32*tm rows
+    if (j < 4 * tm)
+      __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Xtile_ks + xoff[i]), GPUSQ_LPTR(stage + j * 1024), 16, 0, 0);
   }
+  const uint8_t* wsrc = Wtile + wave * kFragValueBytes;
+  uint8_t* wdst = stage + kXStageBytes + wave * kFragValueBytes;
+  const uint32_t loff = (uint32_t)lane * 16;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int f = wave + i * 4;
-    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Wtile + f * kFragValueBytes + lane * 16),
-                                     GPUSQ_LPTR(stage + kXStageBytes + f * kFragValueBytes), 16, 0, 0);
-  }
+  for (int i = 0; i < 4; ++i)
+    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(wsrc + i * 4 * kFragValueBytes + loff), GPUSQ_LPTR(wdst + i * 4 * kFragValueBytes),
+                                     16, 0, 0);
   if (wave < (IS_I8 ? 4 : 2))
-    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Wtile + kTileValueBytes + wave * 1024 + lane * 16),
-                                     GPUSQ_LPTR(stage + kXStageBytes + kTileValueBytes + wave * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(wsrc + kTileValueBytes + loff), GPUSQ_LPTR(wdst + kTileValueBytes), 16, 0, 0);
+}
+
+// Per-lane byte offsets, relative to the tile's first row, of the four X blocks this wavefront copies per K step:
+// block j = wave + 4i holds rows 8j..8j+7; lane l fetches row 8j + l/8, chunk (l%8) ^ ((row >> 1) & 7).  Rows past the
+// end of X re-read the last row (their results are never stored).
+__device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], const Tile& t, int M, int64_t k_bytes, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 8 * (wave + i * 4) + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const int64_t last = (int64_t)M - 1 - t.m0;  // >= 0: a tile starts inside X
+    const int64_t rr = r < last ? r : last;
+    xoff[i] = (uint32_t)(rr * k_bytes + c * 16);
+  }
 }
 
 // All matrix instructions of one K step for one wavefront (128 n x 16*tm m): 8 fragments of A, tm slabs of B.
@@ -261,7 +271,8 @@ __global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, c
   __shared__ __attribute__((aligned(16))) float cs[kBigBN];
   __shared__ __attribute__((aligned(16))) float bs[kBigBN];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps wave-derived addresses in scalar registers
   const int wn = wave & 1, wm = wave >> 1;
   const int64_t k_bytes = (int64_t)a.K * ES;
   const int ksteps = (int)(k_bytes / kStepBytes);
@@ -271,15 +282,28 @@ __global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, c
   const int xcd = (int)(blockIdx.x & 7), wgs_per_xcd = (int)(gridDim.x >> 3);
   int f0, nf, t0;
   const int items = xcd_items(plan, xcd, f0, nf, t0);
-  int item = (int)(blockIdx.x >> 3);
-  if (item >= items) return;
-  Tile t = decode_tile(plan, item < nf ? f0 + item : t0 + item - nf);
-  issue_stage_copies<IS_I8>(S0, Xg, Wg + t.n_blk * w_col_bytes, k_bytes, t, a.M, 0, wave, lane);
+  // A workgroup first takes its tail tiles, then its full tiles, and the tail tiles go preferably to the second
+  // workgroup of each CU (local ids wgs/2 .. wgs-1): the two workgroups that share a CU then run about half a tile out
+  // of phase, so that one is in its store/VALU epilogue while the other is in its matrix-instruction loop.
+  const int wl = (int)(blockIdx.x >> 3);
+  const int nt = items - nf;
+  const int tl = (wl + wgs_per_xcd - (wgs_per_xcd >> 1)) % wgs_per_xcd;  // position in the tail hand-out order
+  const int my_tail = tl < nt ? (nt - tl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
+  const int my_full = wl < nf ? (nf - wl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
+  const int my_items = my_tail + my_full;
+  if (my_items == 0) return;
+  int it = 0;
+  auto tile_of = [&](int i) { return i < my_tail ? t0 + tl + i * wgs_per_xcd : f0 + wl + (i - my_tail) * wgs_per_xcd; };
+  Tile t = decode_tile(plan, tile_of(0));
+  uint32_t xoff[4];
+  tile_x_offsets(xoff, t, a.M, k_bytes, wave, lane);
+  issue_stage_copies<IS_I8>(S0, Xg + t.m0 * k_bytes, Wg + t.n_blk * w_col_bytes, xoff, t.tm, wave, lane);
   ChannelParams prm;
   prm.fetch<IS_I8>(a, t.n_blk * kBigBN + tid);
 
   while (true) {
     const uint8_t* Wt = Wg + t.n_blk * w_col_bytes;
+    const uint8_t* Xt = Xg + t.m0 * k_bytes;
     acc_t acc[kBigTN][kBigTM];
 #pragma unroll
     for (int i = 0; i < kBigTN; ++i)
@@ -291,12 +315,12 @@ __global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, c
     prm.publish(cs, bs, tid);     // read in the epilogue, after the barriers of the main loop
     for (int ks = 0; ks < ksteps; ks += 2) {
       // stage 1 was last read before the barrier that ended the previous trip, so it may be overwritten now
-      if (ks + 1 < ksteps) issue_stage_copies<IS_I8>(S1, Xg, Wt + (int64_t)(ks + 1) * tile_bytes(IS_I8), k_bytes, t, a.M, ks + 1, wave, lane);
+      if (ks + 1 < ksteps) issue_stage_copies<IS_I8>(S1, Xt + (int64_t)(ks + 1) * kStepBytes, Wt + (int64_t)(ks + 1) * tile_bytes(IS_I8), xoff, t.tm, wave, lane);
       compute_stage<IS_I8>(S0, acc, wn, wm, t.tm, lane);
       GPUSQ_WAIT_COPIES_AND_LDS();
       __builtin_amdgcn_s_barrier();
       if (ks + 1 < ksteps) {
-        if (ks + 2 < ksteps) issue_stage_copies<IS_I8>(S0, Xg, Wt + (int64_t)(ks + 2) * tile_bytes(IS_I8), k_bytes, t, a.M, ks + 2, wave, lane);
+        if (ks + 2 < ksteps) issue_stage_copies<IS_I8>(S0, Xt + (int64_t)(ks + 2) * kStepBytes, Wt + (int64_t)(ks + 2) * tile_bytes(IS_I8), xoff, t.tm, wave, lane);
         compute_stage<IS_I8>(S1, acc, wn, wm, t.tm, lane);
         GPUSQ_WAIT_COPIES_AND_LDS();
         __builtin_amdgcn_s_barrier();
@@ -306,11 +330,12 @@ __global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, c
     // K step of the next tile before the epilogue
     const int cur_n = t.n_blk, cur_tm = t.tm;
     const int64_t cur_m0 = t.m0;
-    item += wgs_per_xcd;
-    const bool more = item < items;
+    ++it;
+    const bool more = it < my_items;
     if (more) {
-      t = decode_tile(plan, item < nf ? f0 + item : t0 + item - nf);
-      issue_stage_copies<IS_I8>(S0, Xg, Wg + t.n_blk * w_col_bytes, k_bytes, t, a.M, 0, wave, lane);
+      t = decode_tile(plan, tile_of(it));
+      tile_x_offsets(xoff, t, a.M, k_bytes, wave, lane);
+      issue_stage_copies<IS_I8>(S0, Xg + t.m0 * k_bytes, Wg + t.n_blk * w_col_bytes, xoff, t.tm, wave, lane);
       prm.fetch<IS_I8>(a, t.n_blk * kBigBN + tid);
     }
     wave_epilogue<IS_I8, kBigTN, kBigTM, GELU, OUT>(a, acc, cs, bs, cur_n * kBigBN, cur_n * kBigBN + wn * kBigTN * 16,
