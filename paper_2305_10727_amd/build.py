@@ -11,7 +11,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
     # packed-fp32 instructions are kept out of the generated code on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-value",
+    "-Wall", "-Wno-unused-value", "-Wno-inline-asm",
 ]
 
 

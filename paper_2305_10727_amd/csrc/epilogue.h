@@ -9,21 +9,45 @@ typedef int ep_v2i __attribute__((ext_vector_type(2)));
 typedef _Float16 ep_v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 ep_v4h __attribute__((ext_vector_type(4)));
 
-// Exact-erf GELU, GELU(x) = x * Phi(x), evaluated as  max(x, 0) - t * Phi(-t),  t = min(|x|, 6.5), with
-// Phi(-t) = 2^P(t) and P a degree-5 polynomial fitted to log2 Phi(-t) on [0, 6.5] (weighted so that the result is
-// within 0.15 fp16 ulp of the exact value everywhere, including the negative tail down to fp16 subnormals).
-// One transcendental (v_exp_f32) and eight full-rate VALU operations per element: the fp32 epilogue of a GEMM
-// whose output is written in fp16 is VALU-limited on this chip, so the library erf (dozens of operations) is not
-// an option.  For t > 6.5 the subtracted term is below 3e-10.  NaN inputs give 0.
+// Exact-erf GELU, GELU(x) = x * Phi(x), evaluated as  max(x, 0) - t * Phi(-t),  t = |x|, with Phi(-t) = 2^P(t) and P a
+// degree-5 polynomial fitted to log2 Phi(-t) on [0, 6.5] (weighted so that the result is within 0.15 fp16 ulp of the
+// exact value everywhere, including the negative tail down to fp16 subnormals).  Beyond 6.5 P keeps falling
+// monotonically (to -inf for large t), so the subtracted term stays below 3e-10 there and no clamp of t is needed
+// for finite x; x = +-inf gives NaN.
+// One transcendental (v_exp_f32) and eight full-rate VALU operations per element: the fp32 epilogue of a GEMM whose
+// output is written in fp16 is VALU-limited on this chip, so the library erf (dozens of operations) is not an option.
+constexpr float kGeluP5 = -0.0003336848458275199f, kGeluP4 = 0.005954924505203962f, kGeluP3 = -0.04866418614983559f,
+                kGeluP2 = -0.46354809403419495f, kGeluP1 = -1.149438738822937f, kGeluP0 = -1.0001022815704346f;
+
 __device__ __forceinline__ float gelu_f32(float x) {
-  const float t = fminf(fabsf(x), 6.5f);
-  float p = __fmaf_rn(t, -0.0003336848458275199f, 0.005954924505203962f);
-  p = __fmaf_rn(p, t, -0.04866418614983559f);
-  p = __fmaf_rn(p, t, -0.46354809403419495f);
-  p = __fmaf_rn(p, t, -1.149438738822937f);
-  p = __fmaf_rn(p, t, -1.0001022815704346f);
+  const float t = fabsf(x);
+  float p = __fmaf_rn(t, kGeluP5, kGeluP4);
+  p = __fmaf_rn(p, t, kGeluP3);
+  p = __fmaf_rn(p, t, kGeluP2);
+  p = __fmaf_rn(p, t, kGeluP1);
+  p = __fmaf_rn(p, t, kGeluP0);
   const float q = __builtin_amdgcn_exp2f(p);
   return __fmaf_rn(-t, q, fmaxf(x, 0.0f));
+}
+
+// The same function on 8 values at once, written stage by stage so that the 8 dependency chains interleave: a lone
+// wavefront on a SIMD then issues an independent instruction every cycle instead of waiting on each result.
+__device__ __forceinline__ void gelu_f32_x8(float (&v)[8]) {
+  float p[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(fabsf(v[j]), kGeluP5, kGeluP4);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP3);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP2);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP1);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP0);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(p[j]);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(-fabsf(v[j]), p[j], fmaxf(v[j], 0.0f));
 }
 
 // q = clamp(rint(v / s), -127, 127): the same IEEE division + round-half-even as the quantiser of the activations

@@ -19,6 +19,8 @@
 //                       (no staging registers), two LDS stages, two workgroups per CU so that one workgroup's
 //                       epilogue (VALU + stores) overlaps the other's matrix instructions.  Needs K*elemsize % 128 == 0.
 //   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
+#include <stdlib.h>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -344,6 +346,268 @@ __global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, c
   }
 }
 
+// ------------------------------------------------------------------------------------------------ two-team kernel
+// Direct global->LDS copies issued through inline assembly: 64 lanes x 16 (4) bytes from `gbase` (wavefront-uniform,
+// scalar registers) + `voff` (per lane, unsigned 32 bits) to LDS bytes [lds, lds + 1024 (256)), lane l at lds + 16l
+// (4l).  The LDS base travels in M0.  Issued this way the copies are invisible to the compiler's wait-count
+// bookkeeping, so the only waits on them are the explicit s_waitcnt instructions of the kernel: the compiler would
+// otherwise put a full vmcnt(0) in front of every LDS read that might alias a copy in flight.
+__device__ __forceinline__ void copy16_to_lds(const void* gbase, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+__device__ __forceinline__ void copy4_to_lds(const void* gbase, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t*)p;
+}
+
+constexpr int kRing = 4;            // LDS stages: the K step being read plus three in flight
+constexpr int kCopiesPerStep = 9;   // copy instructions every wavefront of the computing team issues per K step
+
+// One wavefront's share (a quarter) of the copies of one K step of a tile into the LDS stage at `stage_lds`: four
+// 1 KB blocks of the X slab (block j = w + 4i holds rows 8j..8j+7, chunks swizzled as described above
+// issue_stage_copies), four fragments of kept values and 1 KB of index words.  Always exactly kCopiesPerStep
+// instructions, whatever the tile: a short tail tile copies rows it does not use, and on the fp16 path (2 KB of
+// index words) wavefronts 2 and 3 repeat the copies of wavefronts 0 and 1, so that the waits can count instructions.
+template <bool IS_I8>
+__device__ __forceinline__ void issue_step_copies(uint32_t stage_lds, const uint8_t* Xks, const uint8_t* Wks,
+                                                  const uint32_t (&xoff)[4], int w, uint32_t loff) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) copy16_to_lds(Xks, xoff[i], stage_lds + (uint32_t)(w + 4 * i) * 1024u);
+  const uint8_t* wsrc = Wks + w * kFragValueBytes;
+  const uint32_t wdst = stage_lds + kXStageBytes + (uint32_t)w * kFragValueBytes;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) copy16_to_lds(wsrc + i * 4 * kFragValueBytes, loff, wdst + (uint32_t)i * 4 * kFragValueBytes);
+  const int iw = IS_I8 ? w : (w & 1);
+  copy16_to_lds(Wks + kTileValueBytes + iw * 1024, loff, stage_lds + kXStageBytes + kTileValueBytes + (uint32_t)iw * 1024u);
+}
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int kWaitVm0 = 0x0F70;            // vmcnt(0)
+constexpr int kWaitVm0Lgkm0 = 0x0070;       // vmcnt(0) lgkmcnt(0)
+constexpr int kWaitVm18Lgkm0 = 0x4072;      // vmcnt(2 * kCopiesPerStep) lgkmcnt(0)
+static_assert(2 * kCopiesPerStep == 18, "kWaitVm18Lgkm0 encodes two K steps of copies");
+
+// Workgroup-wide barrier preceded by a scheduling barrier (the compiler must not move it above the matrix
+// instructions of the K step) and followed by a compiler-level memory barrier (no LDS read moves above it).
+#define GPUSQ_TEAM_BARRIER()              \
+  do {                                    \
+    __builtin_amdgcn_sched_barrier(0);    \
+    __builtin_amdgcn_s_barrier();         \
+    asm volatile("" ::: "memory");        \
+  } while (0)
+
+// Epilogue of one wavefront of the team that is not computing: same lane -> output mapping as wave_epilogue, with
+//  * the per-channel constants read from the wavefront's own LDS array `p` (128 weight scales, then 128 biases),
+//  * `ksteps` workgroup barriers spread evenly over the 16 batches of 8 outputs per lane, so that this team stays in
+//    step with the K steps of the team that is computing (both execute the same number of barriers per phase),
+//  * a wait for the wavefront's own outstanding copies (requested for the other team's next tile) after the first
+//    batch of arithmetic and before the first store and the first barrier: from then on this wavefront has stores in
+//    flight and never waits on the vector-memory counter again until its next compute phase.
+template <bool IS_I8, int GELU, int OUT>
+__device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM],
+                                              const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active,
+                                              int ksteps) {
+  constexpr bool RAW = IS_I8 && OUT == GPUSQ_I32;
+  int done = 0;
+#pragma unroll
+  for (int g = 0; g < kBigTN / 2; ++g) {
+    const int nl = (g >> 1) * kRowBlock + (g & 1) * 32 + (lane >> 4) * 8;  // channel relative to n_wave
+    float c8[8], b8[8];
+    if constexpr (!RAW) {
+#pragma unroll
+      for (int j = 0; j < 8; j += 4) {
+        const float4 bb = *(const float4*)(p + 128 + nl + j);
+        b8[j] = bb.x; b8[j + 1] = bb.y; b8[j + 2] = bb.z; b8[j + 3] = bb.w;
+        if constexpr (IS_I8) {
+          const float4 cc = *(const float4*)(p + nl + j);
+          c8[j] = s_a * cc.x; c8[j + 1] = s_a * cc.y; c8[j + 2] = s_a * cc.z; c8[j + 3] = s_a * cc.w;
+        } else {
+          c8[j] = c8[j + 1] = c8[j + 2] = c8[j + 3] = 1.0f;
+        }
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < kBigTM; ++mt) {
+      const int batch = g * kBigTM + mt;
+      if (mt < tm_active) {
+        const int64_t m = m_wave + mt * 16 + (lane & 15);
+        float v[8];
+        int raw[8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int j = 4 * t + r;
+            if constexpr (IS_I8) {
+              raw[j] = acc[2 * g + t][mt][r];
+              v[j] = RAW ? 0.0f : __fmaf_rn((float)raw[j], c8[j], b8[j]);
+            } else {
+              raw[j] = 0;
+              v[j] = acc[2 * g + t][mt][r] + b8[j];
+            }
+          }
+        if constexpr (GELU != 0) gelu_f32_x8(v);
+        if (batch == 0) {
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_waitcnt(kWaitVm0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (m < a.M) store_8<IS_I8, OUT>(a, m, n_wave + nl, v, raw);
+      }
+      const int target = ((batch + 1) * ksteps) >> 4;
+      while (done < target) {
+        GPUSQ_TEAM_BARRIER();
+        ++done;
+      }
+    }
+  }
+}
+
+// Workgroup = 8 wavefronts = two teams of 4 (2 along n x 2 along m, 128 channels x 64 rows each, as in the kernel
+// above), one workgroup per CU; wavefronts 0-3 and 4-7 land on the four SIMDs once each, so every SIMD hosts one
+// wavefront of each team.  The workgroup walks over its tiles; team (i mod 2) computes tile i.  Time is cut into
+// phases of `ksteps` workgroup barriers: in phase i one team runs the K loop of tile i (matrix instructions, LDS
+// reads, copy requests) while the other runs the epilogue of tile i-1 (vector ALU, stores), then they swap.  The
+// epilogue's arithmetic and the output stores therefore always overlap matrix work on the same SIMD, the computing
+// team has all four LDS stages (copies run three K steps ahead, across tile boundaries), and because loads and stores
+// are issued by different wavefronts in any phase, waiting for copies never means waiting for stores.
+//
+// Copy protocol.  K steps are numbered g = 0, 1, ... over the whole sequence of tiles; step g lives in stage g mod 4.
+// The wavefronts of the team that computes step g request step g+3 first (stage (g+3) mod 4 was last read in step
+// g-1, which every wavefront left through a barrier after its LDS reads had returned), then run step g, then wait
+// until at most the copies of steps g+2 and g+3 are outstanding (vmcnt counts instructions, and every wavefront
+// issues kCopiesPerStep per step), then meet at the barrier.  So when step g+1 starts, its data has landed, provided
+// it was requested by this team; if it was requested by the other team (the first steps of a tile), that team has
+// waited for all its copies before the first barrier of its epilogue phase (see team_epilogue), which is earlier.
+// When nothing is requested in a step (the last steps of the last tile) the wait is for all copies.
+// Every wavefront executes exactly 1 + (tiles + 1) * ksteps barriers.
+template <bool IS_I8, int GELU, int OUT>
+__global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, const TilePlan plan) {
+  typedef typename AccT<IS_I8>::type acc_t;
+  constexpr int ES = IS_I8 ? 1 : 2;
+  constexpr int STAGE = kXStageBytes + tile_bytes(IS_I8);
+  constexpr bool RAW = IS_I8 && OUT == GPUSQ_I32;
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[kRing * STAGE];
+  __shared__ __attribute__((aligned(1024))) float prm[8][256];  // per wavefront: 128 weight scales, 128 biases
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int team = wave >> 2, w = wave & 3, wn = w & 1, wm = w >> 1;
+  const int64_t k_bytes = (int64_t)a.K * ES;
+  const int ksteps = (int)(k_bytes / kStepBytes);
+  const uint8_t* Xg = (const uint8_t*)a.X;
+  const uint8_t* Wg = (const uint8_t*)a.W;
+  const int64_t w_col_bytes = (int64_t)ksteps * tile_bytes(IS_I8);
+  const int xcd = (int)(blockIdx.x & 7), wgs_per_xcd = (int)(gridDim.x >> 3), wl = (int)(blockIdx.x >> 3);
+  int f0, nf, t0;
+  const int items = xcd_items(plan, xcd, f0, nf, t0);
+  const int my_items = wl < items ? (items - wl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
+  if (my_items == 0) return;  // the whole workgroup leaves before any barrier
+  auto tile_of = [&](int i) {
+    const int it = wl + i * wgs_per_xcd;
+    return decode_tile(plan, it < nf ? f0 + it : t0 + it - nf);
+  };
+  const bool has_bias = !RAW && (a.epilogue & GPUSQ_EPI_BIAS) != 0;
+  const float s_a = (IS_I8 && !RAW) ? a.act_scale[0] : 1.0f;
+  float* my_prm = prm[wave];
+  if (!has_bias) {  // the bias half stays zero for the whole launch
+    my_prm[128 + lane] = 0.0f;
+    my_prm[192 + lane] = 0.0f;
+  }
+  const uint32_t ring_lds = lds_address(ring), prm_lds = lds_address(my_prm);
+  const uint32_t loff = (uint32_t)lane * 16u;
+
+  // cursor of the copy requests: the next K step to request, as (tile, step), with its source addresses
+  int pf_item = 0, pf_ks = 0;
+  const uint8_t *pf_x = Xg, *pf_w = Wg;
+  uint32_t pf_xoff[4] = {0, 0, 0, 0};
+  auto seek = [&](int item, int ks) {
+    while (ks >= ksteps) {
+      ks -= ksteps;
+      ++item;
+    }
+    pf_item = item;
+    pf_ks = ks;
+    if (item < my_items) {
+      const Tile t = tile_of(item);
+      tile_x_offsets(pf_xoff, t, a.M, k_bytes, w, lane);
+      pf_x = Xg + t.m0 * k_bytes + (int64_t)ks * kStepBytes;
+      pf_w = Wg + t.n_blk * w_col_bytes + (int64_t)ks * tile_bytes(IS_I8);
+    }
+  };
+  auto request = [&](int g) -> bool {  // requests the cursor's step into the stage of global step g, advances the cursor
+    const bool any = pf_item < my_items;
+    if (any) {
+      issue_step_copies<IS_I8>(ring_lds + (uint32_t)(g & (kRing - 1)) * STAGE, pf_x, pf_w, pf_xoff, w, loff);
+      ++pf_ks;
+      pf_x += kStepBytes;
+      pf_w += tile_bytes(IS_I8);
+      if (pf_ks == ksteps) seek(pf_item + 1, 0);
+    }
+    return any;
+  };
+
+  if (team == 0) {  // the first three K steps of the sequence
+    seek(0, 0);
+    int n_req = 0;
+    for (int g = 0; g < kRing - 1; ++g) n_req += request(g) ? 1 : 0;
+    if (n_req == kRing - 1)
+      __builtin_amdgcn_s_waitcnt(kWaitVm18Lgkm0);  // step 0 has landed
+    else
+      __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+  }
+  GPUSQ_TEAM_BARRIER();
+
+  int ph = 0;
+  if (team == 1) {  // phase 0: nothing to do for the second team
+    for (int k = 0; k < ksteps; ++k) GPUSQ_TEAM_BARRIER();
+    ph = 1;
+  }
+  while (ph <= my_items) {
+    // ---- compute phase ph --------------------------------------------------------------------------------------
+    if (ph >= my_items) {  // one phase after the last tile: only the other team's last epilogue runs
+      for (int k = 0; k < ksteps; ++k) GPUSQ_TEAM_BARRIER();
+      break;
+    }
+    const Tile t = tile_of(ph);
+    acc_t acc[kBigTN][kBigTM];
+#pragma unroll
+    for (int i = 0; i < kBigTN; ++i)
+#pragma unroll
+      for (int j = 0; j < kBigTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+    seek(ph, kRing - 1);
+    if constexpr (!RAW) {  // this wavefront's 128 channels of epilogue constants, into its own LDS array
+      const int n0 = t.n_blk * kBigBN + wn * (kBigTN * 16);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int n = n0 + i * 64 + lane;
+        n = n < a.N ? n : a.N - 1;  // channels past the end are never stored
+        if constexpr (IS_I8) copy4_to_lds(a.w_scale, (uint32_t)n * 4u, prm_lds + (uint32_t)i * 256u);
+        if (has_bias) copy4_to_lds(a.bias, (uint32_t)n * 4u, prm_lds + 512u + (uint32_t)i * 256u);
+      }
+    }
+    const int g0 = ph * ksteps;
+    for (int ks = 0; ks < ksteps; ++ks) {
+      const int g = g0 + ks;
+      const bool requested = request(g + kRing - 1);
+      compute_stage<IS_I8>(ring + (size_t)(g & (kRing - 1)) * STAGE, acc, wn, wm, t.tm, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if (requested)
+        __builtin_amdgcn_s_waitcnt(kWaitVm18Lgkm0);
+      else
+        __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+      GPUSQ_TEAM_BARRIER();
+    }
+    ++ph;
+    // ---- epilogue phase ph: tile ph-1 --------------------------------------------------------------------------------
+    team_epilogue<IS_I8, GELU, OUT>(a, acc, my_prm, s_a, t.n_blk * kBigBN + wn * (kBigTN * 16), t.m0 + wm * t.tm * 16, lane, t.tm,
+                                    ksteps);
+    ++ph;
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ small / generic kernel
 constexpr int kLdsRow = kStepBytes + 16;  // 144-byte row pitch: 16 rows x 16-byte reads hit 16 distinct bank groups
 
@@ -506,11 +770,37 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
   if (work <= (int64_t)256 * 1024) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
   if (k_bytes % kStepBytes != 0) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);    // ragged K: zero-filling path
+  const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
+  static const bool use_tile_kernel = [] { const char* e = getenv("GPUSQ_KERNEL"); return e && e[0] == 't' && e[1] == 'i'; }();
+  if (!use_tile_kernel) {
+    // persistent grid: one workgroup of two teams per CU, never more workgroups than tiles
+    const int resident = num_cus();
+    const TilePlan plan = make_plan(a.M, a.N, resident);
+    const dim3 grid((unsigned)(ceil_div(plan.total < resident ? plan.total : resident, 8) * 8));
+    if ((ceil_div(plan.total, grid.x) + 2) * (k_bytes / kStepBytes) >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
+    if constexpr (IS_I8) {
+      if (a.out_dt == GPUSQ_I32)
+        spgemm_team_kernel<true, 0, GPUSQ_I32><<<grid, 512, 0, s>>>(a, plan);
+      else if (a.out_dt == GPUSQ_I8 && gelu)
+        spgemm_team_kernel<true, 1, GPUSQ_I8><<<grid, 512, 0, s>>>(a, plan);
+      else if (a.out_dt == GPUSQ_I8)
+        spgemm_team_kernel<true, 0, GPUSQ_I8><<<grid, 512, 0, s>>>(a, plan);
+      else if (gelu)
+        spgemm_team_kernel<true, 1, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+      else
+        spgemm_team_kernel<true, 0, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+    } else {
+      if (gelu)
+        spgemm_team_kernel<false, 1, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+      else
+        spgemm_team_kernel<false, 0, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+    }
+    return check_launch();
+  }
   // persistent grid: two workgroups per CU (the LDS footprint allows no more), never more workgroups than tiles
   const int resident = 2 * num_cus();
   const TilePlan plan = make_plan(a.M, a.N, resident);
   const dim3 grid((unsigned)(ceil_div(plan.total < resident ? plan.total : resident, 8) * 8));
-  const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
   if constexpr (IS_I8) {
     if (a.out_dt == GPUSQ_I32)
       spgemm_tile_kernel<true, 0, GPUSQ_I32><<<grid, 256, 0, s>>>(a, plan);
