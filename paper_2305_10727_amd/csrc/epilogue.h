@@ -30,24 +30,39 @@ __device__ __forceinline__ float gelu_f32(float x) {
   return __fmaf_rn(-t, q, fmaxf(x, 0.0f));
 }
 
+// Pins 8 values in registers at this point of the instruction stream (an empty volatile asm that "modifies" them): the
+// instructions that produce them cannot be moved below it, sunk into a later conditional block, or merged with the
+// instructions that consume them.
+__device__ __forceinline__ void pin8(float (&x)[8]) {
+  asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]));
+}
+
 // The same function on 8 values at once, written stage by stage so that the 8 dependency chains interleave: a lone
-// wavefront on a SIMD then issues an independent instruction every cycle instead of waiting on each result.
+// wavefront on a SIMD then issues an independent instruction every slot instead of waiting on each result.  The pins
+// between the stages keep the compiler from folding the chains back into pairs (which it does to save registers).
 __device__ __forceinline__ void gelu_f32_x8(float (&v)[8]) {
   float p[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(fabsf(v[j]), kGeluP5, kGeluP4);
+  pin8(p);
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP3);
+  pin8(p);
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP2);
+  pin8(p);
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP1);
+  pin8(p);
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = __fmaf_rn(p[j], fabsf(v[j]), kGeluP0);
+  pin8(p);
 #pragma unroll
   for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(p[j]);
+  pin8(p);
 #pragma unroll
   for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(-fabsf(v[j]), p[j], fmaxf(v[j], 0.0f));
+  pin8(v);
 }
 
 // q = clamp(rint(v / s), -127, 127): the same IEEE division + round-half-even as the quantiser of the activations
@@ -89,24 +104,25 @@ __device__ __forceinline__ float epilogue_value(int raw, float accf, float c, fl
   return use_gelu ? gelu_f32(v) : v;
 }
 
-// Converts and stores 8 consecutive output channels [n, n+8) of activation row m held by one lane.
+// Converts and stores 8 consecutive output channels [n, n+8) of one activation row held by one lane; `yp` points at
+// the element (row, n) of Y.
 // N % 4 == 0 is guaranteed by the host, so each half of 4 channels is entirely inside or outside the matrix and
 // 4-channel stores are naturally aligned; with N % 8 == 0 the 8 channels go out in one store.
 // OUT: output dtype fixed at compile time (a gpusq_dtype value), or -1 to take it from the arguments at run time.
 template <bool IS_I8, int OUT = -1>
-__device__ __forceinline__ void store_8(const GemmArgs& a, int64_t m, int n, const float (&v)[8], const int (&raw)[8]) {
+__device__ __forceinline__ void store_8_at(const GemmArgs& a, void* yp, int n, const float (&v)[8], const int (&raw)[8]) {
   const int N = a.N;
   const int out_dt = OUT >= 0 ? OUT : a.out_dt;
   if (n >= N) return;
   const bool whole = (N & 7) == 0;  // then n + 8 <= N as well, because n is a multiple of 8
   const bool second = n + 8 <= N;
   if (IS_I8 && out_dt == GPUSQ_I32) {
-    int* y = (int*)a.Y + m * N + n;
+    int* y = (int*)yp;
     *(ep_v4i*)y = ep_v4i{raw[0], raw[1], raw[2], raw[3]};
     if (second) *(ep_v4i*)(y + 4) = ep_v4i{raw[4], raw[5], raw[6], raw[7]};
   } else if (IS_I8 && out_dt == GPUSQ_I8) {
     const float so = a.out_scale[0];
-    int8_t* y = (int8_t*)a.Y + m * N + n;
+    int8_t* y = (int8_t*)yp;
     int q[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) q[j] = requantize_code(v[j], so) & 0xFF;
@@ -118,7 +134,7 @@ __device__ __forceinline__ void store_8(const GemmArgs& a, int64_t m, int n, con
       if (second) *(int*)(y + 4) = hi;
     }
   } else {
-    _Float16* y = (_Float16*)a.Y + m * N + n;
+    _Float16* y = (_Float16*)yp;
     if (whole) {
       ep_v8h h;
 #pragma unroll
@@ -129,6 +145,15 @@ __device__ __forceinline__ void store_8(const GemmArgs& a, int64_t m, int n, con
       if (second) *(ep_v4h*)(y + 4) = ep_v4h{(_Float16)v[4], (_Float16)v[5], (_Float16)v[6], (_Float16)v[7]};
     }
   }
+}
+
+__host__ __device__ constexpr int dtype_bytes(int dt) { return dt == GPUSQ_I8 ? 1 : (dt == GPUSQ_F16 ? 2 : 4); }
+
+// The same with the address computed from the row m and channel n.
+template <bool IS_I8, int OUT = -1>
+__device__ __forceinline__ void store_8(const GemmArgs& a, int64_t m, int n, const float (&v)[8], const int (&raw)[8]) {
+  const int out_dt = OUT >= 0 ? OUT : a.out_dt;
+  store_8_at<IS_I8, OUT>(a, (uint8_t*)a.Y + (m * a.N + n) * dtype_bytes(out_dt), n, v, raw);
 }
 
 }  // namespace gpusq

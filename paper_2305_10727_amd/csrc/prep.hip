@@ -515,7 +515,7 @@ __global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __res
 template <bool IS_I8>
 __global__ void __launch_bounds__(256) clear_packed_padding_kernel(uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps,
                                                                    int64_t total_lanes) {
-  constexpr int E = step_elems(IS_I8), KL = E / 4, IB = IS_I8 ? 4 : 2;
+  constexpr int E = step_elems(IS_I8), KL = E / 4;
   const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= total_lanes) return;
   const int lane = (int)(id & 63);

@@ -15,12 +15,10 @@
 //   D (4 VGPRs): lane l, register r -> row 4*(l/16)+r, column l%16.
 //
 // Two kernels:
-//   spgemm_tile_kernel  256 n x 128 m workgroup tile, operands brought into LDS by direct global->LDS copies
-//                       (no staging registers), two LDS stages, two workgroups per CU so that one workgroup's
-//                       epilogue (VALU + stores) overlaps the other's matrix instructions.  Needs K*elemsize % 128 == 0.
+//   spgemm_team_kernel  256 n x 128 m tiles, operands brought into LDS by direct global->LDS copies (no staging
+//                       registers), one workgroup of two 4-wavefront teams per CU: one team runs the K loop of a tile
+//                       while the other runs the epilogue of the previous one.  Needs K*elemsize % 128 == 0.
 //   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
-#include <stdlib.h>
-
 #include "common.h"
 #include "epilogue.h"
 
@@ -97,9 +95,6 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename 
 }
 
 // ------------------------------------------------------------------------------------------------ large-tile kernel
-#define GPUSQ_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
-#define GPUSQ_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
-
 constexpr int kBigBN = 256, kBigBM = 128, kBigTN = 8, kBigTM = 4;
 constexpr int kXStageBytes = kBigBM * kStepBytes;  // 16 KB: 128 rows x 128 bytes, 16-byte chunks XOR-swizzled per row
 
@@ -145,34 +140,6 @@ __device__ __forceinline__ Tile decode_tile(const TilePlan& p, int idx) {
   return t;
 }
 
-// One wavefront's share of the copies that bring K step `ks` of a tile into an LDS stage: the X slab (up to 16 KB),
-// 16 fragments of kept values and 4 KB (fp16: 2 KB) of index words are moved in 1 KB pieces dealt round-robin to the
-// 4 wavefronts.  Each copy instruction moves 64 lanes x 16 bytes from per-lane global addresses to 1 KB of
-// consecutive LDS.  The X slab is stored row-major with the 16-byte chunk c of row r at chunk position
-// c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the same K offset fall in 16 different 16-byte
-// bank groups; the swizzle is applied by choosing which global chunk each lane fetches.
-// Addresses are a wavefront-uniform 64-bit base (scalar registers, advanced per K step by scalar adds) plus a 32-bit
-// per-lane offset fixed for the whole tile (`xoff`), so a K step costs no vector ALU work for addressing.
-template <bool IS_I8>
-__device__ __forceinline__ void issue_stage_copies(uint8_t* stage, const uint8_t* Xtile_ks, const uint8_t* Wtile,
-                                                   const uint32_t (&xoff)[4], int tm, int wave, int lane) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int j = wave + i * 4;  // 1 KB block = 8 rows; the tile has 32*tm rows
-    if (j < 4 * tm)
-      __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(Xtile_ks + xoff[i]), GPUSQ_LPTR(stage + j * 1024), 16, 0, 0);
-  }
-  const uint8_t* wsrc = Wtile + wave * kFragValueBytes;
-  uint8_t* wdst = stage + kXStageBytes + wave * kFragValueBytes;
-  const uint32_t loff = (uint32_t)lane * 16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(wsrc + i * 4 * kFragValueBytes + loff), GPUSQ_LPTR(wdst + i * 4 * kFragValueBytes),
-                                     16, 0, 0);
-  if (wave < (IS_I8 ? 4 : 2))
-    __builtin_amdgcn_global_load_lds(GPUSQ_GPTR(wsrc + kTileValueBytes + loff), GPUSQ_LPTR(wdst + kTileValueBytes), 16, 0, 0);
-}
-
 // Per-lane byte offsets, relative to the tile's first row, of the four X blocks this wavefront copies per K step:
 // block j = wave + 4i holds rows 8j..8j+7; lane l fetches row 8j + l/8, chunk (l%8) ^ ((row >> 1) & 7).  Rows past the
 // end of X re-read the last row (their results are never stored).
@@ -184,165 +151,6 @@ __device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], const Tile& 
     const int64_t last = (int64_t)M - 1 - t.m0;  // >= 0: a tile starts inside X
     const int64_t rr = r < last ? r : last;
     xoff[i] = (uint32_t)(rr * k_bytes + c * 16);
-  }
-}
-
-// All matrix instructions of one K step for one wavefront (128 n x 16*tm m): 8 fragments of A, tm slabs of B.
-template <bool IS_I8>
-__device__ __forceinline__ void compute_stage(const uint8_t* stage, typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM], int wn,
-                                              int wm, int tm, int lane) {
-  const uint8_t* Ws = stage + kXStageBytes;
-  const int sw = (lane & 15) >> 1;  // (row >> 1) & 7: slab and wavefront offsets are multiples of 16 rows
-  const int q = lane >> 4;
-  const uint8_t* xrow = stage + (wm * tm * 16 + (lane & 15)) * kStepBytes;
-  const uint8_t* xlo = xrow + (q ^ sw) * 16;
-  const uint8_t* xhi = xrow + ((4 + q) ^ sw) * 16;
-  const uint8_t* abase = Ws + wn * kBigTN * kFragValueBytes + lane * 16;
-  const uint8_t* ibase = Ws + index_offset(IS_I8, wn * kBigTN, lane);  // this lane's 8 index words, consecutive
-  // B slabs first, then the A fragments in the order they are consumed: LDS returns data in request order, so the
-  // matrix instructions of fragment 0 can start while the remaining fragments stream in
-  // (a short tail tile still runs all four slabs: the surplus slabs read stale rows of the stage and their
-  // accumulators are never stored; the matrix pipe is not what limits a K step)
-  v8i b[kBigTM];
-#pragma unroll
-  for (int mt = 0; mt < kBigTM; ++mt) {
-    const v4i lo = *(const v4i*)(xlo + mt * 16 * kStepBytes), hi = *(const v4i*)(xhi + mt * 16 * kStepBytes);
-    b[mt] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  }
-  int ai[kBigTN];
-  if constexpr (IS_I8) {
-    const v4i i0 = *(const v4i*)ibase, i1 = *(const v4i*)(ibase + 16);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      ai[j] = i0[j];
-      ai[4 + j] = i1[j];
-    }
-  } else {
-    const v4i i0 = *(const v4i*)ibase;  // 8 x 16 bits
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      ai[2 * j] = i0[j] & 0xFFFF;
-      ai[2 * j + 1] = (int)((unsigned)i0[j] >> 16);
-    }
-  }
-  v4i av[kBigTN];
-#pragma unroll
-  for (int tn = 0; tn < kBigTN; ++tn) av[tn] = *(const v4i*)(abase + tn * kFragValueBytes);
-#pragma unroll
-  for (int tn = 0; tn < kBigTN; ++tn)
-#pragma unroll
-    for (int mt = 0; mt < kBigTM; ++mt) acc[tn][mt] = smfmac<IS_I8>(av[tn], b[mt], acc[tn][mt], ai[tn]);
-  // Issue order within the K step: the 8 reads of B, the index words and the first three A fragments up front, then
-  // four matrix instructions per fragment with the read of the fragment three ahead in between, so that an LDS round
-  // trip is covered by 12 matrix instructions and at most 4 fragments are live.
-  __builtin_amdgcn_sched_group_barrier(0x100, 8 + (IS_I8 ? 2 : 1) + 3, 0);
-#pragma unroll
-  for (int tn = 0; tn < kBigTN; ++tn) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-    if (tn + 3 < kBigTN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-  }
-}
-
-// s_waitcnt vmcnt(0) lgkmcnt(0) (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]): the
-// wavefront's own global->LDS copies have landed and its LDS reads of the stage it leaves have returned, so after
-// the barrier that follows every stage may be read, and the stage just left may be overwritten.
-// The scheduling barrier in front keeps the compiler from hoisting the wait (and the s_barrier after it) above the
-// matrix instructions of the K step, which would expose the copy latency instead of hiding it behind them.
-#define GPUSQ_WAIT_COPIES_AND_LDS()       \
-  do {                                    \
-    __builtin_amdgcn_sched_barrier(0);    \
-    __builtin_amdgcn_s_waitcnt(0x0070);   \
-  } while (0)
-
-// Workgroup = 4 wavefronts (2 along n x 2 along m), 128 channels x 64 rows each, 128 accumulator registers, two
-// wavefronts per SIMD = two workgroups per CU (the LDS footprint, 2 stages of 36 KB, allows no more).
-//
-// Persistent: the grid holds two workgroups per CU and every workgroup walks over tiles with a fixed stride, so the
-// output stores of one tile drain while the next tile is being computed; the first K step of the next tile is
-// requested before the epilogue of the current one starts, which hides its latency behind the epilogue.
-// Tile order: workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2); XCD x takes an eighth of the
-// full tiles as one contiguous run plus an eighth of the tail tiles, and its workgroups take them in order, so tiles
-// that share an X slab (same rows, n fastest) are computed close in time on one L2.
-template <bool IS_I8, int GELU, int OUT>
-__global__ void __launch_bounds__(256, 2) spgemm_tile_kernel(const GemmArgs a, const TilePlan plan) {
-  typedef typename AccT<IS_I8>::type acc_t;
-  constexpr int ES = IS_I8 ? 1 : 2;
-  constexpr int STAGE = kXStageBytes + tile_bytes(IS_I8);
-  __shared__ __attribute__((aligned(1024))) uint8_t S0[STAGE];
-  __shared__ __attribute__((aligned(1024))) uint8_t S1[STAGE];
-  __shared__ __attribute__((aligned(16))) float cs[kBigBN];
-  __shared__ __attribute__((aligned(16))) float bs[kBigBN];
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps wave-derived addresses in scalar registers
-  const int wn = wave & 1, wm = wave >> 1;
-  const int64_t k_bytes = (int64_t)a.K * ES;
-  const int ksteps = (int)(k_bytes / kStepBytes);
-  const uint8_t* Xg = (const uint8_t*)a.X;
-  const uint8_t* Wg = (const uint8_t*)a.W;
-  const int64_t w_col_bytes = (int64_t)ksteps * tile_bytes(IS_I8);  // packed bytes of one 256-channel block
-  const int xcd = (int)(blockIdx.x & 7), wgs_per_xcd = (int)(gridDim.x >> 3);
-  int f0, nf, t0;
-  const int items = xcd_items(plan, xcd, f0, nf, t0);
-  // A workgroup first takes its tail tiles, then its full tiles, and the tail tiles go preferably to the second
-  // workgroup of each CU (local ids wgs/2 .. wgs-1): the two workgroups that share a CU then run about half a tile out
-  // of phase, so that one is in its store/VALU epilogue while the other is in its matrix-instruction loop.
-  const int wl = (int)(blockIdx.x >> 3);
-  const int nt = items - nf;
-  const int tl = (wl + wgs_per_xcd - (wgs_per_xcd >> 1)) % wgs_per_xcd;  // position in the tail hand-out order
-  const int my_tail = tl < nt ? (nt - tl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
-  const int my_full = wl < nf ? (nf - wl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
-  const int my_items = my_tail + my_full;
-  if (my_items == 0) return;
-  int it = 0;
-  auto tile_of = [&](int i) { return i < my_tail ? t0 + tl + i * wgs_per_xcd : f0 + wl + (i - my_tail) * wgs_per_xcd; };
-  Tile t = decode_tile(plan, tile_of(0));
-  uint32_t xoff[4];
-  tile_x_offsets(xoff, t, a.M, k_bytes, wave, lane);
-  issue_stage_copies<IS_I8>(S0, Xg + t.m0 * k_bytes, Wg + t.n_blk * w_col_bytes, xoff, t.tm, wave, lane);
-  ChannelParams prm;
-  prm.fetch<IS_I8>(a, t.n_blk * kBigBN + tid);
-
-  while (true) {
-    const uint8_t* Wt = Wg + t.n_blk * w_col_bytes;
-    const uint8_t* Xt = Xg + t.m0 * k_bytes;
-    acc_t acc[kBigTN][kBigTM];
-#pragma unroll
-    for (int i = 0; i < kBigTN; ++i)
-#pragma unroll
-      for (int j = 0; j < kBigTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
-
-    GPUSQ_WAIT_COPIES_AND_LDS();  // stage 0 of this tile has landed; the previous tile's reads of cs/bs have returned
-    __builtin_amdgcn_s_barrier();
-    prm.publish(cs, bs, tid);     // read in the epilogue, after the barriers of the main loop
-    for (int ks = 0; ks < ksteps; ks += 2) {
-      // stage 1 was last read before the barrier that ended the previous trip, so it may be overwritten now
-      if (ks + 1 < ksteps) issue_stage_copies<IS_I8>(S1, Xt + (int64_t)(ks + 1) * kStepBytes, Wt + (int64_t)(ks + 1) * tile_bytes(IS_I8), xoff, t.tm, wave, lane);
-      compute_stage<IS_I8>(S0, acc, wn, wm, t.tm, lane);
-      GPUSQ_WAIT_COPIES_AND_LDS();
-      __builtin_amdgcn_s_barrier();
-      if (ks + 1 < ksteps) {
-        if (ks + 2 < ksteps) issue_stage_copies<IS_I8>(S0, Xt + (int64_t)(ks + 2) * kStepBytes, Wt + (int64_t)(ks + 2) * tile_bytes(IS_I8), xoff, t.tm, wave, lane);
-        compute_stage<IS_I8>(S1, acc, wn, wm, t.tm, lane);
-        GPUSQ_WAIT_COPIES_AND_LDS();
-        __builtin_amdgcn_s_barrier();
-      }
-    }
-    // both stages are free now (every wavefront passed the last barrier after its last reads): request the first
-    // K step of the next tile before the epilogue
-    const int cur_n = t.n_blk, cur_tm = t.tm;
-    const int64_t cur_m0 = t.m0;
-    ++it;
-    const bool more = it < my_items;
-    if (more) {
-      t = decode_tile(plan, tile_of(it));
-      tile_x_offsets(xoff, t, a.M, k_bytes, wave, lane);
-      issue_stage_copies<IS_I8>(S0, Xg + t.m0 * k_bytes, Wg + t.n_blk * w_col_bytes, xoff, t.tm, wave, lane);
-      prm.fetch<IS_I8>(a, t.n_blk * kBigBN + tid);
-    }
-    wave_epilogue<IS_I8, kBigTN, kBigTM, GELU, OUT>(a, acc, cs, bs, cur_n * kBigBN, cur_n * kBigBN + wn * kBigTN * 16,
-                                                    cur_m0 + wm * cur_tm * 16, lane, cur_tm);
-    if (!more) break;
   }
 }
 
@@ -362,32 +170,39 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t*)p;
 }
 
-constexpr int kRing = 4;            // LDS stages: the K step being read plus three in flight
+constexpr int kRing = 4;            // LDS stages: the K step being read plus three requested ahead
 constexpr int kCopiesPerStep = 9;   // copy instructions every wavefront of the computing team issues per K step
 
-// One wavefront's share (a quarter) of the copies of one K step of a tile into the LDS stage at `stage_lds`: four
-// 1 KB blocks of the X slab (block j = w + 4i holds rows 8j..8j+7, chunks swizzled as described above
-// issue_stage_copies), four fragments of kept values and 1 KB of index words.  Always exactly kCopiesPerStep
-// instructions, whatever the tile: a short tail tile copies rows it does not use, and on the fp16 path (2 KB of
-// index words) wavefronts 2 and 3 repeat the copies of wavefronts 0 and 1, so that the waits can count instructions.
+// Copy i (0..8) of one wavefront's share (a quarter) of the copies that bring one K step of a tile into the LDS
+// stage at `stage_lds`: i = 0..3 are 1 KB blocks of the X slab (block j = w + 4i holds rows 8j..8j+7), i = 4..7
+// fragments of kept values, i = 8 1 KB of index words.  Each copy moves 64 lanes x 16 bytes from a wavefront-uniform
+// 64-bit base (scalar registers, advanced per K step by scalar adds) plus a 32-bit per-lane offset to 1 KB of
+// consecutive LDS, so a K step costs no vector ALU work for addressing.  The X slab is stored row-major with the
+// 16-byte chunk c of row r at chunk position c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the
+// same K offset fall in 16 different 16-byte bank groups; the swizzle is applied by choosing which global chunk each
+// lane fetches (tile_x_offsets).  Always
+// exactly kCopiesPerStep instructions per step, whatever the tile: a short tail tile copies rows it does not use, and
+// on the fp16 path (2 KB of index words) wavefronts 2 and 3 repeat the copies of wavefronts 0 and 1, so that the
+// waits can count instructions.
 template <bool IS_I8>
-__device__ __forceinline__ void issue_step_copies(uint32_t stage_lds, const uint8_t* Xks, const uint8_t* Wks,
-                                                  const uint32_t (&xoff)[4], int w, uint32_t loff) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) copy16_to_lds(Xks, xoff[i], stage_lds + (uint32_t)(w + 4 * i) * 1024u);
-  const uint8_t* wsrc = Wks + w * kFragValueBytes;
-  const uint32_t wdst = stage_lds + kXStageBytes + (uint32_t)w * kFragValueBytes;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) copy16_to_lds(wsrc + i * 4 * kFragValueBytes, loff, wdst + (uint32_t)i * 4 * kFragValueBytes);
-  const int iw = IS_I8 ? w : (w & 1);
-  copy16_to_lds(Wks + kTileValueBytes + iw * 1024, loff, stage_lds + kXStageBytes + kTileValueBytes + (uint32_t)iw * 1024u);
+__device__ __forceinline__ void issue_step_copy(int i, uint32_t stage_lds, const uint8_t* Xks, const uint8_t* Wks,
+                                                const uint32_t (&xoff)[4], int w, uint32_t loff) {
+  if (i < 4) {
+    copy16_to_lds(Xks, xoff[i], stage_lds + (uint32_t)(w + 4 * i) * 1024u);
+  } else if (i < 8) {
+    const int f = w + 4 * (i - 4);
+    copy16_to_lds(Wks + f * kFragValueBytes, loff, stage_lds + kXStageBytes + (uint32_t)f * kFragValueBytes);
+  } else {
+    const int iw = IS_I8 ? w : (w & 1);
+    copy16_to_lds(Wks + kTileValueBytes + iw * 1024, loff, stage_lds + kXStageBytes + kTileValueBytes + (uint32_t)iw * 1024u);
+  }
 }
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
-constexpr int kWaitVm0 = 0x0F70;            // vmcnt(0)
-constexpr int kWaitVm0Lgkm0 = 0x0070;       // vmcnt(0) lgkmcnt(0)
-constexpr int kWaitVm18Lgkm0 = 0x4072;      // vmcnt(2 * kCopiesPerStep) lgkmcnt(0)
-static_assert(2 * kCopiesPerStep == 18, "kWaitVm18Lgkm0 encodes two K steps of copies");
+constexpr int kWaitVm0 = 0x0F70;         // vmcnt(0)
+constexpr int kWaitVm0Lgkm0 = 0x0070;    // vmcnt(0) lgkmcnt(0)
+constexpr int kWaitVm9Lgkm0 = 0x0079;    // vmcnt(kCopiesPerStep) lgkmcnt(0)
+static_assert(kCopiesPerStep == 9, "kWaitVm9Lgkm0 encodes one K step of copies");
 
 // Workgroup-wide barrier preceded by a scheduling barrier (the compiler must not move it above the matrix
 // instructions of the K step) and followed by a compiler-level memory barrier (no LDS read moves above it).
@@ -398,22 +213,132 @@ static_assert(2 * kCopiesPerStep == 18, "kWaitVm18Lgkm0 encodes two K steps of c
     asm volatile("" ::: "memory");        \
   } while (0)
 
+// Per-lane byte offsets of the B operand inside an X slab: lane l reads row wm*16*tm + 16*mt + l%16, the 16-byte
+// chunks l/16 and 4 + l/16 of it (at their swizzled positions).
+struct BOffsets {
+  uint32_t lo, hi;
+};
+__device__ __forceinline__ BOffsets b_offsets(int wm, int tm, int lane) {
+  const int sw = (lane & 15) >> 1, q = lane >> 4;
+  const uint32_t row = (uint32_t)(wm * tm * 16 + (lane & 15)) * kStepBytes;
+  return BOffsets{row + (uint32_t)((q ^ sw) * 16), row + (uint32_t)(((4 + q) ^ sw) * 16)};
+}
+
+// The four B slabs of one K step, from the X slab at `xslab`, into registers.
+__device__ __forceinline__ void load_b_slabs(v8i (&b)[kBigTM], const uint8_t* xslab, const BOffsets& o) {
+#pragma unroll
+  for (int mt = 0; mt < kBigTM; ++mt) {
+    const v4i lo = *(const v4i*)(xslab + o.lo + mt * 16 * kStepBytes), hi = *(const v4i*)(xslab + o.hi + mt * 16 * kStepBytes);
+    b[mt] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  }
+}
+
+// Index words of fragments 4*half .. 4*half+3 of this lane (its 8 words are consecutive at `ibase`).
+template <bool IS_I8>
+__device__ __forceinline__ void load_index_half(int (&ai)[kBigTN], int half, const uint8_t* ibase) {
+  if constexpr (IS_I8) {
+    const v4i x = *(const v4i*)(ibase + half * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ai[4 * half + j] = x[j];
+  } else {
+    typedef int v2i __attribute__((ext_vector_type(2)));
+    const v2i x = *(const v2i*)(ibase + half * 8);  // 4 x 16 bits
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      ai[4 * half + 2 * j] = x[j] & 0xFFFF;
+      ai[4 * half + 2 * j + 1] = (int)((unsigned)x[j] >> 16);
+    }
+  }
+}
+
+// What a computing wavefront holds in registers when a K step begins: the four B slabs of the step, its A fragments
+// 0..2 (fragment f lives in av[f % 4]) and the index words of fragments 0..3.
+template <bool IS_I8>
+__device__ __forceinline__ void load_step_head(v8i (&b)[kBigTM], v4i (&av)[4], int (&ai)[kBigTN], const uint8_t* stage,
+                                               const BOffsets& bo, uint32_t a_off, uint32_t i_off) {
+  load_b_slabs(b, stage, bo);
+  load_index_half<IS_I8>(ai, 0, stage + kXStageBytes + i_off);
+#pragma unroll
+  for (int f = 0; f < 3; ++f) av[f] = *(const v4i*)(stage + kXStageBytes + a_off + f * kFragValueBytes);
+}
+
+// One K step of a computing wavefront (128 n x 64 m), software-pipelined by hand across steps.  When the step
+// begins its B operand (`b`), its A fragments 0..2 and the index words of fragments 0..3 are already in registers.
+// Per fragment the step issues: the LDS read of the fragment three ahead -- which for the last three fragments is
+// fragment 0..2 of the NEXT step, read from `next` --, one 16-byte piece of the next step's B operand (`bn`), the
+// index words it will need four fragments later, and then the four matrix instructions of the fragment.  So the
+// matrix pipe never waits for a step to "start": LDS latency is always covered by 12 matrix instructions, also across
+// the barrier between two steps.  (`next` = the stage of the next step of the same tile; after the last step of a
+// tile the reads ahead go to `stage` again and are discarded.)
+// The wavefront's kCopiesPerStep copy requests are spread over the step, one per fragment.
+template <bool IS_I8>
+__device__ __forceinline__ void team_step(const uint8_t* stage, const uint8_t* next, const BOffsets& bo,
+                                          typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM], const v8i (&b)[kBigTM],
+                                          v8i (&bn)[kBigTM], v4i (&av)[4], int (&ai)[kBigTN], uint32_t a_off, uint32_t i_off,
+                                          bool requested, uint32_t req_lds, const uint8_t* req_x, const uint8_t* req_w,
+                                          const uint32_t (&xoff)[4], int w, uint32_t loff) {
+  const uint8_t* abase = stage + kXStageBytes + a_off;
+  const uint8_t* ibase = stage + kXStageBytes + i_off;
+  const uint8_t* abase_n = next + kXStageBytes + a_off;
+  const uint8_t* ibase_n = next + kXStageBytes + i_off;
+  // One matrix instruction per slot; in front of each, at most one LDS read and one copy request, so that every other
+  // instruction is issued in the shadow of a matrix instruction (a wavefront issues in order: a clump of reads and
+  // copies between two groups of matrix instructions would leave the matrix pipe idle for its whole length).
+#pragma unroll
+  for (int tn = 0; tn < kBigTN; ++tn) {
+#pragma unroll
+    for (int mt = 0; mt < kBigTM; ++mt) {
+      if (mt == 0) {
+        const int f = tn + 3;
+        av[f & 3] = f < kBigTN ? *(const v4i*)(abase + f * kFragValueBytes) : *(const v4i*)(abase_n + (f - kBigTN) * kFragValueBytes);
+      }
+      if (mt == 1) {
+        const v4i piece = *(const v4i*)(next + ((tn & 1) ? bo.hi : bo.lo) + (tn >> 1) * 16 * kStepBytes);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bn[tn >> 1][4 * (tn & 1) + j] = piece[j];
+      }
+      if (mt == 2 && tn == 0) load_index_half<IS_I8>(ai, 1, ibase);
+      if (mt == 2 && tn == 4) load_index_half<IS_I8>(ai, 0, ibase_n);
+      if (requested) {
+        if (mt == 3) issue_step_copy<IS_I8>(tn, req_lds, req_x, req_w, xoff, w, loff);
+        if (mt == 2 && tn == kBigTN - 1) issue_step_copy<IS_I8>(kBigTN, req_lds, req_x, req_w, xoff, w, loff);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      acc[tn][mt] = smfmac<IS_I8>(av[tn & 3], b[mt], acc[tn][mt], ai[tn]);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // Epilogue of one wavefront of the team that is not computing: same lane -> output mapping as wave_epilogue, with
 //  * the per-channel constants read from the wavefront's own LDS array `p` (128 weight scales, then 128 biases),
 //  * `ksteps` workgroup barriers spread evenly over the 16 batches of 8 outputs per lane, so that this team stays in
 //    step with the K steps of the team that is computing (both execute the same number of barriers per phase),
-//  * a wait for the wavefront's own outstanding copies (requested for the other team's next tile) after the first
-//    batch of arithmetic and before the first store and the first barrier: from then on this wavefront has stores in
-//    flight and never waits on the vector-memory counter again until its next compute phase.
-template <bool IS_I8, int GELU, int OUT>
+//  * a wait for the wavefront's own outstanding copies (requested for the other team's tile) after the first batch of
+//    arithmetic and before the first store and the first barrier: from then on this wavefront has stores in flight
+//    and never waits on the vector-memory counter again until its next compute phase,
+//  * `before_last_barrier()` called once, after the last batch and before the last barrier of the phase: the caller
+//    sets up the wavefront's next tile there (the accumulators are free by then).
+template <bool IS_I8, int GELU, int OUT, class Hook>
 __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM],
                                               const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active,
-                                              int ksteps) {
+                                              int ksteps, Hook&& before_last_barrier) {
   constexpr bool RAW = IS_I8 && OUT == GPUSQ_I32;
+  constexpr int OB = dtype_bytes(OUT);
+  // address of this lane's first 8 channels in each of its 4 rows, computed once: a batch then only adds a constant
+  uint8_t* yrow[kBigTM];
+  bool row_ok[kBigTM];
+#pragma unroll
+  for (int mt = 0; mt < kBigTM; ++mt) {
+    const int64_t m = m_wave + mt * 16 + (lane & 15);
+    row_ok[mt] = m < a.M;
+    yrow[mt] = (uint8_t*)a.Y + (m * a.N + n_wave + (lane >> 4) * 8) * OB;
+  }
   int done = 0;
 #pragma unroll
   for (int g = 0; g < kBigTN / 2; ++g) {
-    const int nl = (g >> 1) * kRowBlock + (g & 1) * 32 + (lane >> 4) * 8;  // channel relative to n_wave
+    const int nb = (g >> 1) * kRowBlock + (g & 1) * 32;  // first channel of the batch relative to n_wave (lane group 0)
+    const int nl = nb + (lane >> 4) * 8;                 // this lane's first channel
     float c8[8], b8[8];
     if constexpr (!RAW) {
 #pragma unroll
@@ -432,7 +357,6 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
     for (int mt = 0; mt < kBigTM; ++mt) {
       const int batch = g * kBigTM + mt;
       if (mt < tm_active) {
-        const int64_t m = m_wave + mt * 16 + (lane & 15);
         float v[8];
         int raw[8];
 #pragma unroll
@@ -442,22 +366,29 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
             const int j = 4 * t + r;
             if constexpr (IS_I8) {
               raw[j] = acc[2 * g + t][mt][r];
-              v[j] = RAW ? 0.0f : __fmaf_rn((float)raw[j], c8[j], b8[j]);
+              v[j] = RAW ? 0.0f : (float)raw[j];
             } else {
               raw[j] = 0;
               v[j] = acc[2 * g + t][mt][r] + b8[j];
             }
           }
+        if constexpr (IS_I8 && !RAW) {
+          pin8(v);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(v[j], c8[j], b8[j]);
+        }
         if constexpr (GELU != 0) gelu_f32_x8(v);
         if (batch == 0) {
           __builtin_amdgcn_sched_barrier(0);
           __builtin_amdgcn_s_waitcnt(kWaitVm0);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (m < a.M) store_8<IS_I8, OUT>(a, m, n_wave + nl, v, raw);
+        if (row_ok[mt]) store_8_at<IS_I8, OUT>(a, yrow[mt] + nb * OB, n_wave + nl, v, raw);
       }
       const int target = ((batch + 1) * ksteps) >> 4;
       while (done < target) {
+        // the phase's last barrier always falls after the last batch: (15 * ksteps) >> 4 < ksteps
+        if (batch == 4 * kBigTM - 1 && done == ksteps - 1) before_last_barrier();
         GPUSQ_TEAM_BARRIER();
         ++done;
       }
@@ -465,8 +396,8 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
   }
 }
 
-// Workgroup = 8 wavefronts = two teams of 4 (2 along n x 2 along m, 128 channels x 64 rows each, as in the kernel
-// above), one workgroup per CU; wavefronts 0-3 and 4-7 land on the four SIMDs once each, so every SIMD hosts one
+// Workgroup = 8 wavefronts = two teams of 4 (2 along n x 2 along m, 128 channels x 64 rows and 128 accumulator
+// registers each), one workgroup per CU (the LDS footprint, 4 stages of 36 KB, allows no more); wavefronts 0-3 and 4-7 land on the four SIMDs once each, so every SIMD hosts one
 // wavefront of each team.  The workgroup walks over its tiles; team (i mod 2) computes tile i.  Time is cut into
 // phases of `ksteps` workgroup barriers: in phase i one team runs the K loop of tile i (matrix instructions, LDS
 // reads, copy requests) while the other runs the epilogue of tile i-1 (vector ALU, stores), then they swap.  The
@@ -475,13 +406,16 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
 // are issued by different wavefronts in any phase, waiting for copies never means waiting for stores.
 //
 // Copy protocol.  K steps are numbered g = 0, 1, ... over the whole sequence of tiles; step g lives in stage g mod 4.
-// The wavefronts of the team that computes step g request step g+3 first (stage (g+3) mod 4 was last read in step
-// g-1, which every wavefront left through a barrier after its LDS reads had returned), then run step g, then wait
-// until at most the copies of steps g+2 and g+3 are outstanding (vmcnt counts instructions, and every wavefront
-// issues kCopiesPerStep per step), then meet at the barrier.  So when step g+1 starts, its data has landed, provided
-// it was requested by this team; if it was requested by the other team (the first steps of a tile), that team has
-// waited for all its copies before the first barrier of its epilogue phase (see team_epilogue), which is earlier.
-// When nothing is requested in a step (the last steps of the last tile) the wait is for all copies.
+// The wavefronts of the team that computes step g request step g+3 during step g (stage (g+3) mod 4 was last read in
+// step g-1, which every wavefront left through a barrier after its LDS reads had returned), then wait until at most
+// the copies just requested are outstanding (vmcnt counts instructions, and every wavefront issues kCopiesPerStep
+// per step), then meet at the barrier.  Invariant: at the barrier that ends step g the data of all steps <= g+2 has
+// landed -- step g+2 was requested during step g-1, either by this team (covered by its wait) or, when g is the
+// first step of a tile, by the other team, which waits for all its copies before the first barrier of its epilogue
+// phase (see team_epilogue).  When nothing is requested in a step (the end of the sequence) the wait is for all
+// copies.  So during step g a wavefront may read stage g and stage g+1 (what it reads ahead for the next step), and a
+// wavefront of the epilogue team may read the stage of the first step of its next tile before the last barrier of
+// its phase (set_up_tile).
 // Every wavefront executes exactly 1 + (tiles + 1) * ksteps barriers.
 template <bool IS_I8, int GELU, int OUT>
 __global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, const TilePlan plan) {
@@ -518,6 +452,8 @@ __global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, c
   }
   const uint32_t ring_lds = lds_address(ring), prm_lds = lds_address(my_prm);
   const uint32_t loff = (uint32_t)lane * 16u;
+  const uint32_t a_off = (uint32_t)(wn * kBigTN * kFragValueBytes + lane * 16);
+  const uint32_t i_off = (uint32_t)index_offset(IS_I8, wn * kBigTN, lane);
 
   // cursor of the copy requests: the next K step to request, as (tile, step), with its source addresses
   int pf_item = 0, pf_ks = 0;
@@ -537,47 +473,31 @@ __global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, c
       pf_w = Wg + t.n_blk * w_col_bytes + (int64_t)ks * tile_bytes(IS_I8);
     }
   };
-  auto request = [&](int g) -> bool {  // requests the cursor's step into the stage of global step g, advances the cursor
-    const bool any = pf_item < my_items;
-    if (any) {
-      issue_step_copies<IS_I8>(ring_lds + (uint32_t)(g & (kRing - 1)) * STAGE, pf_x, pf_w, pf_xoff, w, loff);
-      ++pf_ks;
-      pf_x += kStepBytes;
-      pf_w += tile_bytes(IS_I8);
-      if (pf_ks == ksteps) seek(pf_item + 1, 0);
-    }
-    return any;
+  auto advance = [&]() {
+    ++pf_ks;
+    pf_x += kStepBytes;
+    pf_w += tile_bytes(IS_I8);
+    if (pf_ks == ksteps) seek(pf_item + 1, 0);
   };
 
-  if (team == 0) {  // the first three K steps of the sequence
-    seek(0, 0);
-    int n_req = 0;
-    for (int g = 0; g < kRing - 1; ++g) n_req += request(g) ? 1 : 0;
-    if (n_req == kRing - 1)
-      __builtin_amdgcn_s_waitcnt(kWaitVm18Lgkm0);  // step 0 has landed
-    else
-      __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
-  }
-  GPUSQ_TEAM_BARRIER();
-
-  int ph = 0;
-  if (team == 1) {  // phase 0: nothing to do for the second team
-    for (int k = 0; k < ksteps; ++k) GPUSQ_TEAM_BARRIER();
-    ph = 1;
-  }
-  while (ph <= my_items) {
-    // ---- compute phase ph --------------------------------------------------------------------------------------
-    if (ph >= my_items) {  // one phase after the last tile: only the other team's last epilogue runs
-      for (int k = 0; k < ksteps; ++k) GPUSQ_TEAM_BARRIER();
-      break;
-    }
-    const Tile t = tile_of(ph);
-    acc_t acc[kBigTN][kBigTM];
+  // state of a wavefront across its compute and epilogue phases
+  acc_t acc[kBigTN][kBigTM];
+  v8i b0[kBigTM], b1[kBigTM];  // B operands of the current and the next K step (roles alternate)
+  v4i av[4];                   // A fragments in flight
+  int ai[kBigTN];              // index words
+  Tile t = tile_of(0);
+  BOffsets bo = b_offsets(wm, t.tm, lane);
+  // Everything a wavefront can do for its tile `item` before the phase in which it computes it: called after the
+  // barrier that ends the second-to-last step of the previous phase (the tile's first stage has landed by then) and
+  // before the last barrier of that phase.
+  auto set_up_tile = [&](int item) {
+    t = tile_of(item);
+    bo = b_offsets(wm, t.tm, lane);
 #pragma unroll
     for (int i = 0; i < kBigTN; ++i)
 #pragma unroll
       for (int j = 0; j < kBigTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
-    seek(ph, kRing - 1);
+    seek(item, kRing - 1);
     if constexpr (!RAW) {  // this wavefront's 128 channels of epilogue constants, into its own LDS array
       const int n0 = t.n_blk * kBigBN + wn * (kBigTN * 16);
 #pragma unroll
@@ -588,22 +508,72 @@ __global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, c
         if (has_bias) copy4_to_lds(a.bias, (uint32_t)n * 4u, prm_lds + 512u + (uint32_t)i * 256u);
       }
     }
-    const int g0 = ph * ksteps;
-    for (int ks = 0; ks < ksteps; ++ks) {
-      const int g = g0 + ks;
-      const bool requested = request(g + kRing - 1);
-      compute_stage<IS_I8>(ring + (size_t)(g & (kRing - 1)) * STAGE, acc, wn, wm, t.tm, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      if (requested)
-        __builtin_amdgcn_s_waitcnt(kWaitVm18Lgkm0);
-      else
-        __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+    load_step_head<IS_I8>(b0, av, ai, ring + (size_t)((item * ksteps) & (kRing - 1)) * STAGE, bo, a_off, i_off);
+  };
+
+  if (team == 0) {  // the first three K steps of the sequence
+    seek(0, 0);
+    int n_req = 0;
+    for (int g = 0; g < kRing - 1; ++g) {
+      if (pf_item < my_items) {
+#pragma unroll
+        for (int i = 0; i < kCopiesPerStep; ++i)
+          issue_step_copy<IS_I8>(i, ring_lds + (uint32_t)g * STAGE, pf_x, pf_w, pf_xoff, w, loff);
+        advance();
+        ++n_req;
+      }
+    }
+    if (n_req == kRing - 1)
+      __builtin_amdgcn_s_waitcnt(kWaitVm9Lgkm0);  // steps 0 and 1 have landed
+    else
+      __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+  }
+  GPUSQ_TEAM_BARRIER();
+
+  int ph = 0;
+  if (team == 0) {
+    set_up_tile(0);
+  } else {  // phase 0: the second team only gets ready for its first tile
+    for (int k = 0; k < ksteps; ++k) {
+      if (k == ksteps - 1 && my_items > 1) set_up_tile(1);
       GPUSQ_TEAM_BARRIER();
     }
+    ph = 1;
+  }
+  while (ph <= my_items) {
+    // ---- compute phase ph --------------------------------------------------------------------------------------
+    if (ph >= my_items) {  // one phase after the last tile: only the other team's last epilogue runs
+      for (int k = 0; k < ksteps; ++k) GPUSQ_TEAM_BARRIER();
+      break;
+    }
+    const int g0 = ph * ksteps;
+    auto step = [&](int ks, const v8i (&b)[kBigTM], v8i (&bn)[kBigTM]) {
+      const int g = g0 + ks;
+      const bool requested = pf_item < my_items;
+      const uint8_t* stage = ring + (size_t)(g & (kRing - 1)) * STAGE;
+      const uint8_t* next = ks + 1 < ksteps ? ring + (size_t)((g + 1) & (kRing - 1)) * STAGE : stage;
+      team_step<IS_I8>(stage, next, bo, acc, b, bn, av, ai, a_off, i_off, requested,
+                       ring_lds + (uint32_t)((g + kRing - 1) & (kRing - 1)) * STAGE, pf_x, pf_w, pf_xoff, w, loff);
+      __builtin_amdgcn_sched_barrier(0);
+      if (requested) {
+        __builtin_amdgcn_s_waitcnt(kWaitVm9Lgkm0);
+        advance();
+      } else {
+        __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+      }
+      GPUSQ_TEAM_BARRIER();
+    };
+    for (int ks = 0; ks < ksteps; ks += 2) {
+      step(ks, b0, b1);
+      if (ks + 1 < ksteps) step(ks + 1, b1, b0);
+    }
     ++ph;
-    // ---- epilogue phase ph: tile ph-1 --------------------------------------------------------------------------------
+    // ---- epilogue phase ph: tile ph-1; at its end, get ready for tile ph+1 -------------------------------------------
+    const int next_item = ph + 1;
     team_epilogue<IS_I8, GELU, OUT>(a, acc, my_prm, s_a, t.n_blk * kBigBN + wn * (kBigTN * 16), t.m0 + wm * t.tm * 16, lane, t.tm,
-                                    ksteps);
+                                    ksteps, [&]() {
+                                      if (next_item < my_items) set_up_tile(next_item);
+                                    });
     ++ph;
   }
 }
@@ -771,8 +741,7 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   if (work <= (int64_t)256 * 1024) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
   if (k_bytes % kStepBytes != 0) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);    // ragged K: zero-filling path
   const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
-  static const bool use_tile_kernel = [] { const char* e = getenv("GPUSQ_KERNEL"); return e && e[0] == 't' && e[1] == 'i'; }();
-  if (!use_tile_kernel) {
+  {
     // persistent grid: one workgroup of two teams per CU, never more workgroups than tiles
     const int resident = num_cus();
     const TilePlan plan = make_plan(a.M, a.N, resident);
@@ -797,28 +766,6 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
     }
     return check_launch();
   }
-  // persistent grid: two workgroups per CU (the LDS footprint allows no more), never more workgroups than tiles
-  const int resident = 2 * num_cus();
-  const TilePlan plan = make_plan(a.M, a.N, resident);
-  const dim3 grid((unsigned)(ceil_div(plan.total < resident ? plan.total : resident, 8) * 8));
-  if constexpr (IS_I8) {
-    if (a.out_dt == GPUSQ_I32)
-      spgemm_tile_kernel<true, 0, GPUSQ_I32><<<grid, 256, 0, s>>>(a, plan);
-    else if (a.out_dt == GPUSQ_I8 && gelu)
-      spgemm_tile_kernel<true, 1, GPUSQ_I8><<<grid, 256, 0, s>>>(a, plan);
-    else if (a.out_dt == GPUSQ_I8)
-      spgemm_tile_kernel<true, 0, GPUSQ_I8><<<grid, 256, 0, s>>>(a, plan);
-    else if (gelu)
-      spgemm_tile_kernel<true, 1, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
-    else
-      spgemm_tile_kernel<true, 0, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
-  } else {
-    if (gelu)
-      spgemm_tile_kernel<false, 1, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
-    else
-      spgemm_tile_kernel<false, 0, GPUSQ_F16><<<grid, 256, 0, s>>>(a, plan);
-  }
-  return check_launch();
 }
 
 gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s) {

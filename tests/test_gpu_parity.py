@@ -357,6 +357,38 @@ def test_c1_full_size_sampled_rows_and_self_consistency(g):
     assert rel_err(host(yhd)[rows], ref) <= 2e-3
 
 
+# Shapes that take the two-team large-tile kernel (M*N > 256K, K a multiple of the K step) and exercise its corner
+# cases: 1, 2, 3 and 5 K steps (copy requests that run across several tiles, odd step counts), fewer tiles than CUs,
+# several tiles per workgroup with short tail tiles, N that is not a multiple of 256 or of 8, M that is not a multiple of 16.
+TEAM_SHAPES = [(2100, 128, 520, 11), (1500, 256, 388, 12), (4500, 640, 1024, 13), (9000, 384, 2304, 14), (12345, 128, 264, 15)]
+
+
+@pytest.mark.parametrize("M,K,N,seed", TEAM_SHAPES)
+def test_large_tile_kernel_corner_shapes(g, M, K, N, seed):
+    p = Int8Problem(M, K, N, seed)
+    d = gpu_prepare_int8(g, p.W32, p.X32)
+    exp = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
+    acc = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+    assert np.array_equal(host(acc), exp)
+    assert torch.equal(acc, g.gemm_int8_dense(d["Xq"], d["Wq"], out_dtype=torch.int32))
+    bias = dev(p.bias)
+    y = host(g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=bias))
+    assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(exp, p.s_a, p.s_w, p.bias)["y16"].view(np.uint16))
+    yg = host(g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=bias, gelu=True))
+    assert ulp_diff_f16(yg, oracle.epilogue_int8_f64(exp, p.s_a, p.s_w, p.bias, gelu=True)["y16"]).max() <= 1
+    so = np.float32(np.abs(exp).max() * p.s_a * p.s_w.max() / 127.0)
+    q = host(g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], out_dtype=torch.int8,
+                           out_scale=dev(np.array([so], np.float32))))
+    assert np.array_equal(q, oracle.epilogue_int8_f32(exp, p.s_a, p.s_w, None, out_scale=float(so))["q8"])
+    # FP16 path on the same shape (twice as many K steps), exact on small integers
+    X, W, Wh, vals, meta, _ = fp16_problem(M, K, N, seed, integers=True)
+    v, m = g.compress(dev(Wh))
+    packed = g.pack(v, m, K)
+    _, a64 = oracle.spgemm_fp16(X, vals, meta)
+    yh = host(g.spgemm_fp16(dev(X), packed, N))
+    assert np.array_equal(yh.view(np.uint16), oracle.epilogue_fp16_f64(a64)["y16"].view(np.uint16))
+
+
 # ------------------------------------------------------------------------------------------------ error paths
 def test_error_statuses(g):
     W = dev(np.zeros((4, 6), np.float32))
