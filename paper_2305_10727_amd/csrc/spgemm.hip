@@ -383,7 +383,7 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
           __builtin_amdgcn_s_waitcnt(kWaitVm0);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (row_ok[mt]) store_8_at<IS_I8, OUT>(a, yrow[mt] + nb * OB, n_wave + nl, v, raw);
+        if (row_ok[mt]) store_8_at<IS_I8, OUT, true>(a, yrow[mt] + nb * OB, n_wave + nl, v, raw);
       }
       const int target = ((batch + 1) * ksteps) >> 4;
       while (done < target) {
