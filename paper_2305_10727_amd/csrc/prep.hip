@@ -406,29 +406,47 @@ gpusq_status launch_pack(const void* values, const uint8_t* meta, void* packed, 
 // bytes and 4 (2) index bytes; the thread prunes its groups of 4, quantises or rounds them, applies the compression
 // rule to the low-precision group, and writes the unit to every requested output.  All arithmetic is the same
 // sequence of operations as the separate kernels above, so the results are bit-identical to running them in turn.
+// A workgroup handles `rows_per_block` (1, 2, 4 or 8) consecutive channels with 256 / rows_per_block threads each, so
+// that short rows (K = 768 has only 24 lane units) still keep most of the workgroup busy.
 template <bool IS_I8>
 __global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __restrict__ W, float* __restrict__ Wp,
                                                               uint8_t* __restrict__ Wlow, float* __restrict__ w_scale,
                                                               uint8_t* __restrict__ values, uint8_t* __restrict__ meta,
-                                                              uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps) {
-  extern __shared__ float row[];
+                                                              uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t ksteps,
+                                                              int rows_per_block) {
+  extern __shared__ float rows_lds[];  // rows_per_block rows of K floats
+  __shared__ float red[256];
   constexpr int E = step_elems(IS_I8), ES = IS_I8 ? 1 : 2, KL = E / 4, IB = IS_I8 ? 4 : 2;
-  const int64_t n = blockIdx.x;
-  const float* w = W + n * K;
+  const int tpr = 256 / rows_per_block;         // threads per row
+  const int lr = (int)threadIdx.x / tpr;        // local row
+  const int tr = (int)threadIdx.x % tpr;        // thread within the row
+  const int64_t n = (int64_t)blockIdx.x * rows_per_block + lr;
+  const bool live = n < N;
+  float* row = rows_lds + (int64_t)lr * K;
   float amax = 0.0f;
-  for (int64_t k = (int64_t)threadIdx.x * 4; k < K; k += 1024) {
-    const float4 v = *(const float4*)(w + k);
-    *(float4*)(row + k) = v;
-    amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+  if (live) {
+    const float* w = W + n * K;
+    for (int64_t k = (int64_t)tr * 4; k < K; k += (int64_t)tpr * 4) {
+      const float4 v = *(const float4*)(w + k);
+      *(float4*)(row + k) = v;
+      amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
   }
   float s = 1.0f;
-  if constexpr (IS_I8) {
-    amax = block_max(amax);  // contains the barrier that publishes row[]
+  if constexpr (IS_I8) {  // max over the row's threads (any order gives the same maximum), through LDS
+    red[threadIdx.x] = amax;
+    __syncthreads();  // also publishes the rows
+    for (int h = tpr >> 1; h > 0; h >>= 1) {
+      if (tr < h) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + h]);
+      __syncthreads();
+    }
+    amax = red[lr * tpr];
     s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
-    if (threadIdx.x == 0) w_scale[n] = s;
+    if (live && tr == 0) w_scale[n] = s;
   } else {
     __syncthreads();
   }
+  if (!live) return;
   const int64_t mrb = (K / 4 + 1) / 2;
   const int64_t units = (K + KL - 1) / KL;
   // packed position of this channel: tile nb, fragment f, row r of the fragment
@@ -437,7 +455,7 @@ __global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __res
   // inverse of packed_row_to_channel: c64 = 32*(t/2) + 8*(r/4) + 4*(t%2) + r%4
   const int t = 2 * (c64 >> 5) + ((c64 >> 2) & 1), r = 4 * ((c64 >> 3) & 3) + (c64 & 3);
   const int f = blk * 4 + t;
-  for (int64_t u = threadIdx.x; u < units; u += 256) {
+  for (int64_t u = tr; u < units; u += tpr) {
     const int64_t k0 = u * KL;
     uint8_t vbytes[16];
     uint8_t ibytes[IB];
@@ -538,7 +556,12 @@ gpusq_status launch_prepare_weights(const float* W, gpusq_dtype dt, float* Wp, v
                                     uint8_t* meta, void* packed, int64_t N, int64_t K, hipStream_t s) {
   const bool is_i8 = dt == GPUSQ_I8;
   const int64_t ksteps = ceil_div(K, step_elems(is_i8));
-  const size_t lds = (size_t)K * sizeof(float);
+  // as many rows per workgroup as keep every row's threads busy (one thread per 32-byte lane unit) within 64 KB of LDS
+  const int64_t units = ceil_div(K, step_elems(is_i8) / 4);
+  int rpb = 1;
+  while (rpb < 8 && 256 / (rpb * 2) >= units && (size_t)K * sizeof(float) * (rpb * 2) <= 64 * 1024) rpb *= 2;
+  const size_t lds = (size_t)K * sizeof(float) * rpb;
+  const unsigned grid = (unsigned)ceil_div(N, rpb);
   const bool padded = (N % kTileRows) != 0 || (K % step_elems(is_i8)) != 0;
   if (padded) {
     const int64_t total_lanes = ceil_div(N, kTileRows) * ksteps * 16 * 64;
@@ -549,11 +572,11 @@ gpusq_status launch_prepare_weights(const float* W, gpusq_dtype dt, float* Wp, v
       clear_packed_padding_kernel<false><<<blocks, 256, 0, s>>>((uint8_t*)packed, N, K, ksteps, total_lanes);
   }
   if (is_i8)
-    prepare_weights_kernel<true><<<(unsigned)N, 256, lds, s>>>(W, Wp, (uint8_t*)Wlow, w_scale, (uint8_t*)values, meta,
-                                                               (uint8_t*)packed, N, K, ksteps);
+    prepare_weights_kernel<true><<<grid, 256, lds, s>>>(W, Wp, (uint8_t*)Wlow, w_scale, (uint8_t*)values, meta, (uint8_t*)packed, N, K,
+                                                        ksteps, rpb);
   else
-    prepare_weights_kernel<false><<<(unsigned)N, 256, lds, s>>>(W, Wp, (uint8_t*)Wlow, w_scale, (uint8_t*)values, meta,
-                                                                (uint8_t*)packed, N, K, ksteps);
+    prepare_weights_kernel<false><<<grid, 256, lds, s>>>(W, Wp, (uint8_t*)Wlow, w_scale, (uint8_t*)values, meta, (uint8_t*)packed, N, K,
+                                                         ksteps, rpb);
   return check_launch();
 }
 
