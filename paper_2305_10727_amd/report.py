@@ -1,0 +1,106 @@
+"""Per-GEMM timing table over the linear-layer shapes of all workload configurations (c0 ... c4): sparse INT8 and FP16
+against their dense twins, with buffers that stay in the memory-side cache ("hot") and with a rotation of buffer sets
+larger than it ("cold").  `python -m paper_2305_10727_amd.report [--out FILE]` on a GPU machine; prints a markdown table.
+
+Inputs are random device tensors of the configurations' shapes and distributions (N(0,1) activations, N(0, 0.02)
+weights); every number is a sparse or dense GEMM launch through the C ABI, timed with HIP events on the launch stream.
+"""
+import argparse
+
+import torch
+
+from . import synth
+from .pipeline import SparseLinear
+
+SPARSE_PEAK = {"int8": 10070.0, "fp16": 5030.0}  # nominal dense-equivalent T(FL)OP/s of the gfx950 sparse matrix instructions
+INFINITY_CACHE = 256 << 20
+
+
+def _time(fns, iters):
+    """average us per launch cycling through `fns` (one per buffer set)"""
+    for f in fns:
+        f()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(iters):
+        fns[i % len(fns)]()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters * 1e3
+
+
+def layer_rows(M, K, N, gelu, iters):
+    dev = torch.device("cuda")
+    rows = []
+    for prec in ("int8", "fp16"):
+        e = 1 if prec == "int8" else 2
+        per_set = M * K * e + M * N * 2
+        n_sets = max(3, -(-2 * INFINITY_CACHE // per_set))  # cold: the sets together exceed twice the cache
+        n_sets = min(n_sets, max(3, (6 << 30) // per_set))
+        W = torch.randn(N, K, device=dev) * 0.02
+        bias = torch.randn(N, device=dev) * 0.01
+        sets = []
+        for _ in range(n_sets):
+            lin = SparseLinear(M, K, N, prec, gelu=gelu, bias=True)
+            if sets:  # weights are shared between the sets: only the activations and the outputs rotate
+                for name in ("W_low", "values", "meta", "packed", "W_pruned"):
+                    setattr(lin, name, getattr(sets[0][0], name))
+                if prec == "int8":
+                    lin.w_scale = sets[0][0].w_scale
+            else:
+                lin.prepare_weights(W, fused=K * 4 <= 64 * 1024)
+            X = torch.randn(M, K, device=dev).half()
+            if prec == "int8":
+                lin.quantize_activations(X)
+            sets.append((lin, X))
+        ops = 2.0 * M * N * K
+        t_hot = _time([lambda s=sets[0]: s[0].gemm(s[1], bias)], iters)
+        t_cold = _time([lambda s=s: s[0].gemm(s[1], bias) for s in sets], iters)
+        td_hot = _time([lambda s=sets[0]: s[0].gemm_dense(s[1], bias)], iters)
+        td_cold = _time([lambda s=s: s[0].gemm_dense(s[1], bias) for s in sets], iters)
+        alg = M * K * e + N * K * e // 2 + N * K // 8 + 8 * N + M * N * 2
+        rows.append(dict(prec=prec, t_hot=t_hot, t_cold=t_cold, td_hot=td_hot, td_cold=td_cold, tops=ops / t_cold / 1e6,
+                         frac=ops / t_cold / 1e6 / SPARSE_PEAK[prec], hbm=alg / t_cold / 1e6 / 8.0, sets=n_sets))
+        del sets
+        torch.cuda.empty_cache()
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default="")
+    ap.add_argument("--iters", type=int, default=30)
+    ap.add_argument("--configs", default="c0,c1,c2,c3,c4_vitl,c4_vith")
+    a = ap.parse_args()
+    lines = ["| config | layer | M | K | N | GELU | path | sparse cold us | sparse hot us | dense cold us | dense hot us | speedup (cold) | "
+             "TOPS dense-equiv. (cold) | of sparse peak | of 8 TB/s (algorithmic bytes) |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    totals = {}
+    for cfg_name in a.configs.split(","):
+        cfg = synth.CONFIGS[cfg_name]
+        M = cfg["M"]
+        for name, K, N, gelu, _dist in cfg["layers"]:
+            for r in layer_rows(M, K, N, gelu, a.iters):
+                lines.append("| %s | %s | %d | %d | %d | %s | %s | %.1f | %.1f | %.1f | %.1f | %.2f | %.0f | %.3f | %.3f |" % (
+                    cfg_name, name, M, K, N, "yes" if gelu else "no", r["prec"], r["t_cold"], r["t_hot"], r["td_cold"], r["td_hot"],
+                    r["td_cold"] / r["t_cold"], r["tops"], r["frac"], r["hbm"]))
+                key = (cfg_name, r["prec"])
+                t = totals.setdefault(key, [0.0, 0.0, 0.0])
+                t[0] += r["t_cold"] * cfg["depth"]
+                t[1] += r["td_cold"] * cfg["depth"]
+                t[2] += 2.0 * M * N * K * cfg["depth"]
+                print(lines[-1], flush=True)
+    lines += ["", "Whole configuration (sum over its layers x depth, cold buffers; the same weights are reused across the depth):", "",
+              "| config | path | sparse ms | dense ms | speedup | TOPS dense-equiv. |", "|---|---|---|---|---|---|"]
+    for (cfg_name, prec), (ts, td, ops) in totals.items():
+        lines.append("| %s | %s | %.3f | %.3f | %.2f | %.0f |" % (cfg_name, prec, ts / 1e3, td / 1e3, td / ts, ops / ts / 1e6))
+    text = "\n".join(lines) + "\n"
+    print(text)
+    if a.out:
+        with open(a.out, "w") as fh:
+            fh.write(text)
+
+
+if __name__ == "__main__":
+    main()
