@@ -46,6 +46,47 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // row in one store; fragments 2 and 3 give the next 32 channels the same way.
 __host__ __device__ inline int packed_row_to_channel(int t, int r) { return 32 * (t >> 1) + 8 * (r >> 2) + 4 * (t & 1) + (r & 3); }
 
+// Integer code of x under the scale s: clamp(rint(x / s), -127, 127) with the IEEE fp32 division of the definition
+// (not a reciprocal multiply) and round-half-even, NaN -> 0, so that the code is decided exactly as a plain CPU
+// evaluation of the formula decides it -- but without paying for a division per element.  r = fl(1 / s) (correctly
+// rounded, computed once per scale).  t = x * r carries two roundings, |t - x/s| <= |x/s| (2^-23 + 2^-48), and the
+// correctly rounded quotient is within 2^-24 |x/s| of x/s, so the quotient lies within 0.38 |t| 2^-21 of t.  rint()
+// of the two can differ only if a half-integer lies between them or on one of them, which is excluded when t is at
+// least |t| 2^-21 away from every half-integer (t - floor(t) is exact in fp32).  Only the rare element inside that
+// band (about 1 in 10^5 for |t| near 100) pays for the division; |t| >= 2^20, where the test always fails, is clamped
+// either way.  +-inf and tiny or zero t take the multiply path and give the same code as the division.
+__device__ __forceinline__ int finish_code(float x, float q) {
+  q = rintf(q);
+  q = fminf(fmaxf(q, -127.0f), 127.0f);  // NaN -> -127 -> handled below
+  return (x != x) ? 0 : (int)q;
+}
+// N values at once: the band test of all N values of all lanes is folded into one wavefront-uniform branch, so the
+// common case executes no division at all (a per-element conditional is turned into a select by the compiler, which
+// then evaluates the division for every element).
+template <int N>
+__device__ __forceinline__ void quantize_codes(const float (&x)[N], float s, float r, int (&q)[N]) {
+  float t[N];
+  bool near_half = false;
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    t[j] = x[j] * r;
+    near_half |= fabsf(__builtin_amdgcn_fractf(t[j]) - 0.5f) < fabsf(t[j]) * 0x1p-21f;
+  }
+  if (__builtin_amdgcn_ballot_w64(near_half) != 0) {  // some element of some lane sits next to a rounding boundary
+#pragma unroll
+    for (int j = 0; j < N; ++j) t[j] = __fdiv_rn(x[j], s);
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) q[j] = finish_code(x[j], t[j]);
+}
+__device__ __forceinline__ int quantize_code(float x, float s, float r) {
+  const float xs[1] = {x};
+  int q[1];
+  quantize_codes<1>(xs, s, r, q);
+  return q[0];
+}
+__device__ __forceinline__ float scale_reciprocal(float s) { return __fdiv_rn(1.0f, s); }
+
 void set_last_hip_error(hipError_t e);
 
 struct GemmArgs {

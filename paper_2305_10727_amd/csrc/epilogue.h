@@ -65,13 +65,6 @@ __device__ __forceinline__ void gelu_f32_x8(float (&v)[8]) {
   pin8(v);
 }
 
-// q = clamp(rint(v / s), -127, 127): the same IEEE division + round-half-even as the quantiser of the activations
-__device__ __forceinline__ int requantize_code(float v, float s) {
-  float r = rintf(__fdiv_rn(v, s));
-  r = fminf(fmaxf(r, -127.0f), 127.0f);
-  return (v != v) ? 0 : (int)r;
-}
-
 // Per-channel epilogue constants of a workgroup's output channels, staged in LDS: c[n] = act_scale * w_scale[n]
 // (1 on the FP16 path) and b[n] = bias[n] (0 when there is no bias, which leaves fma(x, c, 0) == x * c and
 // acc + 0 == acc bit for bit).  fetch() issues the global loads early (one channel per thread), publish() writes
@@ -126,11 +119,12 @@ __device__ __forceinline__ void store_8_at(const GemmArgs& a, void* yp, int n, c
     *(ep_v4i*)y = ep_v4i{raw[0], raw[1], raw[2], raw[3]};
     if (second) *(ep_v4i*)(y + 4) = ep_v4i{raw[4], raw[5], raw[6], raw[7]};
   } else if (IS_I8 && out_dt == GPUSQ_I8) {
-    const float so = a.out_scale[0];
+    const float so = a.out_scale[0], rso = scale_reciprocal(so);  // the same code rule as the quantiser of the activations
     int8_t* y = (int8_t*)yp;
     int q[8];
+    quantize_codes<8>(v, so, rso, q);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) q[j] = requantize_code(v[j], so) & 0xFF;
+    for (int j = 0; j < 8; ++j) q[j] &= 0xFF;
     const int lo = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24), hi = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
     if (whole) {
       *(ep_v2i*)y = ep_v2i{lo, hi};

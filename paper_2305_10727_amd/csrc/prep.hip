@@ -91,14 +91,6 @@ gpusq_status launch_cast_f16(const float* in, void* out, int64_t n, hipStream_t 
 __device__ __forceinline__ float load_as_f32(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_as_f32(const _Float16* p, int64_t i) { return (float)p[i]; }
 
-// q = clamp(rint(x / s)): IEEE fp32 division (not a reciprocal multiply) and round-half-even, so that the integer
-// code is decided exactly as a plain CPU evaluation of the same formula decides it.
-__device__ __forceinline__ int quantize_code(float x, float s) {
-  float r = rintf(__fdiv_rn(x, s));
-  r = fminf(fmaxf(r, -127.0f), 127.0f);  // NaN -> -127 -> handled below
-  return (x != x) ? 0 : (int)r;
-}
-
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -124,16 +116,18 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const T* __restrict_
     s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
     if (lane == 0) scale[row] = s;
   }
+  const float rs = scale_reciprocal(s);
   int8_t* q = Q + row * cols;
   if ((cols & 3) == 0) {
     for (int64_t c = (int64_t)lane * 4; c < cols; c += 256) {
-      const int a = quantize_code(load_as_f32(x, c), s), b = quantize_code(load_as_f32(x, c + 1), s);
-      const int cc = quantize_code(load_as_f32(x, c + 2), s), d = quantize_code(load_as_f32(x, c + 3), s);
-      *(uint32_t*)(q + c) = (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(cc & 0xFF) << 16) |
-                            ((uint32_t)(d & 0xFF) << 24);
+      const float xs[4] = {load_as_f32(x, c), load_as_f32(x, c + 1), load_as_f32(x, c + 2), load_as_f32(x, c + 3)};
+      int qc[4];
+      quantize_codes<4>(xs, s, rs, qc);
+      *(uint32_t*)(q + c) = (uint32_t)(qc[0] & 0xFF) | ((uint32_t)(qc[1] & 0xFF) << 8) | ((uint32_t)(qc[2] & 0xFF) << 16) |
+                            ((uint32_t)(qc[3] & 0xFF) << 24);
     }
   } else {
-    for (int64_t c = lane; c < cols; c += 64) q[c] = (int8_t)quantize_code(load_as_f32(x, c), s);
+    for (int64_t c = lane; c < cols; c += 64) q[c] = (int8_t)quantize_code(load_as_f32(x, c), s, rs);
   }
 }
 
@@ -196,19 +190,22 @@ __global__ void __launch_bounds__(256) quantize_tensor_kernel(const T* __restric
   } else {
     s = scale[0];
   }
+  const float rs = scale_reciprocal(s);
   const int64_t stride = (int64_t)gridDim.x * blockDim.x * 8;
   for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < n; i += stride) {
     if (i + 8 <= n) {
       float v[8];
       load8(X + i, v);
+      int qc[8];
+      quantize_codes<8>(v, s, rs, qc);
       uint32_t w[2];
 #pragma unroll
       for (int h = 0; h < 2; ++h)
-        w[h] = (uint32_t)(quantize_code(v[4 * h], s) & 0xFF) | ((uint32_t)(quantize_code(v[4 * h + 1], s) & 0xFF) << 8) |
-               ((uint32_t)(quantize_code(v[4 * h + 2], s) & 0xFF) << 16) | ((uint32_t)(quantize_code(v[4 * h + 3], s) & 0xFF) << 24);
+        w[h] = (uint32_t)(qc[4 * h] & 0xFF) | ((uint32_t)(qc[4 * h + 1] & 0xFF) << 8) | ((uint32_t)(qc[4 * h + 2] & 0xFF) << 16) |
+               ((uint32_t)(qc[4 * h + 3] & 0xFF) << 24);
       *(uint2*)(Q + i) = uint2{w[0], w[1]};
     } else {
-      for (int64_t j = i; j < n; ++j) Q[j] = (int8_t)quantize_code(load_as_f32(X, j), s);
+      for (int64_t j = i; j < n; ++j) Q[j] = (int8_t)quantize_code(load_as_f32(X, j), s, rs);
     }
   }
 }
@@ -447,6 +444,7 @@ __global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __res
     __syncthreads();
   }
   if (!live) return;
+  const float rs = scale_reciprocal(s);
   const int64_t mrb = (K / 4 + 1) / 2;
   const int64_t units = (K + KL - 1) / KL;
   // packed position of this channel: tile nb, fragment f, row r of the fragment
@@ -475,7 +473,10 @@ __global__ void __launch_bounds__(256) prepare_weights_kernel(const float* __res
         if (Wp) *(float4*)(Wp + n * K + k) = p;
         unsigned nib;
         if constexpr (IS_I8) {
-          const int q0 = quantize_code(p.x, s), q1 = quantize_code(p.y, s), q2 = quantize_code(p.z, s), q3 = quantize_code(p.w, s);
+          const float ps[4] = {p.x, p.y, p.z, p.w};
+          int qc[4];
+          quantize_codes<4>(ps, s, rs, qc);
+          const int q0 = qc[0], q1 = qc[1], q2 = qc[2], q3 = qc[3];
           if (Wlow) *(uint32_t*)(Wlow + n * K + k) = (uint32_t)(q0 & 0xFF) | ((uint32_t)(q1 & 0xFF) << 8) | ((uint32_t)(q2 & 0xFF) << 16) | ((uint32_t)(q3 & 0xFF) << 24);
           const unsigned mq = keep_mask_of_4((unsigned)abs(q0), (unsigned)abs(q1), (unsigned)abs(q2), (unsigned)abs(q3));
           nib = nibble_of_mask(mq);

@@ -122,6 +122,38 @@ def test_quantize_tensor_bit_exact(g, dtype):
 
 
 # ------------------------------------------------------------------------------------------------ a3 compress
+def test_quantize_codes_next_to_rounding_boundaries(g):
+    """The kernels decide the code from x * (1/s) and divide only when that product is within a narrow band around a
+    half-integer; the definition is rint(x / s) with the IEEE division.  Inputs placed a few ulps either side of every
+    half-integer multiple of the scale (and on it), for several kinds of scale, must give the oracle's codes."""
+    rng = np.random.default_rng(5)
+    scales = [np.float32(1.0), np.float32(0.03125), np.float32(4.0 / 127.0), np.float32(3.1415927 / 127.0), np.float32(1e-3),
+              np.float32(0.99999994), np.float32(1.9999999), np.float32(np.nextafter(np.float32(0.5), np.float32(1.0))),
+              *(rng.uniform(1e-4, 10.0, 8).astype(np.float32))]
+    m = np.arange(-128, 128, dtype=np.float64) + 0.5
+    rows = []
+    for s in scales:
+        base = (m * np.float64(s)).astype(np.float32)
+        x = base.copy()
+        for k in range(1, 9):  # k ulps up and down
+            up, dn = base.copy(), base.copy()
+            for _ in range(k):
+                up, dn = np.nextafter(up, np.float32(np.inf)), np.nextafter(dn, np.float32(-np.inf))
+            x = np.concatenate([x, up, dn])
+        rows.append(x)
+    X = np.stack(rows).astype(np.float32)  # [len(scales), 256 * 17]
+    sc = np.array(scales, np.float32)
+    exp_rows, _ = oracle.quantize_rows_int8(X, scale=sc)
+    got_rows, _ = g.quantize_int8(dev(X), g.PER_ROW, scale=dev(sc))
+    assert np.array_equal(host(got_rows), exp_rows)
+    for i, s in enumerate(scales):
+        exp_t, _ = oracle.quantize_tensor_int8(X[i:i + 1], scale=float(s))
+        got_t, _ = g.quantize_int8(dev(X[i:i + 1]), g.PER_TENSOR, scale=dev(np.array([s], np.float32)))
+        assert np.array_equal(host(got_t), exp_t)
+    # the re-quantising GEMM epilogue uses the same rule: identity weights turn X into the accumulators' source
+    # (covered for random data by test_int8_epilogues; here the boundary values go through a one-column "GEMM")
+
+
 @pytest.mark.parametrize("dtype", [np.float16, np.int8])
 def test_compress_decompress_bit_exact(g, dtype):
     rng = np.random.default_rng(3)
