@@ -421,6 +421,64 @@ def test_large_tile_kernel_corner_shapes(g, M, K, N, seed):
     assert np.array_equal(yh.view(np.uint16), oracle.epilogue_fp16_f64(a64)["y16"].view(np.uint16))
 
 
+def _sampled_rows(M, n_random=192, seed=0):
+    return np.unique(np.concatenate([np.arange(64), np.arange(M - 160, M), np.random.default_rng(seed).integers(0, M, n_random)]))
+
+
+FULL_SIZE_LAYERS = [
+    # (config, layer index): the shapes the other workload configurations add to c1
+    ("c2", 0), ("c2", 1), ("c2", 3),          # ViT-Base qkv, proj, fc2 (GELU-shaped input, K = 3072) at batch 128
+    ("c3", 2), ("c3", 3),                     # Swin-B stage 3 fc1 (GELU), fc2 at batch 64
+    ("c4_vitl", 3), ("c4_vith", 2),           # ViT-L fc2 (K = 4096), ViT-H fc1 (GELU, M = 65792, N = 5120) at batch 256
+]
+
+
+@pytest.mark.parametrize("cfg_name,layer", FULL_SIZE_LAYERS)
+def test_full_size_layers_sampled_rows(g, cfg_name, layer):
+    """Full-size linear layers of configurations c2-c4 through the same launch path as the benchmark; the oracle
+    computes sampled rows (first 64, last 160 including the ragged tail tiles, 192 random) one by one."""
+    cfg = synth.CONFIGS[cfg_name]
+    M = cfg["M"]
+    _, K, N, gelu, dist = cfg["layers"][layer]
+    ids = (100 + list(synth.CONFIGS).index(cfg_name), layer)
+    X = synth.activations(M, K, dist, seed=cfg["seed"], ids=ids)
+    W = synth.weights(N, K, seed=cfg["seed"], ids=ids)
+    bias = synth.bias(N, seed=cfg["seed"], ids=ids)
+    rows = _sampled_rows(M)
+    # INT8 path
+    d = gpu_prepare_int8(g, W, X)
+    P, _ = oracle.prune_2to4(W)
+    Wq, s_w = oracle.quantize_rows_int8(P)
+    s_a = np.float32(np.abs(X).max() / np.float32(127.0))
+    assert host(d["s_a"])[0] == s_a
+    Xq_rows, _ = oracle.quantize_tensor_int8(X[rows], scale=float(s_a))
+    assert np.array_equal(host(d["Xq"])[rows], Xq_rows) and np.array_equal(host(d["Wq"]), Wq)
+    vals, meta, _ = oracle.compress(Wq)
+    exp = oracle.spgemm_int8(Xq_rows, vals, meta)
+    acc = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+    assert np.array_equal(host(acc)[rows], exp)
+    del acc
+    y = g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), gelu=gelu)
+    o = oracle.epilogue_int8_f64(exp, s_a, s_w, bias, gelu=gelu)
+    assert ulp_diff_f16(host(y)[rows], o["y16"]).max() <= 1
+    if not gelu:
+        assert np.array_equal(host(y)[rows].view(np.uint16), oracle.epilogue_int8_f32(exp, s_a, s_w, bias)["y16"].view(np.uint16))
+    # sparse == dense twin on every row
+    yd = g.gemm_int8_dense(d["Xq"], d["Wq"], act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), gelu=gelu)
+    assert torch.equal(y, yd)
+    del y, yd, d
+    # FP16 path
+    Xh = X.astype(np.float16)
+    Wp = g.cast_f16(g.prune_2to4(dev(W)))
+    v, m = g.compress(Wp)
+    packed = g.pack(v, m, K)
+    yh = g.spgemm_fp16(dev(Xh), packed, N, bias=dev(bias), gelu=gelu)
+    vals16, meta16, _ = oracle.compress(P.astype(np.float16))
+    _, a64 = oracle.spgemm_fp16(Xh[rows], vals16, meta16)
+    ref = oracle.epilogue_fp16_f64(a64, bias, gelu)["ref"]
+    assert rel_err(host(yh)[rows], ref) <= 2e-3
+
+
 # ------------------------------------------------------------------------------------------------ error paths
 def test_error_statuses(g):
     W = dev(np.zeros((4, 6), np.float32))
