@@ -134,17 +134,23 @@ __device__ __forceinline__ void store_8_at(const GemmArgs& a, void* yp, int n, c
     }
   } else {
     _Float16* y = (_Float16*)yp;
+    // The fp32 value is rounded to fp32 before it is rounded to fp16: without the pin the compiler may fuse the last
+    // fp32 operation with the conversion (v_fma_mix*), which rounds once and differs in rare last bits.
+    float w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[j] = v[j];
+    pin8(w);
     if (whole) {
       ep_v8h h;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) h[j] = (_Float16)v[j];
+      for (int j = 0; j < 8; ++j) h[j] = (_Float16)w[j];
       if constexpr (STREAM)
         __builtin_nontemporal_store(h, (ep_v8h*)y);
       else
         *(ep_v8h*)y = h;
     } else {
-      *(ep_v4h*)y = ep_v4h{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
-      if (second) *(ep_v4h*)(y + 4) = ep_v4h{(_Float16)v[4], (_Float16)v[5], (_Float16)v[6], (_Float16)v[7]};
+      *(ep_v4h*)y = ep_v4h{(_Float16)w[0], (_Float16)w[1], (_Float16)w[2], (_Float16)w[3]};
+      if (second) *(ep_v4h*)(y + 4) = ep_v4h{(_Float16)w[4], (_Float16)w[5], (_Float16)w[6], (_Float16)w[7]};
     }
   }
 }

@@ -15,9 +15,9 @@
 //   D (4 VGPRs): lane l, register r -> row 4*(l/16)+r, column l%16.
 //
 // Two kernels:
-//   spgemm_team_kernel  256 n x 128 m tiles, operands brought into LDS by direct global->LDS copies (no staging
-//                       registers), one workgroup of two 4-wavefront teams per CU: one team runs the K loop of a tile
-//                       while the other runs the epilogue of the previous one.  Needs K*elemsize % 128 == 0.
+//   spgemm_tile_kernel  tiles of 256 channels x up to 256 rows, operands brought into a three-stage LDS ring by direct
+//                       global->LDS copies (no staging registers), one persistent workgroup of 8 wavefronts per CU.
+//                       Needs K*elemsize % 128 == 0.
 //   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
 #include "common.h"
 #include "epilogue.h"
@@ -94,30 +94,58 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename 
   }
 }
 
-// ------------------------------------------------------------------------------------------------ large-tile kernel
-constexpr int kBigBN = 256, kBigBM = 128, kBigTN = 8, kBigTM = 4;
-constexpr int kXStageBytes = kBigBM * kStepBytes;  // 16 KB: 128 rows x 128 bytes, 16-byte chunks XOR-swizzled per row
+// ------------------------------------------------------------------------------------------------ tile kernel
+// One persistent workgroup of 8 wavefronts per CU on tiles of 256 channels x 64*tm rows (tm <= 4): 2 wavefronts along n x
+// 4 along m, 128 channels x 16*tm rows and 128 accumulator registers each.  All wavefronts run the K loop of a tile,
+// then all run its epilogue.  With two wavefronts per SIMD in the same phase, two of them issue matrix instructions in
+// the K loop and two issue the epilogue's vector arithmetic (a lone wavefront cannot issue either kind back to back),
+// and the weight tile is brought into the CU once per 256 rows: 52 KB per K step through the vector-memory path, which
+// at 48-64 bytes per clock and CU is the narrowest pipe of the K loop.
+//
+// LDS: a ring of three stages (X slab 32 KB, kept values 16 KB, index words 4/2 KB).  K steps are numbered g = 0, 1, ...
+// over the workgroup's whole sequence of tiles; step g lives in stage g % 3.  One workgroup barrier per K step, in front
+// of fragment kBarrierFrag: by then a wavefront has issued, and waits for, the last LDS read of the step's stage, and
+// it waits for its own copies of step g+1 (the vector-memory counter retires in order, so "at most the copies of step
+// g+2 outstanding" means step g+1 has landed).  Behind the barrier stage g+1 is complete and is read ahead (the head of
+// the next step: its B operand, its first three A fragments, half of its index words), and stage g is free: the copies
+// of step g+3 are requested there, two whole steps before they are needed, also across tile boundaries (the next
+// tile's first steps land during the epilogue).  Every wavefront executes exactly one barrier per step of every tile
+// of the workgroup, plus one at start-up.
+constexpr int kTileBN = 256, kTileTN = 8, kTileTM = 4, kTileWM = 4, kRing = 3;
+constexpr int kXSlabBytes = kTileWM * kTileTM * 16 * kStepBytes;  // 32 KB: 256 rows x 128 bytes, 16-byte chunks XOR-swizzled per row
+constexpr int kBarrierFrag = 5;
+constexpr int kCopies = 7;  // copy instructions per wavefront and K step: 4 X blocks, 2 fragments, 1 KB of index words
 
-// The list of tiles of one launch.  The first `full_tiles` tiles are 256 channels x 128 rows (n fastest); the rows that
-// are left over after the last whole round of tiles over the resident workgroups are cut into shorter tiles of
-// 32*tail_tm rows, so that the last round costs a fraction of a full round instead of a whole one.
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]), all with lgkmcnt(0)
+constexpr int kWaitVm0 = 0x0070;    // vmcnt(0)
+constexpr int kWaitVm7 = 0x0077;    // vmcnt(kCopies)
+constexpr int kWaitVm14 = 0x007E;   // vmcnt(2 * kCopies)
+constexpr int kWaitVm23 = 0x4077;   // vmcnt(kCopies + 16)
+static_assert(kCopies == 7, "the wait immediates encode 7, 14 and 7 + 16");
+static_assert(kBarrierFrag + 3 == kTileTN && (kTileTN - kBarrierFrag) * kTileTM >= 2 * kTileTM + 1 &&
+                  (kTileTN - kBarrierFrag) * kTileTM >= kCopies, "slot plan of tile_step");
+
+// The list of tiles of one launch.  The first `full_tiles` tiles have 64*full_tm rows (n fastest); the rows behind the
+// last of them are cut into tail tiles of 64*tail_tm rows.  The host picks the three numbers so that the workgroup
+// with the most work finishes as early as possible (make_plan).
 struct TilePlan {
   int tiles_n;      // 256-channel blocks
+  int full_tm;      // 1..4
+  int full_chunks;  // row chunks covered by full tiles
   int full_tiles;   // = full_chunks * tiles_n
-  int full_chunks;  // 128-row chunks covered by full tiles
-  int tail_tm;      // 1..4: a tail tile has 32*tail_tm rows (slabs per wavefront)
+  int tail_tm;      // 1..4
   int total;        // full + tail tiles
 };
 
 struct Tile {
   int n_blk;
-  int tm;      // 16-row slabs per wavefront (2 wavefronts along m): the tile has 32*tm rows
+  int tm;      // 16-row slabs per wavefront (4 wavefronts along m): the tile has 64*tm rows
   int64_t m0;
 };
 
 // Item i of the list of XCD x: the XCD's share of the full tiles (a contiguous run, so tiles that share an X slab
 // meet in one L2), then its share of the tail tiles.
-__device__ __forceinline__ int xcd_items(const TilePlan& p, int x, int& f0, int& nf, int& t0) {
+__host__ __device__ __forceinline__ int xcd_items(const TilePlan& p, int x, int& f0, int& nf, int& t0) {
   const int tail = p.total - p.full_tiles;
   f0 = (int)((int64_t)x * p.full_tiles / 8);
   nf = (int)((int64_t)(x + 1) * p.full_tiles / 8) - f0;
@@ -129,32 +157,17 @@ __device__ __forceinline__ Tile decode_tile(const TilePlan& p, int idx) {
   Tile t;
   if (idx < p.full_tiles) {
     t.n_blk = idx % p.tiles_n;
-    t.m0 = (int64_t)(idx / p.tiles_n) * kBigBM;
-    t.tm = kBigTM;
+    t.m0 = (int64_t)(idx / p.tiles_n) * (16 * kTileWM) * p.full_tm;
+    t.tm = p.full_tm;
   } else {
     const int j = idx - p.full_tiles;
     t.n_blk = j % p.tiles_n;
-    t.m0 = (int64_t)p.full_chunks * kBigBM + (int64_t)(j / p.tiles_n) * 32 * p.tail_tm;
+    t.m0 = ((int64_t)p.full_chunks * p.full_tm + (int64_t)(j / p.tiles_n) * p.tail_tm) * (16 * kTileWM);
     t.tm = p.tail_tm;
   }
   return t;
 }
 
-// Per-lane byte offsets, relative to the tile's first row, of the four X blocks this wavefront copies per K step:
-// block j = wave + 4i holds rows 8j..8j+7; lane l fetches row 8j + l/8, chunk (l%8) ^ ((row >> 1) & 7).  Rows past the
-// end of X re-read the last row (their results are never stored).
-__device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], const Tile& t, int M, int64_t k_bytes, int wave, int lane) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = 8 * (wave + i * 4) + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    const int64_t last = (int64_t)M - 1 - t.m0;  // >= 0: a tile starts inside X
-    const int64_t rr = r < last ? r : last;
-    xoff[i] = (uint32_t)(rr * k_bytes + c * 16);
-  }
-}
-
-// ------------------------------------------------------------------------------------------------ two-team kernel
 // Direct global->LDS copies issued through inline assembly: 64 lanes x 16 (4) bytes from `gbase` (wavefront-uniform,
 // scalar registers) + `voff` (per lane, unsigned 32 bits) to LDS bytes [lds, lds + 1024 (256)), lane l at lds + 16l
 // (4l).  The LDS base travels in M0.  Issued this way the copies are invisible to the compiler's wait-count
@@ -170,48 +183,42 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t*)p;
 }
 
-constexpr int kRing = 4;            // LDS stages: the K step being read plus three requested ahead
-constexpr int kCopiesPerStep = 9;   // copy instructions every wavefront of the computing team issues per K step
-
-// Copy i (0..8) of one wavefront's share (a quarter) of the copies that bring one K step of a tile into the LDS
-// stage at `stage_lds`: i = 0..3 are 1 KB blocks of the X slab (block j = w + 4i holds rows 8j..8j+7), i = 4..7
-// fragments of kept values, i = 8 1 KB of index words.  Each copy moves 64 lanes x 16 bytes from a wavefront-uniform
-// 64-bit base (scalar registers, advanced per K step by scalar adds) plus a 32-bit per-lane offset to 1 KB of
-// consecutive LDS, so a K step costs no vector ALU work for addressing.  The X slab is stored row-major with the
-// 16-byte chunk c of row r at chunk position c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the
-// same K offset fall in 16 different 16-byte bank groups; the swizzle is applied by choosing which global chunk each
-// lane fetches (tile_x_offsets).  Always
-// exactly kCopiesPerStep instructions per step, whatever the tile: a short tail tile copies rows it does not use, and
-// on the fp16 path (2 KB of index words) wavefronts 2 and 3 repeat the copies of wavefronts 0 and 1, so that the
-// waits can count instructions.
+// Copy i (0..6) of one wavefront's share (an eighth) of the copies that bring one K step of a tile into the LDS stage
+// at `stage_lds`: i = 0..3 are 1 KB blocks of the X slab (block j = wave + 8i holds rows 8j..8j+7), i = 4, 5 fragments
+// of kept values, i = 6 1 KB of index words.  Each copy moves 64 lanes x 16 bytes from a wavefront-uniform 64-bit base
+// (scalar registers, advanced per K step by scalar adds) plus a 32-bit per-lane offset to 1 KB of consecutive LDS, so
+// a K step costs no vector ALU work for addressing.  Always exactly kCopies instructions per step, whatever the tile
+// (a short tile copies rows it does not use; there are only 4 KB / 2 KB of index words, so some wavefronts repeat a
+// block), so that the waits can count instructions.
 template <bool IS_I8>
 __device__ __forceinline__ void issue_step_copy(int i, uint32_t stage_lds, const uint8_t* Xks, const uint8_t* Wks,
-                                                const uint32_t (&xoff)[4], int w, uint32_t loff) {
+                                                const uint32_t (&xoff)[4], int wave, uint32_t loff) {
   if (i < 4) {
-    copy16_to_lds(Xks, xoff[i], stage_lds + (uint32_t)(w + 4 * i) * 1024u);
-  } else if (i < 8) {
-    const int f = w + 4 * (i - 4);
-    copy16_to_lds(Wks + f * kFragValueBytes, loff, stage_lds + kXStageBytes + (uint32_t)f * kFragValueBytes);
+    copy16_to_lds(Xks, xoff[i], stage_lds + (uint32_t)(wave + 8 * i) * 1024u);
+  } else if (i < 6) {
+    const int f = wave + 8 * (i - 4);
+    copy16_to_lds(Wks + f * kFragValueBytes, loff, stage_lds + kXSlabBytes + (uint32_t)f * kFragValueBytes);
   } else {
-    const int iw = IS_I8 ? w : (w & 1);
-    copy16_to_lds(Wks + kTileValueBytes + iw * 1024, loff, stage_lds + kXStageBytes + kTileValueBytes + (uint32_t)iw * 1024u);
+    const int iw = IS_I8 ? (wave & 3) : (wave & 1);
+    copy16_to_lds(Wks + kTileValueBytes + iw * 1024, loff, stage_lds + kXSlabBytes + kTileValueBytes + (uint32_t)iw * 1024u);
   }
 }
 
-// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
-constexpr int kWaitVm0 = 0x0F70;         // vmcnt(0)
-constexpr int kWaitVm0Lgkm0 = 0x0070;    // vmcnt(0) lgkmcnt(0)
-constexpr int kWaitVm9Lgkm0 = 0x0079;    // vmcnt(kCopiesPerStep) lgkmcnt(0)
-static_assert(kCopiesPerStep == 9, "kWaitVm9Lgkm0 encodes one K step of copies");
-
-// Workgroup-wide barrier preceded by a scheduling barrier (the compiler must not move it above the matrix
-// instructions of the K step) and followed by a compiler-level memory barrier (no LDS read moves above it).
-#define GPUSQ_TEAM_BARRIER()              \
-  do {                                    \
-    __builtin_amdgcn_sched_barrier(0);    \
-    __builtin_amdgcn_s_barrier();         \
-    asm volatile("" ::: "memory");        \
-  } while (0)
+// Per-lane byte offsets, relative to the tile's first row, of the four X blocks a wavefront copies per K step: lane l
+// fetches row 8j + l/8 of block j, chunk (l%8) ^ ((row >> 1) & 7).  The X slab is stored row-major with the 16-byte
+// chunk c of row r at chunk position c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the same K
+// offset fall in 16 different 16-byte bank groups; the swizzle is applied by choosing which global chunk each lane
+// fetches.  Rows past the end of X re-read the last row (their results are never stored).
+__device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], int64_t m0, int M, int64_t k_bytes, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 8 * (wave + i * 8) + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const int64_t last = (int64_t)M - 1 - m0;  // >= 0: a tile starts inside X
+    const int64_t rr = r < last ? r : last;
+    xoff[i] = (uint32_t)(rr * k_bytes + c * 16);
+  }
+}
 
 // Per-lane byte offsets of the B operand inside an X slab: lane l reads row wm*16*tm + 16*mt + l%16, the 16-byte
 // chunks l/16 and 4 + l/16 of it (at their swizzled positions).
@@ -224,18 +231,9 @@ __device__ __forceinline__ BOffsets b_offsets(int wm, int tm, int lane) {
   return BOffsets{row + (uint32_t)((q ^ sw) * 16), row + (uint32_t)(((4 + q) ^ sw) * 16)};
 }
 
-// The four B slabs of one K step, from the X slab at `xslab`, into registers.
-__device__ __forceinline__ void load_b_slabs(v8i (&b)[kBigTM], const uint8_t* xslab, const BOffsets& o) {
-#pragma unroll
-  for (int mt = 0; mt < kBigTM; ++mt) {
-    const v4i lo = *(const v4i*)(xslab + o.lo + mt * 16 * kStepBytes), hi = *(const v4i*)(xslab + o.hi + mt * 16 * kStepBytes);
-    b[mt] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  }
-}
-
 // Index words of fragments 4*half .. 4*half+3 of this lane (its 8 words are consecutive at `ibase`).
 template <bool IS_I8>
-__device__ __forceinline__ void load_index_half(int (&ai)[kBigTN], int half, const uint8_t* ibase) {
+__device__ __forceinline__ void load_index_half(int (&ai)[kTileTN], int half, const uint8_t* ibase) {
   if constexpr (IS_I8) {
     const v4i x = *(const v4i*)(ibase + half * 16);
 #pragma unroll
@@ -251,57 +249,76 @@ __device__ __forceinline__ void load_index_half(int (&ai)[kBigTN], int half, con
   }
 }
 
-// What a computing wavefront holds in registers when a K step begins: the four B slabs of the step, its A fragments
-// 0..2 (fragment f lives in av[f % 4]) and the index words of fragments 0..3.
+// What a wavefront holds in registers when a K step begins: the four B slabs of the step, its A fragments 0..2
+// (fragment f lives in av[f % 4]) and the index words of fragments 0..3; read from the stage whose X slab is at `xslab`
+// and whose weight tile is at `wtile`.
 template <bool IS_I8>
-__device__ __forceinline__ void load_step_head(v8i (&b)[kBigTM], v4i (&av)[4], int (&ai)[kBigTN], const uint8_t* stage,
-                                               const BOffsets& bo, uint32_t a_off, uint32_t i_off) {
-  load_b_slabs(b, stage, bo);
-  load_index_half<IS_I8>(ai, 0, stage + kXStageBytes + i_off);
+__device__ __forceinline__ void load_step_head(v8i (&b)[kTileTM], v4i (&av)[4], int (&ai)[kTileTN], const uint8_t* xslab,
+                                               const uint8_t* wtile, const BOffsets& bo, uint32_t a_off, uint32_t i_off) {
 #pragma unroll
-  for (int f = 0; f < 3; ++f) av[f] = *(const v4i*)(stage + kXStageBytes + a_off + f * kFragValueBytes);
+  for (int mt = 0; mt < kTileTM; ++mt) {
+    const v4i lo = *(const v4i*)(xslab + bo.lo + mt * 16 * kStepBytes), hi = *(const v4i*)(xslab + bo.hi + mt * 16 * kStepBytes);
+    b[mt] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  }
+  load_index_half<IS_I8>(ai, 0, wtile + i_off);
+#pragma unroll
+  for (int f = 0; f < 3; ++f) av[f] = *(const v4i*)(wtile + a_off + f * kFragValueBytes);
 }
 
-// One K step of a computing wavefront (128 n x 64 m), software-pipelined by hand across steps.  When the step
-// begins its B operand (`b`), its A fragments 0..2 and the index words of fragments 0..3 are already in registers.
-// Per fragment the step issues: the LDS read of the fragment three ahead -- which for the last three fragments is
-// fragment 0..2 of the NEXT step, read from `next` --, one 16-byte piece of the next step's B operand (`bn`), the
-// index words it will need four fragments later, and then the four matrix instructions of the fragment.  So the
-// matrix pipe never waits for a step to "start": LDS latency is always covered by 12 matrix instructions, also across
-// the barrier between two steps.  (`next` = the stage of the next step of the same tile; after the last step of a
-// tile the reads ahead go to `stage` again and are discarded.)
-// The wavefront's kCopiesPerStep copy requests are spread over the step, one per fragment.
-template <bool IS_I8>
-__device__ __forceinline__ void team_step(const uint8_t* stage, const uint8_t* next, const BOffsets& bo,
-                                          typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM], const v8i (&b)[kBigTM],
-                                          v8i (&bn)[kBigTM], v4i (&av)[4], int (&ai)[kBigTN], uint32_t a_off, uint32_t i_off,
+// One K step of a wavefront (128 n x 64 m), software-pipelined by hand across steps.  When the step begins its B
+// operand `b`, its A fragments 0..2 and the index words of fragments 0..3 are in registers.  Per fragment the step
+// issues the LDS read of the fragment three ahead, then the four matrix instructions of the fragment; in front of
+// fragment kBarrierFrag the wait and the barrier (see the kernel); behind it, one per matrix instruction, the reads
+// of the next step's head from `next` into `bn`, `av`, `ai` and the wavefront's kCopies copy requests.  So every other
+// instruction is issued in the shadow of a matrix instruction.
+// wait_mode (wavefront-uniform): what may stay outstanding at the barrier: 0 = nothing, 1 = one step of copies,
+// 2 = one step of copies and 16 output stores.
+// last (wavefront-uniform): the last step of a tile reads nothing ahead (the head of the next tile's first step is read
+// after the epilogue, which keeps those registers free for the epilogue's arithmetic).
+// behind_barrier(): called once, right behind the barrier and before the step's copy requests.
+template <bool IS_I8, class Hook>
+__device__ __forceinline__ void tile_step(bool last, int wait_mode, const uint8_t* stage, const uint8_t* next, const BOffsets& bo,
+                                          typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM], const v8i (&b)[kTileTM],
+                                          v8i (&bn)[kTileTM], v4i (&av)[4], int (&ai)[kTileTN], uint32_t a_off, uint32_t i_off,
                                           bool requested, uint32_t req_lds, const uint8_t* req_x, const uint8_t* req_w,
-                                          const uint32_t (&xoff)[4], int w, uint32_t loff) {
-  const uint8_t* abase = stage + kXStageBytes + a_off;
-  const uint8_t* ibase = stage + kXStageBytes + i_off;
-  const uint8_t* abase_n = next + kXStageBytes + a_off;
-  const uint8_t* ibase_n = next + kXStageBytes + i_off;
-  // One matrix instruction per slot; in front of each, at most one LDS read and one copy request, so that every other
-  // instruction is issued in the shadow of a matrix instruction (a wavefront issues in order: a clump of reads and
-  // copies between two groups of matrix instructions would leave the matrix pipe idle for its whole length).
+                                          const uint32_t (&xoff)[4], int wave, uint32_t loff, Hook&& behind_barrier) {
+  const uint8_t* abase = stage + kXSlabBytes + a_off;
+  const uint8_t* ibase = stage + kXSlabBytes + i_off;
+  const uint8_t* abase_n = next + kXSlabBytes + a_off;
+  const uint8_t* ibase_n = next + kXSlabBytes + i_off;
 #pragma unroll
-  for (int tn = 0; tn < kBigTN; ++tn) {
+  for (int tn = 0; tn < kTileTN; ++tn) {
 #pragma unroll
-    for (int mt = 0; mt < kBigTM; ++mt) {
+    for (int mt = 0; mt < kTileTM; ++mt) {
+      if (tn == kBarrierFrag && mt == 0) {
+        __builtin_amdgcn_sched_barrier(0);  // the compiler must not move the wait above the matrix instructions before it
+        if (wait_mode == 0)
+          __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        else if (wait_mode == 1)
+          __builtin_amdgcn_s_waitcnt(kWaitVm7);
+        else
+          __builtin_amdgcn_s_waitcnt(kWaitVm23);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");  // no LDS read moves above the barrier
+        behind_barrier();
+      }
       if (mt == 0) {
-        const int f = tn + 3;
-        av[f & 3] = f < kBigTN ? *(const v4i*)(abase + f * kFragValueBytes) : *(const v4i*)(abase_n + (f - kBigTN) * kFragValueBytes);
+        const int f = tn + 3;  // f >= kTileTN exactly when tn >= kBarrierFrag: the next stage, behind the barrier
+        if (f < kTileTN)
+          av[f & 3] = *(const v4i*)(abase + f * kFragValueBytes);
+        else if (!last)
+          av[f & 3] = *(const v4i*)(abase_n + (f - kTileTN) * kFragValueBytes);
       }
-      if (mt == 1) {
-        const v4i piece = *(const v4i*)(next + ((tn & 1) ? bo.hi : bo.lo) + (tn >> 1) * 16 * kStepBytes);
+      if (tn == 0 && mt == 2) load_index_half<IS_I8>(ai, 1, ibase);
+      if (tn >= kBarrierFrag) {
+        const int slot = (tn - kBarrierFrag) * kTileTM + mt;  // 0..11
+        if (!last && slot < 2 * kTileTM) {
+          const v4i piece = *(const v4i*)(next + ((slot & 1) ? bo.hi : bo.lo) + (slot >> 1) * 16 * kStepBytes);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bn[tn >> 1][4 * (tn & 1) + j] = piece[j];
-      }
-      if (mt == 2 && tn == 0) load_index_half<IS_I8>(ai, 1, ibase);
-      if (mt == 2 && tn == 4) load_index_half<IS_I8>(ai, 0, ibase_n);
-      if (requested) {
-        if (mt == 3) issue_step_copy<IS_I8>(tn, req_lds, req_x, req_w, xoff, w, loff);
-        if (mt == 2 && tn == kBigTN - 1) issue_step_copy<IS_I8>(kBigTN, req_lds, req_x, req_w, xoff, w, loff);
+          for (int j = 0; j < 4; ++j) bn[slot >> 1][4 * (slot & 1) + j] = piece[j];
+        }
+        if (!last && slot == 2 * kTileTM) load_index_half<IS_I8>(ai, 0, ibase_n);
+        if (requested && slot < kCopies) issue_step_copy<IS_I8>(slot, req_lds, req_x, req_w, xoff, wave, loff);
       }
       __builtin_amdgcn_sched_barrier(0);
       acc[tn][mt] = smfmac<IS_I8>(av[tn & 3], b[mt], acc[tn][mt], ai[tn]);
@@ -310,33 +327,25 @@ __device__ __forceinline__ void team_step(const uint8_t* stage, const uint8_t* n
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// Epilogue of one wavefront of the team that is not computing: same lane -> output mapping as wave_epilogue, with
-//  * the per-channel constants read from the wavefront's own LDS array `p` (128 weight scales, then 128 biases),
-//  * `ksteps` workgroup barriers spread evenly over the 16 batches of 8 outputs per lane, so that this team stays in
-//    step with the K steps of the team that is computing (both execute the same number of barriers per phase),
-//  * a wait for the wavefront's own outstanding copies (requested for the other team's tile) after the first batch of
-//    arithmetic and before the first store and the first barrier: from then on this wavefront has stores in flight
-//    and never waits on the vector-memory counter again until its next compute phase,
-//  * `before_last_barrier()` called once, after the last batch and before the last barrier of the phase: the caller
-//    sets up the wavefront's next tile there (the accumulators are free by then).
-template <bool IS_I8, int GELU, int OUT, class Hook>
-__device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kBigTN][kBigTM],
-                                              const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active,
-                                              int ksteps, Hook&& before_last_barrier) {
+// Epilogue of one wavefront of the tile kernel for every output type and any N % 4 == 0: 128 channels x 16*tm_active rows
+// of accumulators -> Y in batches of 32 channels x 16 rows (one 16-byte store per lane and batch for fp16 output); same
+// lane -> output mapping as wave_epilogue, per-channel constants from the LDS array `p` (128 weight scales, then 128
+// biases).
+template <bool IS_I8, int GELU, int OUT>
+__device__ __forceinline__ void batch_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM],
+                                             const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active) {
   constexpr bool RAW = IS_I8 && OUT == GPUSQ_I32;
   constexpr int OB = dtype_bytes(OUT);
-  // address of this lane's first 8 channels in each of its 4 rows, computed once: a batch then only adds a constant
-  uint8_t* yrow[kBigTM];
-  bool row_ok[kBigTM];
+  uint8_t* yrow[kTileTM];
+  bool row_ok[kTileTM];
 #pragma unroll
-  for (int mt = 0; mt < kBigTM; ++mt) {
+  for (int mt = 0; mt < kTileTM; ++mt) {
     const int64_t m = m_wave + mt * 16 + (lane & 15);
     row_ok[mt] = m < a.M;
     yrow[mt] = (uint8_t*)a.Y + (m * a.N + n_wave + (lane >> 4) * 8) * OB;
   }
-  int done = 0;
 #pragma unroll
-  for (int g = 0; g < kBigTN / 2; ++g) {
+  for (int g = 0; g < kTileTN / 2; ++g) {
     const int nb = (g >> 1) * kRowBlock + (g & 1) * 32;  // first channel of the batch relative to n_wave (lane group 0)
     const int nl = nb + (lane >> 4) * 8;                 // this lane's first channel
     float c8[8], b8[8];
@@ -354,8 +363,7 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
       }
     }
 #pragma unroll
-    for (int mt = 0; mt < kBigTM; ++mt) {
-      const int batch = g * kBigTM + mt;
+    for (int mt = 0; mt < kTileTM; ++mt) {
       if (mt < tm_active) {
         float v[8];
         int raw[8];
@@ -378,57 +386,104 @@ __device__ __forceinline__ void team_epilogue(const GemmArgs& a, const typename 
           for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(v[j], c8[j], b8[j]);
         }
         if constexpr (GELU != 0) gelu_f32_x8(v);
-        if (batch == 0) {
-          __builtin_amdgcn_sched_barrier(0);
-          __builtin_amdgcn_s_waitcnt(kWaitVm0);
-          __builtin_amdgcn_sched_barrier(0);
-        }
         if (row_ok[mt]) store_8_at<IS_I8, OUT, true>(a, yrow[mt] + nb * OB, n_wave + nl, v, raw);
-      }
-      const int target = ((batch + 1) * ksteps) >> 4;
-      while (done < target) {
-        // the phase's last barrier always falls after the last batch: (15 * ksteps) >> 4 < ksteps
-        if (batch == 4 * kBigTM - 1 && done == ksteps - 1) before_last_barrier();
-        GPUSQ_TEAM_BARRIER();
-        ++done;
       }
     }
   }
 }
 
-// Workgroup = 8 wavefronts = two teams of 4 (2 along n x 2 along m, 128 channels x 64 rows and 128 accumulator
-// registers each), one workgroup per CU (the LDS footprint, 4 stages of 36 KB, allows no more); wavefronts 0-3 and 4-7 land on the four SIMDs once each, so every SIMD hosts one
-// wavefront of each team.  The workgroup walks over its tiles; team (i mod 2) computes tile i.  Time is cut into
-// phases of `ksteps` workgroup barriers: in phase i one team runs the K loop of tile i (matrix instructions, LDS
-// reads, copy requests) while the other runs the epilogue of tile i-1 (vector ALU, stores), then they swap.  The
-// epilogue's arithmetic and the output stores therefore always overlap matrix work on the same SIMD, the computing
-// team has all four LDS stages (copies run three K steps ahead, across tile boundaries), and because loads and stores
-// are issued by different wavefronts in any phase, waiting for copies never means waiting for stores.
-//
-// Copy protocol.  K steps are numbered g = 0, 1, ... over the whole sequence of tiles; step g lives in stage g mod 4.
-// The wavefronts of the team that computes step g request step g+3 during step g (stage (g+3) mod 4 was last read in
-// step g-1, which every wavefront left through a barrier after its LDS reads had returned), then wait until at most
-// the copies just requested are outstanding (vmcnt counts instructions, and every wavefront issues kCopiesPerStep
-// per step), then meet at the barrier.  Invariant: at the barrier that ends step g the data of all steps <= g+2 has
-// landed -- step g+2 was requested during step g-1, either by this team (covered by its wait) or, when g is the
-// first step of a tile, by the other team, which waits for all its copies before the first barrier of its epilogue
-// phase (see team_epilogue).  When nothing is requested in a step (the end of the sequence) the wait is for all
-// copies.  So during step g a wavefront may read stage g and stage g+1 (what it reads ahead for the next step), and a
-// wavefront of the epilogue team may read the stage of the first step of its next tile before the last barrier of
-// its phase (set_up_tile).
-// Every wavefront executes exactly 1 + (tiles + 1) * ksteps barriers.
+// fp16 epilogue that writes whole 128-byte lines.  The accumulator layout gives a lane (c = lane % 16, q = lane / 16) 8
+// consecutive channels of activation row c of a slab, so a plain 16-byte store per lane covers 16 rows x 64 bytes: half
+// lines, which the memory pipeline of a CU accepts at less than a third of the rate of whole lines (measured: 23-30 B/ns
+// per CU against 100 B/ns).  Here two batches of 32 channels (64 consecutive channels = 128 bytes of a row) are paired
+// and lanes c and c+8 of a 16-lane row swap one half through DPP (row_ror:8), after which the first store of the pair
+// covers rows 0..7 of the slab, the second rows 8..15, each lane writing 16 bytes of a whole line:
+//   lanes c < 8 : store 1 = own row, first half (own)        store 2 = row c+8, first half (from lane c+8)
+//   lanes c >= 8: store 1 = row c-8, second half (from c-8)  store 2 = own row, second half (own)
+// Needs N % 8 == 0 (a lane's 8 channels are inside or outside together).
+template <bool IS_I8, int GELU>
+__device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM],
+                                              const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active) {
+  const int c = lane & 15, q = lane >> 4, up = c >> 3;
+  // byte address of this lane's 16 bytes in the first store of slab 0, pair 0
+  uint8_t* y0 = (uint8_t*)a.Y + ((m_wave + (c & 7)) * a.N + n_wave) * 2 + up * 64 + q * 16;
+  const int64_t slab_bytes = (int64_t)16 * a.N * 2, half_bytes = (int64_t)8 * a.N * 2;
+#pragma unroll
+  for (int gp = 0; gp < kTileTN / 4; ++gp) {
+    const int nl = gp * kRowBlock + q * 8;  // first channel (relative to n_wave) of this lane's accumulators in the pair's first batch
+    float c8[2][8], b8[2][8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 8; j += 4) {
+        const float4 bb = *(const float4*)(p + 128 + nl + 32 * h + j);
+        b8[h][j] = bb.x; b8[h][j + 1] = bb.y; b8[h][j + 2] = bb.z; b8[h][j + 3] = bb.w;
+        if constexpr (IS_I8) {
+          const float4 cc = *(const float4*)(p + nl + 32 * h + j);
+          c8[h][j] = s_a * cc.x; c8[h][j + 1] = s_a * cc.y; c8[h][j + 2] = s_a * cc.z; c8[h][j + 3] = s_a * cc.w;
+        } else {
+          c8[h][j] = c8[h][j + 1] = c8[h][j + 2] = c8[h][j + 3] = 1.0f;
+        }
+      }
+    // the channels this lane stores: those of its own half of the line
+    const bool n_ok = n_wave + gp * kRowBlock + up * 32 + q * 8 < a.N;
+#pragma unroll
+    for (int mt = 0; mt < kTileTM; ++mt) {
+      if (mt < tm_active) {
+        ep_v4i H[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          float v[8];
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int j = 4 * t + r;
+              if constexpr (IS_I8)
+                v[j] = (float)acc[4 * gp + 2 * h + t][mt][r];
+              else
+                v[j] = acc[4 * gp + 2 * h + t][mt][r] + b8[h][j];
+            }
+          if constexpr (IS_I8) {
+            pin8(v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(v[j], c8[h][j], b8[h][j]);
+          }
+          if constexpr (GELU != 0) gelu_f32_x8(v);
+          pin8(v);  // the fp32 result is rounded to fp32 before it is rounded to fp16 (no fused fma-and-convert)
+          ep_v8h hh;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) hh[j] = (_Float16)v[j];
+          H[h] = __builtin_bit_cast(ep_v4i, hh);
+        }
+        ep_v4i s1, s2;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          // row_ror:8 = 0x128; bank_mask 0xC: lanes 8..15 of a row take the rotated source, 0x3: lanes 0..7
+          s1[d] = __builtin_amdgcn_update_dpp(H[0][d], H[1][d], 0x128, 0xF, 0xC, false);
+          s2[d] = __builtin_amdgcn_update_dpp(H[1][d], H[0][d], 0x128, 0xF, 0x3, false);
+        }
+        const int64_t row = m_wave + mt * 16 + (c & 7);
+        uint8_t* y = y0 + mt * slab_bytes + gp * (kRowBlock * 2);
+        if (n_ok && row < a.M) __builtin_nontemporal_store(s1, (ep_v4i*)y);
+        if (n_ok && row + 8 < a.M) __builtin_nontemporal_store(s2, (ep_v4i*)(y + half_bytes));
+      }
+    }
+  }
+}
+
 template <bool IS_I8, int GELU, int OUT>
-__global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, const TilePlan plan) {
+__global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, const TilePlan plan) {
   typedef typename AccT<IS_I8>::type acc_t;
   constexpr int ES = IS_I8 ? 1 : 2;
-  constexpr int STAGE = kXStageBytes + tile_bytes(IS_I8);
+  constexpr int STAGE = kXSlabBytes + tile_bytes(IS_I8);
   constexpr bool RAW = IS_I8 && OUT == GPUSQ_I32;
   __shared__ __attribute__((aligned(1024))) uint8_t ring[kRing * STAGE];
-  __shared__ __attribute__((aligned(1024))) float prm[8][256];  // per wavefront: 128 weight scales, 128 biases
+  // per tile parity and 128-channel half: 128 weight scales, 128 biases (with the int8 ring: 160 KB in all, the CU's LDS)
+  __shared__ __attribute__((aligned(1024))) float prm[2][2][256];
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int team = wave >> 2, w = wave & 3, wn = w & 1, wm = w >> 1;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wn = wave & 1, wm = wave >> 1;
   const int64_t k_bytes = (int64_t)a.K * ES;
   const int ksteps = (int)(k_bytes / kStepBytes);
   const uint8_t* Xg = (const uint8_t*)a.X;
@@ -439,142 +494,149 @@ __global__ void __launch_bounds__(512, 1) spgemm_team_kernel(const GemmArgs a, c
   const int items = xcd_items(plan, xcd, f0, nf, t0);
   const int my_items = wl < items ? (items - wl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
   if (my_items == 0) return;  // the whole workgroup leaves before any barrier
+  const int total_steps = my_items * ksteps;
   auto tile_of = [&](int i) {
     const int it = wl + i * wgs_per_xcd;
     return decode_tile(plan, it < nf ? f0 + it : t0 + it - nf);
   };
   const bool has_bias = !RAW && (a.epilogue & GPUSQ_EPI_BIAS) != 0;
   const float s_a = (IS_I8 && !RAW) ? a.act_scale[0] : 1.0f;
-  float* my_prm = prm[wave];
-  if (!has_bias) {  // the bias half stays zero for the whole launch
-    my_prm[128 + lane] = 0.0f;
-    my_prm[192 + lane] = 0.0f;
+  if (!has_bias && wm == 0) {  // the bias halves stay zero for the whole launch (visible after the first barrier)
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      prm[par][wn][128 + lane] = 0.0f;
+      prm[par][wn][192 + lane] = 0.0f;
+    }
   }
-  const uint32_t ring_lds = lds_address(ring), prm_lds = lds_address(my_prm);
+  const uint32_t ring_lds = lds_address(ring), prm_lds = lds_address(prm[0][wn]);
+  // The 128 channels [n0, n0 + 128) of epilogue constants of this wavefront's half of a tile, into the constants array
+  // of the given parity; requested by the first wavefront of the half.  n0 < 0: nothing (there is no such tile).
+  auto request_constants = [&](int n0, int parity) {
+    if constexpr (!RAW) {
+      if (wm == 0 && n0 >= 0) {
+        const uint32_t dst = prm_lds + (uint32_t)parity * (uint32_t)sizeof(prm[0]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          int n = n0 + i * 64 + lane;
+          n = n < a.N ? n : a.N - 1;  // channels past the end are never stored
+          if constexpr (IS_I8) copy4_to_lds(a.w_scale, (uint32_t)n * 4u, dst + (uint32_t)i * 256u);
+          if (has_bias) copy4_to_lds(a.bias, (uint32_t)n * 4u, dst + 512u + (uint32_t)i * 256u);
+        }
+      }
+    }
+  };
   const uint32_t loff = (uint32_t)lane * 16u;
-  const uint32_t a_off = (uint32_t)(wn * kBigTN * kFragValueBytes + lane * 16);
-  const uint32_t i_off = (uint32_t)index_offset(IS_I8, wn * kBigTN, lane);
+  const uint32_t a_off = (uint32_t)(wn * kTileTN * kFragValueBytes + lane * 16);
+  const uint32_t i_off = (uint32_t)index_offset(IS_I8, wn * kTileTN, lane);
 
   // cursor of the copy requests: the next K step to request, as (tile, step), with its source addresses
   int pf_item = 0, pf_ks = 0;
   const uint8_t *pf_x = Xg, *pf_w = Wg;
   uint32_t pf_xoff[4] = {0, 0, 0, 0};
-  auto seek = [&](int item, int ks) {
-    while (ks >= ksteps) {
-      ks -= ksteps;
-      ++item;
-    }
+  auto seek = [&](int item) {
     pf_item = item;
-    pf_ks = ks;
+    pf_ks = 0;
     if (item < my_items) {
       const Tile t = tile_of(item);
-      tile_x_offsets(pf_xoff, t, a.M, k_bytes, w, lane);
-      pf_x = Xg + t.m0 * k_bytes + (int64_t)ks * kStepBytes;
-      pf_w = Wg + t.n_blk * w_col_bytes + (int64_t)ks * tile_bytes(IS_I8);
+      tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane);
+      pf_x = Xg + t.m0 * k_bytes;
+      pf_w = Wg + t.n_blk * w_col_bytes;
     }
   };
   auto advance = [&]() {
     ++pf_ks;
     pf_x += kStepBytes;
     pf_w += tile_bytes(IS_I8);
-    if (pf_ks == ksteps) seek(pf_item + 1, 0);
+    if (pf_ks == ksteps) seek(pf_item + 1);
   };
 
-  // state of a wavefront across its compute and epilogue phases
-  acc_t acc[kBigTN][kBigTM];
-  v8i b0[kBigTM], b1[kBigTM];  // B operands of the current and the next K step (roles alternate)
-  v4i av[4];                   // A fragments in flight
-  int ai[kBigTN];              // index words
-  Tile t = tile_of(0);
-  BOffsets bo = b_offsets(wm, t.tm, lane);
-  // Everything a wavefront can do for its tile `item` before the phase in which it computes it: called after the
-  // barrier that ends the second-to-last step of the previous phase (the tile's first stage has landed by then) and
-  // before the last barrier of that phase.
-  auto set_up_tile = [&](int item) {
-    t = tile_of(item);
-    bo = b_offsets(wm, t.tm, lane);
-#pragma unroll
-    for (int i = 0; i < kBigTN; ++i)
-#pragma unroll
-      for (int j = 0; j < kBigTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
-    seek(item, kRing - 1);
-    if constexpr (!RAW) {  // this wavefront's 128 channels of epilogue constants, into its own LDS array
-      const int n0 = t.n_blk * kBigBN + wn * (kBigTN * 16);
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        int n = n0 + i * 64 + lane;
-        n = n < a.N ? n : a.N - 1;  // channels past the end are never stored
-        if constexpr (IS_I8) copy4_to_lds(a.w_scale, (uint32_t)n * 4u, prm_lds + (uint32_t)i * 256u);
-        if (has_bias) copy4_to_lds(a.bias, (uint32_t)n * 4u, prm_lds + 512u + (uint32_t)i * 256u);
-      }
-    }
-    load_step_head<IS_I8>(b0, av, ai, ring + (size_t)((item * ksteps) & (kRing - 1)) * STAGE, bo, a_off, i_off);
-  };
+  acc_t acc[kTileTN][kTileTM];
+  v8i b0[kTileTM], b1[kTileTM];  // B operands of the current and the next K step (roles alternate)
+  v4i av[4];                     // A fragments in flight
+  int ai[kTileTN];               // index words
 
-  if (team == 0) {  // the first three K steps of the sequence
-    seek(0, 0);
+  // the constants of the first tile, then the first three K steps of the sequence
+  request_constants(tile_of(0).n_blk * kTileBN + wn * (kTileTN * 16), 0);
+  seek(0);
+  {
     int n_req = 0;
-    for (int g = 0; g < kRing - 1; ++g) {
+    for (int g = 0; g < kRing; ++g) {
       if (pf_item < my_items) {
 #pragma unroll
-        for (int i = 0; i < kCopiesPerStep; ++i)
-          issue_step_copy<IS_I8>(i, ring_lds + (uint32_t)g * STAGE, pf_x, pf_w, pf_xoff, w, loff);
+        for (int i = 0; i < kCopies; ++i)
+          issue_step_copy<IS_I8>(i, ring_lds + (uint32_t)g * STAGE, pf_x, pf_w, pf_xoff, wave, loff);
         advance();
         ++n_req;
       }
     }
-    if (n_req == kRing - 1)
-      __builtin_amdgcn_s_waitcnt(kWaitVm9Lgkm0);  // steps 0 and 1 have landed
+    if (n_req == kRing)
+      __builtin_amdgcn_s_waitcnt(kWaitVm14);  // the constants and step 0 have landed
     else
-      __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);
   }
-  GPUSQ_TEAM_BARRIER();
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
-  int ph = 0;
-  if (team == 0) {
-    set_up_tile(0);
-  } else {  // phase 0: the second team only gets ready for its first tile
-    for (int k = 0; k < ksteps; ++k) {
-      if (k == ksteps - 1 && my_items > 1) set_up_tile(1);
-      GPUSQ_TEAM_BARRIER();
-    }
-    ph = 1;
-  }
-  while (ph <= my_items) {
-    // ---- compute phase ph --------------------------------------------------------------------------------------
-    if (ph >= my_items) {  // one phase after the last tile: only the other team's last epilogue runs
-      for (int k = 0; k < ksteps; ++k) GPUSQ_TEAM_BARRIER();
-      break;
-    }
-    const int g0 = ph * ksteps;
-    auto step = [&](int ks, const v8i (&b)[kBigTM], v8i (&bn)[kBigTM]) {
-      const int g = g0 + ks;
+  int g = 0, slot = 0;     // global K step and its ring stage
+  int stores_pending = 0;  // output stores of the previous tile's epilogue (-1: unknown)
+  for (int item = 0; item < my_items; ++item) {
+    const Tile t = tile_of(item);
+    const BOffsets bo = b_offsets(wm, t.tm, lane);
+    const int next_n0 = item + 1 < my_items ? tile_of(item + 1).n_blk * kTileBN + wn * (kTileTN * 16) : -1;
+#pragma unroll
+    for (int i = 0; i < kTileTN; ++i)
+#pragma unroll
+      for (int j = 0; j < kTileTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+    // the stage of the tile's first step has landed: start-up barrier, or the barrier in the previous tile's last step
+    load_step_head<IS_I8>(b0, av, ai, ring + (size_t)slot * STAGE, ring + (size_t)slot * STAGE + kXSlabBytes, bo, a_off, i_off);
+    auto step = [&](int ks, const v8i (&b)[kTileTM], v8i (&bn)[kTileTM]) {
       const bool requested = pf_item < my_items;
-      const uint8_t* stage = ring + (size_t)(g & (kRing - 1)) * STAGE;
-      const uint8_t* next = ks + 1 < ksteps ? ring + (size_t)((g + 1) & (kRing - 1)) * STAGE : stage;
-      team_step<IS_I8>(stage, next, bo, acc, b, bn, av, ai, a_off, i_off, requested,
-                       ring_lds + (uint32_t)((g + kRing - 1) & (kRing - 1)) * STAGE, pf_x, pf_w, pf_xoff, w, loff);
-      __builtin_amdgcn_sched_barrier(0);
-      if (requested) {
-        __builtin_amdgcn_s_waitcnt(kWaitVm9Lgkm0);
-        advance();
-      } else {
-        __builtin_amdgcn_s_waitcnt(kWaitVm0Lgkm0);
-      }
-      GPUSQ_TEAM_BARRIER();
+      const int nslot = slot + 1 == kRing ? 0 : slot + 1;
+      // Outstanding at the barrier of step g, oldest first: the copies of step g+1, then those of step g+2 (if the
+      // sequence has one), which may stay in flight.  In the first two steps of a tile the output stores of the previous
+      // tile's epilogue sit in the queue behind the copies waited for, so they may stay in flight too: the stores drain
+      // to memory while the K loop goes on.  The third barrier of a tile then waits for copies that were requested after
+      // those stores.  (Only the common count, the 16 stores of a wavefront whose 128 x 64 outputs all lie inside Y, is
+      // exploited; any other count waits for the stores as well, which is only stricter.)
+      const int wait_mode = g + 2 >= total_steps ? 0 : (ks < 2 ? (stores_pending < 0 ? 0 : (stores_pending >= 16 ? 2 : 1)) : 1);
+      tile_step<IS_I8>(ks + 1 == ksteps, wait_mode, ring + (size_t)slot * STAGE, ring + (size_t)nslot * STAGE, bo, acc, b, bn, av, ai,
+                       a_off, i_off, requested, ring_lds + (uint32_t)slot * STAGE, pf_x, pf_w, pf_xoff, wave, loff, [&]() {
+                         // The next tile's constants go into the other constants array, which was last read in the
+                         // previous tile's epilogue (every wavefront has left it: it passed this tile's barriers).  They
+                         // are older than this step's copy requests and than this tile's output stores, so the wait in
+                         // front of the next tile's first barrier covers them and that barrier publishes them.
+                         if (ks + 1 == ksteps) request_constants(next_n0, (item + 1) & 1);
+                       });
+      if (requested) advance();
+      ++g;
+      slot = nslot;
     };
     for (int ks = 0; ks < ksteps; ks += 2) {
       step(ks, b0, b1);
       if (ks + 1 < ksteps) step(ks + 1, b1, b0);
     }
-    ++ph;
-    // ---- epilogue phase ph: tile ph-1; at its end, get ready for tile ph+1 -------------------------------------------
-    const int next_item = ph + 1;
-    team_epilogue<IS_I8, GELU, OUT>(a, acc, my_prm, s_a, t.n_blk * kBigBN + wn * (kBigTN * 16), t.m0 + wm * t.tm * 16, lane, t.tm,
-                                    ksteps, [&]() {
-                                      if (next_item < my_items) set_up_tile(next_item);
-                                    });
-    ++ph;
+    const int n_wave = t.n_blk * kTileBN + wn * (kTileTN * 16);
+    const int64_t m_wave = t.m0 + wm * t.tm * 16;
+    const int64_t rows = (int64_t)a.M - m_wave;
+    const int chans = a.N - n_wave;
+    // The epilogue, and the number of store instructions this wavefront issues in it (with N % 8 != 0 that number
+    // depends on the lanes: then the next tile waits for everything, because a count that is too high would let its
+    // copies go unwaited).
+    if (OUT == GPUSQ_F16 && (a.N & 7) == 0) {
+      line_epilogue<IS_I8, GELU>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
+      // per pair of batches (64 channels) with a channel inside N: one store per slab with a row inside M among its
+      // first 8 rows and one for its last 8 rows
+      int n = 0;
+      for (int mt = 0; mt < t.tm; ++mt) n += (16 * mt < rows) + (16 * mt + 8 < rows);
+      stores_pending = n * (chans <= 0 ? 0 : (chans > kRowBlock ? 2 : 1));
+    } else {
+      batch_epilogue<IS_I8, GELU, OUT>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
+      // one (two for 2 x 16 bytes of int32) per batch of 32 channels x 16 rows with a row inside M and a channel inside N
+      const int mts = rows <= 0 ? 0 : (rows >= t.tm * 16 ? t.tm : (int)((rows + 15) >> 4));
+      const int gs = chans <= 0 ? 0 : (chans >= 128 ? 4 : (chans + 31) >> 5);
+      stores_pending = (a.N & 7) ? -1 : mts * gs * (OUT == GPUSQ_I32 ? 2 : 1);
+    }
   }
 }
 
@@ -709,29 +771,64 @@ static int num_cus() {
   return cus;
 }
 
-// Full 128-row tiles for as many whole rounds over the resident workgroups as the problem has; the remaining rows in
-// shorter tiles, as tall as still fits them in one more round.
-static TilePlan make_plan(int M, int N, int resident) {
-  TilePlan p;
-  p.tiles_n = (int)ceil_div(N, kBigBN);
-  const int chunks = (int)ceil_div(M, kBigBM);
-  const int all_tiles = chunks * p.tiles_n;
-  int full_chunks = chunks;
-  if (all_tiles > resident && all_tiles % resident != 0) full_chunks = (all_tiles / resident) * resident / p.tiles_n;
-  p.full_chunks = full_chunks;
-  p.full_tiles = full_chunks * p.tiles_n;
-  const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * kBigBM;
-  p.tail_tm = kBigTM;
-  int tail_tiles = 0;
-  if (rows_left > 0) {
-    for (int tm = kBigTM; tm >= 1; --tm) {
-      p.tail_tm = tm;
-      tail_tiles = (int)ceil_div(rows_left, 32 * tm) * p.tiles_n;
-      if (tm > 1 && (int)ceil_div(rows_left, 32 * (tm - 1)) * p.tiles_n > resident) break;  // a shorter tile would need a second round
+// Estimated run time (arbitrary units, fitted to traces of the kernel on MI355X) of one tile of 64*tm rows: a K step
+// costs a fixed part (the weight tile, the barrier) and a part per slab (matrix instructions, X slab), the epilogue a
+// part per slab that is larger with GELU.
+static double tile_cost(int tm, int ksteps, bool gelu) { return ksteps * (0.5 + 0.15 * tm) + (gelu ? 1.6 : 1.1) * tm + 0.3; }
+
+// The workgroup with the most work under the kernel's assignment (XCD x takes its share of the list, its workgroup wl
+// the items wl, wl + W, ...).
+static double plan_makespan(const TilePlan& p, int grid, int ksteps, bool gelu) {
+  const int W = grid / 8;
+  const double cf = tile_cost(p.full_tm, ksteps, gelu), ct = tile_cost(p.tail_tm, ksteps, gelu);
+  double worst = 0;
+  for (int x = 0; x < 8; ++x) {
+    int f0, nf, t0;
+    const int items = xcd_items(p, x, f0, nf, t0);
+    for (int wl = 0; wl < W && wl < items; ++wl) {
+      const int mine = (items - wl + W - 1) / W;
+      const int full = wl < nf ? (nf - wl + W - 1) / W : 0;
+      const double c = full * cf + (mine - full) * ct;
+      if (c > worst) worst = c;
     }
   }
-  p.total = p.full_tiles + tail_tiles;
-  return p;
+  return worst;
+}
+
+static int grid_for(const TilePlan& p, int resident) { return (int)ceil_div(p.total < resident ? p.total : resident, 8) * 8; }
+
+// Candidates: full tiles of 64, 128, 192 or 256 rows, either over all of M, or for as many whole rounds over the resident
+// workgroups as the problem has with the remaining rows in tail tiles of 64..64*full_tm rows; the one whose busiest
+// workgroup finishes first wins.
+static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
+  TilePlan best{};
+  double best_cost = -1;
+  const int tiles_n = (int)ceil_div(N, kTileBN);
+  auto consider = [&](int ftm, int full_chunks, int ttm) {
+    TilePlan p;
+    p.tiles_n = tiles_n;
+    p.full_tm = ftm;
+    p.full_chunks = full_chunks;
+    p.full_tiles = full_chunks * tiles_n;
+    p.tail_tm = ttm;
+    const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * 64 * ftm;
+    p.total = p.full_tiles + (rows_left > 0 ? (int)ceil_div(rows_left, 64 * ttm) * tiles_n : 0);
+    const double c = plan_makespan(p, grid_for(p, resident), ksteps, gelu);
+    if (best_cost < 0 || c < best_cost) {
+      best_cost = c;
+      best = p;
+    }
+  };
+  for (int ftm = kTileTM; ftm >= 1; --ftm) {
+    const int chunks = (int)ceil_div(M, 64 * ftm);
+    consider(ftm, chunks, ftm);
+    const int all_tiles = chunks * tiles_n;
+    if (all_tiles > resident && all_tiles % resident != 0) {
+      const int full_chunks = (all_tiles / resident) * resident / tiles_n;
+      for (int ttm = ftm; ttm >= 1; --ttm) consider(ftm, full_chunks, ttm);
+    }
+  }
+  return best;
 }
 
 template <bool IS_I8>
@@ -741,31 +838,30 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   if (work <= (int64_t)256 * 1024) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
   if (k_bytes % kStepBytes != 0) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);    // ragged K: zero-filling path
   const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
-  {
-    // persistent grid: one workgroup of two teams per CU, never more workgroups than tiles
-    const int resident = num_cus();
-    const TilePlan plan = make_plan(a.M, a.N, resident);
-    const dim3 grid((unsigned)(ceil_div(plan.total < resident ? plan.total : resident, 8) * 8));
-    if ((ceil_div(plan.total, grid.x) + 2) * (k_bytes / kStepBytes) >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
-    if constexpr (IS_I8) {
-      if (a.out_dt == GPUSQ_I32)
-        spgemm_team_kernel<true, 0, GPUSQ_I32><<<grid, 512, 0, s>>>(a, plan);
-      else if (a.out_dt == GPUSQ_I8 && gelu)
-        spgemm_team_kernel<true, 1, GPUSQ_I8><<<grid, 512, 0, s>>>(a, plan);
-      else if (a.out_dt == GPUSQ_I8)
-        spgemm_team_kernel<true, 0, GPUSQ_I8><<<grid, 512, 0, s>>>(a, plan);
-      else if (gelu)
-        spgemm_team_kernel<true, 1, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
-      else
-        spgemm_team_kernel<true, 0, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
-    } else {
-      if (gelu)
-        spgemm_team_kernel<false, 1, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
-      else
-        spgemm_team_kernel<false, 0, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
-    }
-    return check_launch();
+  // persistent grid: one workgroup per CU, never more workgroups than tiles
+  const int resident = num_cus();
+  const int ksteps = (int)(k_bytes / kStepBytes);
+  const TilePlan plan = make_plan(a.M, a.N, resident, ksteps, gelu);
+  const dim3 grid((unsigned)grid_for(plan, resident));
+  if ((ceil_div(plan.total, grid.x) + 2) * ksteps >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
+  if constexpr (IS_I8) {
+    if (a.out_dt == GPUSQ_I32)
+      spgemm_tile_kernel<true, 0, GPUSQ_I32><<<grid, 512, 0, s>>>(a, plan);
+    else if (a.out_dt == GPUSQ_I8 && gelu)
+      spgemm_tile_kernel<true, 1, GPUSQ_I8><<<grid, 512, 0, s>>>(a, plan);
+    else if (a.out_dt == GPUSQ_I8)
+      spgemm_tile_kernel<true, 0, GPUSQ_I8><<<grid, 512, 0, s>>>(a, plan);
+    else if (gelu)
+      spgemm_tile_kernel<true, 1, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+    else
+      spgemm_tile_kernel<true, 0, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+  } else {
+    if (gelu)
+      spgemm_tile_kernel<false, 1, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
+    else
+      spgemm_tile_kernel<false, 0, GPUSQ_F16><<<grid, 512, 0, s>>>(a, plan);
   }
+  return check_launch();
 }
 
 gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s) {
