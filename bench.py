@@ -123,7 +123,7 @@ def main():
     gemm_bytes = M * K + N * K // 2 + N * K // 8 + 8 * N + 4 + 2 * M * N
     gemm_s = gemm_ms_in_step * 1e-3
     roofline = {"bound": "hbm", "achieved": gemm_bytes / gemm_s / 1e9, "peak": 8000.0, "unit": "GB/s",
-                "frac": gemm_bytes / gemm_s / 1e9 / 8000.0, "traffic": None, "kernel": "spgemm_team_kernel<int8, GELU, fp16 out> (fused epilogue)",
+                "frac": gemm_bytes / gemm_s / 1e9 / 8000.0, "traffic": None, "kernel": "spgemm_tile_kernel<int8, GELU, fp16 out> (fused epilogue)",
                 "algorithmic_bytes": gemm_bytes, "avg_launch_ms": gemm_ms_in_step}
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "spgemm_int8_c1_traffic.json")
     if os.path.exists(traffic_file):  # HBM bytes per launch from committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE)

@@ -101,11 +101,11 @@ __device__ __forceinline__ float epilogue_value(int raw, float accf, float c, fl
 // the element (row, n) of Y.
 // N % 4 == 0 is guaranteed by the host, so each half of 4 channels is entirely inside or outside the matrix and
 // 4-channel stores are naturally aligned; with N % 8 == 0 the 8 channels go out in one store.
-// STREAM: give that 16-byte fp16 store the non-temporal hint.  Y is written once and not read again, and in the
-// two-team kernel (64 contiguous bytes per row and instruction, operands re-read by every tile through the L2) the hint
-// keeps Y from pushing the operands out of the L2: measured there, it cuts the HBM reads by 40% and the run time by 8%.
-// It is a measured choice per kernel and store shape: the same hint makes the dense kernel's stores, and narrower or
-// strided stores (int8 / int32 output), markedly slower.
+// STREAM: give that 16-byte fp16 store the non-temporal hint.  Y is written once and not read again, and in the tile
+// kernel (operands re-read by every tile through the L2) the hint keeps Y from pushing the operands out of the L2:
+// measured there, it cuts the HBM reads by 40% and the run time by 8%.  It is a measured choice per kernel and store
+// shape: the same hint makes the dense kernel's stores, and narrower or strided stores (int8 / int32 output), markedly
+// slower.
 // OUT: output dtype fixed at compile time (a gpusq_dtype value), or -1 to take it from the arguments at run time.
 template <bool IS_I8, int OUT = -1, bool STREAM = false>
 __device__ __forceinline__ void store_8_at(const GemmArgs& a, void* yp, int n, const float (&v)[8], const int (&raw)[8]) {

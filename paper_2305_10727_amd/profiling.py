@@ -89,7 +89,7 @@ def main():
                 traffic[k] = dict(read_bytes=rb, write_bytes=wb)
                 lines.append("%-72s %14.2f %14.2f %14.2f" % (short(k), rb / 1e6, wb / 1e6, (rb + wb) / 1e6))
             result["traffic"] = traffic
-            gemm = [v for k, v in traffic.items() if "spgemm_team_kernel" in k]
+            gemm = [v for k, v in traffic.items() if "spgemm_tile_kernel" in k]
             if gemm:
                 result["hbm_bytes_per_launch"] = gemm[0]["read_bytes"] + gemm[0]["write_bytes"]
                 result["fetch_scale_bytes_per_unit"] = f_scale

@@ -389,14 +389,17 @@ def test_c1_full_size_sampled_rows_and_self_consistency(g):
     assert rel_err(host(yhd)[rows], ref) <= 2e-3
 
 
-# Shapes that take the two-team large-tile kernel (M*N > 256K, K a multiple of the K step) and exercise its corner
-# cases: 1, 2, 3 and 5 K steps (copy requests that run across several tiles, odd step counts), fewer tiles than CUs,
-# several tiles per workgroup with short tail tiles, N that is not a multiple of 256 or of 8, M that is not a multiple of 16.
-TEAM_SHAPES = [(2100, 128, 520, 11), (1500, 256, 388, 12), (4500, 640, 1024, 13), (9000, 384, 2304, 14), (12345, 128, 264, 15)]
+# Shapes that take the tile kernel (M*N > 256K, K a multiple of the K step) and exercise its corner cases: 1, 2, 3 and 5
+# K steps (copy requests that run across several tiles, odd step counts), fewer tiles than CUs, several tiles per
+# workgroup with short tail tiles (the waits that let one tile's output stores drain during the next tile's K loop, with
+# one and two K steps per tile), N that is not a multiple of 256, of 64 or of 8 (whole-line and per-batch epilogues),
+# M that is not a multiple of 8.
+TILE_SHAPES = [(2100, 128, 520, 11), (1500, 256, 388, 12), (4500, 640, 1024, 13), (9000, 384, 2304, 14), (12345, 128, 264, 15),
+               (50003, 256, 512, 16), (41000, 128, 776, 17)]
 
 
-@pytest.mark.parametrize("M,K,N,seed", TEAM_SHAPES)
-def test_large_tile_kernel_corner_shapes(g, M, K, N, seed):
+@pytest.mark.parametrize("M,K,N,seed", TILE_SHAPES)
+def test_tile_kernel_corner_shapes(g, M, K, N, seed):
     p = Int8Problem(M, K, N, seed)
     d = gpu_prepare_int8(g, p.W32, p.X32)
     exp = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
