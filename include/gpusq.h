@@ -129,6 +129,15 @@ gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const floa
                                const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale,
                                int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
 
+/* ---- host-side introspection (no GPU work, no device access when cus > 0): how gpusq_spgemm_fp16 / gpusq_spgemm_int8
+ * (dt = GPUSQ_F16 / GPUSQ_I8 = the operand type) decompose a problem on a device with `cus` compute units (cus <= 0: the
+ * current device).  out[0] = kernel (0: small kernel, 64 x 64 tiles; 1: small kernel, 128 x 128 tiles, any K % 16 == 0;
+ * 2: tile kernel); for the tile kernel out[1] = rows per tile unit u, out[2] = 256-channel blocks, out[3] = full_tm
+ * (a full tile has u * full_tm rows), out[4] = row chunks covered by full tiles, out[5] = tail_tm (the remaining rows
+ * are cut into tiles of u * tail_tm rows), out[6] = tiles in all, out[7] = workgroups launched.  Same argument checks
+ * as the GEMM calls (sizes only). */
+gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]);
+
 /* ---- dense twins: the same computation from the masked but uncompressed W [N][K], on dense matrix instructions,
  * built the same way; the baseline the sparse kernels are compared with. */
 gpusq_status gpusq_gemm_fp16_dense(const void* X, const void* W, const float* bias, void* Y,

@@ -147,6 +147,18 @@ gpusq_status gpusq_prepare_weights(const float* W, gpusq_dtype dt, float* W_prun
   return launch_prepare_weights(W, dt, W_pruned, W_low, w_scale, values, meta, packed, N, K, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]) {
+  if (!out) return GPUSQ_ERR_NULL;
+  if (M <= 0) return GPUSQ_ERR_SHAPE;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (M > INT32_MAX || M * N > kMaxElems || M * K > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (epilogue & ~(GPUSQ_EPI_BIAS | GPUSQ_EPI_GELU)) return GPUSQ_ERR_UNSUPPORTED;
+  if (K % 16 != 0 || N % 4 != 0) return GPUSQ_ERR_UNSUPPORTED;
+  return plan_spgemm(dt == GPUSQ_I8, M, N, K, epilogue, cus, out);
+}
+
 gpusq_status gpusq_spgemm_fp16(const void* X, const void* Wpacked, const float* bias, void* Y, int64_t M, int64_t N,
                                int64_t K, int epilogue, void* stream) {
   gpusq_status st = check_gemm(X, Wpacked, bias, Y, M, N, K, epilogue);

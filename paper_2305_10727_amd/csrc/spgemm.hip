@@ -771,10 +771,10 @@ static int num_cus() {
   return cus;
 }
 
-// Estimated run time (arbitrary units, fitted to traces of the kernel on MI355X) of one tile of 64*tm rows: a K step
-// costs a fixed part (the weight tile, the barrier) and a part per slab (matrix instructions, X slab), the epilogue a
-// part per slab that is larger with GELU.
-static double tile_cost(int tm, int ksteps, bool gelu) { return ksteps * (0.5 + 0.15 * tm) + (gelu ? 1.6 : 1.1) * tm + 0.3; }
+// Estimated run time (microseconds, fitted to traces of the kernel on MI355X) of one tile of 64*tm rows: a K step costs
+// the same whatever tm (a short tile still runs every wavefront through whole operands: measured 1.1-1.2 us for
+// tm = 1..4), the epilogue scales with the rows stored and is larger with GELU.
+static double tile_cost(int tm, int ksteps, bool gelu) { return ksteps * 1.1 + (gelu ? 1.6 : 1.1) * tm + 0.3; }
 
 // The workgroup with the most work under the kernel's assignment (XCD x takes its share of the list, its workgroup wl
 // the items wl, wl + W, ...).
@@ -831,12 +831,38 @@ static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
   return best;
 }
 
+// Which kernel a problem takes: 0 = small kernel with 64 x 64 tiles (latency-bound sizes), 1 = small kernel with
+// 128 x 128 tiles (ragged K: zero-filling path), 2 = tile kernel.
+static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K) {
+  if (M * N <= (int64_t)256 * 1024) return 0;
+  if ((K * (is_i8 ? 1 : 2)) % kStepBytes != 0) return 1;
+  return 2;
+}
+
+gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t* out) {
+  const int choice = kernel_choice(is_i8, M, N, K);
+  for (int i = 0; i < 8; ++i) out[i] = 0;
+  out[0] = choice;
+  if (choice != 2) return GPUSQ_OK;
+  const int resident = cus > 0 ? cus : num_cus();
+  const int ksteps = (int)(K * (is_i8 ? 1 : 2) / kStepBytes);
+  const TilePlan p = make_plan((int)M, (int)N, resident, ksteps, (epilogue & GPUSQ_EPI_GELU) != 0);
+  out[1] = 64;
+  out[2] = p.tiles_n;
+  out[3] = p.full_tm;
+  out[4] = p.full_chunks;
+  out[5] = p.tail_tm;
+  out[6] = p.total;
+  out[7] = grid_for(p, resident);
+  return GPUSQ_OK;
+}
+
 template <bool IS_I8>
 static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
-  const int64_t work = (int64_t)a.M * a.N;
   const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
-  if (work <= (int64_t)256 * 1024) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);  // 64 x 64 tiles: latency-bound sizes
-  if (k_bytes % kStepBytes != 0) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);    // ragged K: zero-filling path
+  const int choice = kernel_choice(IS_I8, a.M, a.N, a.K);
+  if (choice == 0) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);
+  if (choice == 1) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);
   const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
   // persistent grid: one workgroup per CU, never more workgroups than tiles
   const int resident = num_cus();

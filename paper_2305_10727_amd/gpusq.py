@@ -23,7 +23,7 @@ EXPORTS = [
     "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
     "gpusq_quantize_workspace_bytes",
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
-    "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
+    "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
 ]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_int8_dense.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+        L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
         for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
                      "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
             getattr(L, name).restype = ci
@@ -149,6 +150,14 @@ def decompress(values, meta, K):
     _check(lib().gpusq_decompress(_ptr(values), _ptr(meta), _ptr(W), _TORCH_DT[values.dtype], N, K, _stream()),
            "gpusq_decompress")
     return W
+
+
+def spgemm_plan(dtype, M, N, K, epilogue=0, cus=0):
+    """gpusq_spgemm_plan: the tile decomposition of a sparse GEMM (host-side; no GPU needed when cus > 0)."""
+    out = (ctypes.c_int32 * 8)()
+    _check(lib().gpusq_spgemm_plan(_TORCH_DT[dtype], M, N, K, epilogue, cus, out), "gpusq_spgemm_plan")
+    keys = ("kernel", "unit_rows", "tiles_n", "full_tm", "full_chunks", "tail_tm", "tiles", "workgroups")
+    return dict(zip(keys, list(out)))
 
 
 def packed_bytes(dtype, N, K):

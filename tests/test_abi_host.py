@@ -90,3 +90,46 @@ def test_binding_refuses_host_tensors():
     from paper_2305_10727_amd import gpusq
     with pytest.raises(ValueError):
         gpusq.prune_2to4(torch.zeros(4, 8))
+
+
+def _plan(lib, dt, M, N, K, epi, cus):
+    out = (ctypes.c_int32 * 8)()
+    lib.gpusq_spgemm_plan.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                      ctypes.POINTER(ctypes.c_int32)]
+    st = lib.gpusq_spgemm_plan(dt, M, N, K, epi, cus, out)
+    return st, list(out)
+
+
+def test_tile_plan_covers_every_row_exactly_once(lib):
+    """The host-side tile plan of the sparse GEMM: the full tiles and the tail tiles partition the rows of X, the tile
+    count is consistent, no more workgroups than tiles or compute units (rounded to the 8 XCDs), and a small or ragged-K
+    problem takes the small kernel."""
+    I8, F16 = 2, 1
+    shapes = [(12608, 3072, 768), (25216, 768, 3072), (12544, 512, 2048), (65792, 5120, 1280), (50432, 1024, 4096),
+              (600, 512, 384), (1500, 388, 256), (2100, 520, 128), (12345, 264, 128), (70000, 256, 128), (257, 1024, 1024),
+              (3, 100000, 256), (999999, 4, 128)]
+    for cus in (256, 64, 304, 8):
+        for dt in (I8, F16):
+            for epi in (0, 3):
+                for M, N, K in shapes:
+                    st, p = _plan(lib, dt, M, N, K, epi, cus)
+                    assert st == 0, (M, N, K)
+                    kernel, u, tiles_n, ftm, fchunks, ttm, total, wgs = p
+                    if M * N <= 256 * 1024:
+                        assert kernel == 0
+                        continue
+                    assert kernel == 2 and u == 64 and tiles_n == -(-N // 256)
+                    assert 1 <= ftm <= 4 and 1 <= ttm <= 4 and fchunks >= 0
+                    full_rows = fchunks * u * ftm
+                    assert full_rows - u * ftm < M          # no full tile lies entirely beyond M
+                    rows_left = max(M - full_rows, 0)
+                    tail_chunks = -(-rows_left // (u * ttm))
+                    assert total == (fchunks + tail_chunks) * tiles_n
+                    assert full_rows + tail_chunks * u * ttm >= M                # every row is covered
+                    assert tail_chunks == 0 or full_rows + (tail_chunks - 1) * u * ttm < M  # and no tail tile is empty
+                    assert wgs % 8 == 0 and wgs <= -(-cus // 8) * 8 and wgs >= min(total, 8) and wgs - 8 < total
+    # ragged K (not a multiple of the 128-byte K step) -> zero-filling small kernel; argument errors are reported
+    assert _plan(lib, I8, 4096, 4096, 144, 0, 256) == (0, [1, 0, 0, 0, 0, 0, 0, 0])
+    assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 2 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
+    assert _plan(lib, I8, 0, 4096, 128, 0, 256)[0] == 2 and _plan(lib, I8, 128, 4096, 130, 0, 256)[0] == 2
+    assert _plan(lib, 0, 128, 4096, 128, 0, 256)[0] == 4 and _plan(lib, I8, 128, 4098, 128, 0, 256)[0] == 4
