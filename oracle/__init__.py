@@ -234,3 +234,30 @@ def linear_int8_sparse(X, values, meta, s_a, s_w, bias=None, gelu=False):
                                         int(bool(gelu)), _p(y16), _i64(M), _i64(N), _i64(K))
     assert r == 0
     return y16.view(np.float16)
+
+
+# ---------------------------------------------------------------- patch embedding (strided convolution, Sec. 3.3)
+def patch_conv_int8(img, Wc):
+    """img int8 [B,C,H,W], Wc int8 [D,C,P,P] -> (acc int32 [B*(H/P)*(W/P), D], multiply-accumulates performed)"""
+    img = _c(img, np.int8); Wc = _c(Wc, np.int8)
+    B, C, H, W = img.shape; D, C2, P, P2 = Wc.shape
+    assert C2 == C and P2 == P
+    acc = np.empty((B * (H // P) * (W // P), D), np.int32)
+    f = lib().oracle_patch_conv_int8
+    f.restype = ctypes.c_int64
+    macs = f(_p(img), _p(Wc), _p(acc), _i64(B), _i64(C), _i64(H), _i64(W), _i64(P), _i64(D))
+    assert macs >= 0
+    return acc, int(macs)
+
+
+def patch_conv_f16(img, Wc):
+    """img fp16 [B,C,H,W], Wc fp16 [D,C,P,P] -> (acc float64 [B*(H/P)*(W/P), D], multiply-accumulates performed)"""
+    img = _c(img, np.uint16); Wc = _c(Wc, np.uint16)
+    B, C, H, W = img.shape; D, C2, P, P2 = Wc.shape
+    assert C2 == C and P2 == P
+    acc = np.empty((B * (H // P) * (W // P), D), np.float64)
+    f = lib().oracle_patch_conv_f16
+    f.restype = ctypes.c_int64
+    macs = f(_p(img), _p(Wc), _p(acc), _i64(B), _i64(C), _i64(H), _i64(W), _i64(P), _i64(D))
+    assert macs >= 0
+    return acc, int(macs)

@@ -23,7 +23,8 @@
  * Parity pins (tests/test_oracle_pins.py): exactly-2-of-4 invariant, brute force over the 6 index pairs,
  * exhaustive small-integer grids, compress/decompress round trip, the storage-saving closed forms printed in
  * Sec. 3.1 (43.75 % / 37.5 %), sparse GEMM == dense GEMM on masked weights, numpy int64 / float64 matmul,
- * quantiser error bound, GELU closed-form values.  No function here is "parity unpinned".
+ * quantiser error bound, GELU closed-form values; the patch-embedding convolution against the reshape-and-matmul
+ * form computed by numpy and against the operation count printed in Sec. 3.3.  No function here is "parity unpinned".
  *
  * Loops are the definitions written out; the only parallelism is an OpenMP "for" over independent output rows.
  */
@@ -437,6 +438,61 @@ int oracle_epilogue_fp16_f64(const double* acc64, const float* bias, int gelu, d
       if (Y16) Y16[m * N + n] = oracle_f64_to_f16(v);
     }
   return 0;
+}
+
+/* ------------------------------------------------------------------ patch embedding as a strided convolution */
+
+/* The patch-embedding layer [Sec. 3.3]: a convolution with C input channels, D output channels, kernel size and
+ * stride both P, on images [B][C][H][W]; every P x P patch becomes one token.  Written out as the convolution it
+ * is (no im2col, no GEMM):
+ *   acc[b][py][px][d] = sum_{c, i, j} img[b][c][py*P + i][px*P + j] * Wc[d][c][i][j]
+ * H and W must be multiples of P.  Returns the number of multiply-accumulates performed (counted in the loops), so
+ * that the operation count the paper prints, 2 * B * C * H * W * D, can be checked against the loops themselves;
+ * -1 on a shape error. */
+int64_t oracle_patch_conv_int8(const int8_t* img, const int8_t* Wc, int32_t* acc, int64_t B, int64_t C, int64_t H,
+                               int64_t W, int64_t P, int64_t D) {
+  if (P <= 0 || H % P || W % P) return -1;
+  const int64_t py_n = H / P, px_n = W / P;
+  int64_t macs = 0;
+#pragma omp parallel for schedule(static) reduction(+ : macs)
+  for (int64_t t = 0; t < B * py_n * px_n; ++t) {
+    const int64_t b = t / (py_n * px_n), py = (t / px_n) % py_n, px = t % px_n;
+    for (int64_t d = 0; d < D; ++d) {
+      int32_t s = 0;
+      for (int64_t c = 0; c < C; ++c)
+        for (int64_t i = 0; i < P; ++i)
+          for (int64_t j = 0; j < P; ++j) {
+            s += (int32_t)img[((b * C + c) * H + py * P + i) * W + px * P + j] * (int32_t)Wc[((d * C + c) * P + i) * P + j];
+            ++macs;
+          }
+      acc[t * D + d] = s;
+    }
+  }
+  return macs;
+}
+
+/* The same for fp16 operands, accumulated in fp64 (each product of two fp16 numbers is exact in fp64). */
+int64_t oracle_patch_conv_f16(const uint16_t* img, const uint16_t* Wc, double* acc64, int64_t B, int64_t C, int64_t H,
+                              int64_t W, int64_t P, int64_t D) {
+  if (P <= 0 || H % P || W % P) return -1;
+  const int64_t py_n = H / P, px_n = W / P;
+  int64_t macs = 0;
+#pragma omp parallel for schedule(static) reduction(+ : macs)
+  for (int64_t t = 0; t < B * py_n * px_n; ++t) {
+    const int64_t b = t / (py_n * px_n), py = (t / px_n) % py_n, px = t % px_n;
+    for (int64_t d = 0; d < D; ++d) {
+      double s = 0.0;
+      for (int64_t c = 0; c < C; ++c)
+        for (int64_t i = 0; i < P; ++i)
+          for (int64_t j = 0; j < P; ++j) {
+            s += (double)oracle_f16_to_f32(img[((b * C + c) * H + py * P + i) * W + px * P + j]) *
+                 (double)oracle_f16_to_f32(Wc[((d * C + c) * P + i) * P + j]);
+            ++macs;
+          }
+      acc64[t * D + d] = s;
+    }
+  }
+  return macs;
 }
 
 /* ------------------------------------------------------------------ whole linear layer, sparse form (CPU baseline) */

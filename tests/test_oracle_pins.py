@@ -397,3 +397,51 @@ def test_end_to_end_dequantised_layer_approximates_the_float_layer():
     ref = X.astype(np.float64) @ P.astype(np.float64).T
     assert np.abs(y - ref).max() / np.abs(ref).max() < 0.03
     assert np.corrcoef(y.ravel(), ref.ravel())[0, 1] > 0.999
+
+
+# ---------------------------------------------------------------- patch embedding (strided convolution, Sec. 3.3)
+def _patches(img, P):
+    """reshape-and-transpose form of cutting [B,C,H,W] into flattened P x P patches: rows (b, py, px), columns (c, i, j)"""
+    B, C, H, W = img.shape
+    return img.reshape(B, C, H // P, P, W // P, P).transpose(0, 2, 4, 1, 3, 5).reshape(B * (H // P) * (W // P), C * P * P)
+
+
+def test_patch_convolution_equals_matmul_on_flattened_patches_and_counts_the_papers_flops():
+    golden = dict(l.split() for l in open(os.path.join(GOLDEN, "patch_embedding_flops.txt")) if l.strip() and not l.startswith("#"))
+    per_mac = int(golden["flops_per_multiply_accumulate"])
+    rng = np.random.default_rng(7)
+    for B, C, H, W, P, D in [(2, 3, 8, 12, 4, 5), (1, 3, 14, 28, 14, 6), (3, 1, 6, 6, 1, 4), (2, 2, 16, 16, 16, 3)]:
+        img = rng.integers(-127, 128, (B, C, H, W), dtype=np.int8)
+        Wc = rng.integers(-127, 128, (D, C, P, P), dtype=np.int8)
+        acc, macs = oracle.patch_conv_int8(img, Wc)
+        assert per_mac * macs == 2 * B * C * H * W * D            # the count printed in Sec. 3.3
+        ref = _patches(img, P).astype(np.int64) @ Wc.reshape(D, -1).astype(np.int64).T
+        assert np.array_equal(acc, ref)
+        img16 = rng.standard_normal((B, C, H, W)).astype(np.float16)
+        W16 = (rng.standard_normal((D, C, P, P)) * 0.1).astype(np.float16)
+        a64, macs16 = oracle.patch_conv_f16(img16, W16)
+        assert macs16 == macs
+        ref64 = _patches(img16, P).astype(np.float64) @ W16.reshape(D, -1).astype(np.float64).T
+        assert np.allclose(a64, ref64, rtol=1e-12, atol=1e-12)
+
+
+def test_patch_convolution_special_cases():
+    rng = np.random.default_rng(8)
+    # one patch covering the whole image: a plain dot product per output channel
+    img = rng.integers(-127, 128, (1, 3, 4, 4), dtype=np.int8)
+    Wc = rng.integers(-127, 128, (2, 3, 4, 4), dtype=np.int8)
+    acc, _ = oracle.patch_conv_int8(img, Wc)
+    assert acc.shape == (1, 2)
+    assert acc[0, 1] == int((img[0].astype(np.int64) * Wc[1].astype(np.int64)).sum())
+    # locality: one pixel only influences the token of its own patch
+    img = rng.integers(-100, 100, (2, 3, 8, 8), dtype=np.int8)
+    Wc = rng.integers(1, 100, (4, 3, 4, 4), dtype=np.int8)
+    a0, _ = oracle.patch_conv_int8(img, Wc)
+    img2 = img.copy()
+    img2[1, 2, 5, 2] += 1                                         # image 1, patch row 1, patch column 0
+    a1, _ = oracle.patch_conv_int8(img2, Wc)
+    changed = np.nonzero((a0 != a1).any(axis=1))[0]
+    assert changed.tolist() == [1 * 4 + 1 * 2 + 0]
+    assert np.array_equal(a1[6] - a0[6], Wc[:, 2, 1, 2].astype(np.int32))   # by exactly the weight at (c=2, i=1, j=2)
+    # shape errors
+    assert oracle.lib().oracle_patch_conv_int8(None, None, None, 1, 1, 5, 4, 2, 1) == -1
