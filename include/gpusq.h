@@ -129,6 +129,18 @@ gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const floa
                                const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale,
                                int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
 
+/* ---- patch embedding [Sec. 3.3: the patch-embedding layer is a convolution with C input channels, D_embed output
+ * channels and kernel size = stride = P on images N x C x H x W, each P x P patch becoming one token; 2:4 sparsity is
+ * applied to it like to the linear layers].  With kernel = stride the convolution is the product of the flattened patches
+ * with the flattened weights, so it runs on the same sparse GEMM: this call writes the flattened patches,
+ *   X[(b*(H/P) + py)*(W/P) + px][(c*P + i)*P + j] = img[b][c][py*P + i][px*P + j],   X[.][k] = 0 for C*P*P <= k < K_pad,
+ * and gpusq_spgemm_* with K = K_pad on weights [D_embed][C][P][P] flattened to [D_embed][C*P*P] (zero-padded to K_pad,
+ * pruned / quantised / compressed / packed like any other weight) gives Y [B*(H/P)*(W/P)][D_embed].
+ *   img [B][C][H][W] and X [B*(H/P)*(W/P)][K_pad] of dt (GPUSQ_I8: an image quantised with gpusq_quantize_int8, or
+ *   GPUSQ_F16); H % P == 0, W % P == 0, K_pad >= C*P*P (else GPUSQ_ERR_SHAPE); the GEMM needs K_pad % 16 == 0. */
+gpusq_status gpusq_im2col_patches(const void* img, void* X, gpusq_dtype dt, int64_t B, int64_t C, int64_t H, int64_t W,
+                                  int64_t P, int64_t K_pad, void* stream);
+
 /* ---- host-side introspection (no GPU work, no device access when cus > 0): how gpusq_spgemm_fp16 / gpusq_spgemm_int8
  * (dt = GPUSQ_F16 / GPUSQ_I8 = the operand type) decompose a problem on a device with `cus` compute units (cus <= 0: the
  * current device).  out[0] = kernel (0: small kernel, 64 x 64 tiles; 1: small kernel, 128 x 128 tiles, any K % 16 == 0;

@@ -147,6 +147,18 @@ gpusq_status gpusq_prepare_weights(const float* W, gpusq_dtype dt, float* W_prun
   return launch_prepare_weights(W, dt, W_pruned, W_low, w_scale, values, meta, packed, N, K, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_im2col_patches(const void* img, void* X, gpusq_dtype dt, int64_t B, int64_t C, int64_t H, int64_t W,
+                                  int64_t P, int64_t K_pad, void* stream) {
+  if (!img || !X) return GPUSQ_ERR_NULL;
+  if (B <= 0 || C <= 0 || H <= 0 || W <= 0 || P <= 0 || H % P != 0 || W % P != 0) return GPUSQ_ERR_SHAPE;
+  if (C > 65536 || P > 4096 || H > (1 << 20) || W > (1 << 20)) return GPUSQ_ERR_SHAPE;
+  if (C * P * P > INT32_MAX || K_pad < C * P * P || K_pad > INT32_MAX) return GPUSQ_ERR_SHAPE;
+  if (B * C * H * W > kMaxElems || B * (H / P) * (W / P) * K_pad > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(img) || !aligned16(X)) return GPUSQ_ERR_ALIGN;
+  return launch_im2col_patches(img, X, dt, B, C, H, W, P, K_pad, (hipStream_t)stream);
+}
+
 gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]) {
   if (!out) return GPUSQ_ERR_NULL;
   if (M <= 0) return GPUSQ_ERR_SHAPE;

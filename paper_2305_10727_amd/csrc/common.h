@@ -108,6 +108,8 @@ gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilog
 
 gpusq_status launch_prune(const void* Win, void* Wout, uint8_t* mask, gpusq_dtype dt, int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_cast_f16(const float* in, void* out, int64_t n, hipStream_t s);
+gpusq_status launch_im2col_patches(const void* img, void* X, gpusq_dtype dt, int64_t B, int64_t C, int64_t H, int64_t W, int64_t P,
+                                   int64_t K_pad, hipStream_t s);
 gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
                              int64_t rows, int64_t cols, void* workspace, hipStream_t s);
 gpusq_status launch_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,

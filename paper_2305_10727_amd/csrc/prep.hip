@@ -81,6 +81,68 @@ __global__ void __launch_bounds__(256) cast_f16_kernel(const float* __restrict__
   }
 }
 
+// ---- patch embedding: images [B][C][H][W] -> flattened patches X [B*(H/P)*(W/P)][K_pad] (Sec. 3.3) ------------------------
+// Row m = (b, py, px) of X holds patch (py, px) of image b, column k = (c*P + i)*P + j holds pixel (py*P + i, px*P + j) of
+// channel c (the order of a convolution weight [D][C][P][P] flattened along its last three axes); columns C*P*P..K_pad-1
+// are zero.  One thread moves VEC consecutive columns, which lie in one image row when P % VEC == 0.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256) im2col_patches_kernel(const T* __restrict__ img, T* __restrict__ X, int C, int H, int W, int P,
+                                                             int K, int K_pad, int64_t units) {
+  typedef T vec_t __attribute__((ext_vector_type(VEC)));
+  const int kv = K_pad / VEC, px_n = W / P, py_n = H / P;
+  for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < units; u += (int64_t)gridDim.x * 256) {
+    const int64_t m = u / kv;
+    const int k0 = (int)(u - m * kv) * VEC;
+    vec_t v = vec_t(0);
+    if (k0 < K) {
+      const int c = k0 / (P * P), r = k0 - c * P * P, i = r / P, j = r - i * P;
+      const int px = (int)(m % px_n), py = (int)((m / px_n) % py_n);
+      const int64_t b = m / ((int64_t)px_n * py_n);
+      const T* src = img + ((b * C + c) * H + (int64_t)py * P + i) * W + (int64_t)px * P + j;
+      if constexpr (VEC == 1)
+        v = vec_t(*src);
+      else
+        v = *(const vec_t*)src;
+    }
+    *(vec_t*)(X + m * K_pad + k0) = v;
+  }
+}
+
+template <typename T>
+static gpusq_status launch_im2col_typed(const T* img, T* X, int64_t B, int64_t C, int64_t H, int64_t W, int64_t P, int64_t K_pad,
+                                        hipStream_t s) {
+  const int64_t M = B * (H / P) * (W / P);
+  const int K = (int)(C * P * P);
+  // the widest power-of-two move (up to 16 bytes) for which every source and destination address is aligned: it must
+  // divide P (a move stays inside one image row and pixel offsets are multiples of it), W and K_pad
+  int vec = 16 / (int)sizeof(T);
+  while (vec > 1 && (P % vec != 0 || W % vec != 0 || K_pad % vec != 0)) vec >>= 1;
+  const int64_t units = M * (K_pad / vec);
+  const int64_t want = ceil_div(units, 256);
+  const unsigned grid = (unsigned)(want < 16384 ? want : 16384);
+#define GPUSQ_IM2COL_CASE(V) \
+  case V:                    \
+    im2col_patches_kernel<T, V><<<grid, 256, 0, s>>>(img, X, (int)C, (int)H, (int)W, (int)P, K, (int)K_pad, units); \
+    break;
+  switch (vec) {
+    GPUSQ_IM2COL_CASE(16)
+    GPUSQ_IM2COL_CASE(8)
+    GPUSQ_IM2COL_CASE(4)
+    GPUSQ_IM2COL_CASE(2)
+    default:
+      im2col_patches_kernel<T, 1><<<grid, 256, 0, s>>>(img, X, (int)C, (int)H, (int)W, (int)P, K, (int)K_pad, units);
+      break;
+  }
+#undef GPUSQ_IM2COL_CASE
+  return check_launch();
+}
+
+gpusq_status launch_im2col_patches(const void* img, void* X, gpusq_dtype dt, int64_t B, int64_t C, int64_t H, int64_t W, int64_t P,
+                                   int64_t K_pad, hipStream_t s) {
+  if (dt == GPUSQ_I8) return launch_im2col_typed<int8_t>((const int8_t*)img, (int8_t*)X, B, C, H, W, P, K_pad, s);
+  return launch_im2col_typed<_Float16>((const _Float16*)img, (_Float16*)X, B, C, H, W, P, K_pad, s);
+}
+
 gpusq_status launch_cast_f16(const float* in, void* out, int64_t n, hipStream_t s) {
   const int64_t want = ceil_div(n, 256 * 4);
   cast_f16_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>(in, (_Float16*)out, n);

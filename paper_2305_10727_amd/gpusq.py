@@ -23,7 +23,7 @@ EXPORTS = [
     "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
     "gpusq_quantize_workspace_bytes",
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
-    "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
+    "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
 ]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_int8_dense.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+        L.gpusq_im2col_patches.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, i64, vp]
         L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
         for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
                      "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
@@ -150,6 +151,16 @@ def decompress(values, meta, K):
     _check(lib().gpusq_decompress(_ptr(values), _ptr(meta), _ptr(W), _TORCH_DT[values.dtype], N, K, _stream()),
            "gpusq_decompress")
     return W
+
+
+def im2col_patches(img, P, K_pad=None):
+    """gpusq_im2col_patches: img [B,C,H,W] (int8 or fp16) -> flattened patches [B*(H/P)*(W/P), K_pad] (zero-padded columns)"""
+    B, C, H, W = img.shape
+    K = C * P * P
+    K_pad = K if K_pad is None else K_pad
+    X = torch.empty((B * (H // P) * (W // P), K_pad), dtype=img.dtype, device=img.device)
+    _check(lib().gpusq_im2col_patches(_ptr(img), _ptr(X), _TORCH_DT[img.dtype], B, C, H, W, P, K_pad, _stream()), "gpusq_im2col_patches")
+    return X
 
 
 def spgemm_plan(dtype, M, N, K, epilogue=0, cus=0):

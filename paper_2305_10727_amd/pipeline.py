@@ -101,3 +101,47 @@ class SparseLinear:
         """all steps of the path in order, as one benchmark step times them"""
         self.prepare_weights(W)
         return self.forward(X, bias, out_scale)
+
+
+class SparsePatchEmbed:
+    """Patch embedding (a convolution with kernel = stride = P) on the sparse GEMM: images [B,C,H,W] -> tokens
+    [B*(H/P)*(W/P), D].  The weight [D,C,P,P] is flattened to [D, C*P*P] (zero-padded to whole 128-byte K steps) and
+    prepared like a linear layer's; an image is (quantised per tensor and) cut into flattened patches by
+    gpusq_im2col_patches, then multiplied by gpusq_spgemm_*."""
+
+    def __init__(self, B, C, H, W, P, D, precision="int8", bias=True, device="cuda"):
+        self.shape = (B, C, H, W)
+        self.P, self.D, self.precision = P, D, precision
+        self.K = C * P * P
+        step = 128 if precision == "int8" else 64  # whole 128-byte K steps: the tile kernel's requirement
+        self.K_pad = -(-self.K // step) * step
+        self.M = B * (H // P) * (W // P)
+        self.linear = SparseLinear(self.M, self.K_pad, D, precision, gelu=False, bias=bias, device=device)
+        xdt = torch.int8 if precision == "int8" else torch.float16
+        self.X = torch.empty((self.M, self.K_pad), dtype=xdt, device=device)
+        if precision == "int8":
+            n = B * C * H * W
+            self.img_q = torch.empty((B, C, H, W), dtype=torch.int8, device=device)
+            self.workspace = torch.empty((max(G.lib().gpusq_quantize_workspace_bytes(G.PER_TENSOR, 1, n), 16),), dtype=torch.uint8,
+                                         device=device)
+
+    def prepare_weights(self, Wc):
+        """Wc [D,C,P,P] fp32"""
+        Wflat = torch.zeros((self.D, self.K_pad), dtype=torch.float32, device=Wc.device)
+        Wflat[:, :self.K] = Wc.reshape(self.D, self.K)
+        self.linear.prepare_weights(Wflat, fused=self.K_pad * 4 <= 64 * 1024)
+
+    def forward(self, img, bias):
+        """img [B,C,H,W] fp16 (or fp32 on the int8 path)"""
+        L, s = G.lib(), G._stream()
+        B, C, H, W = self.shape
+        if self.precision == "int8":
+            G._check(L.gpusq_quantize_int8(_p(img), G._TORCH_DT[img.dtype], _p(self.img_q), _p(self.linear.act_scale), G.PER_TENSOR, 0,
+                                           1, B * C * H * W, _p(self.workspace), s), "gpusq_quantize_int8")
+            src, dt = self.img_q, G.I8
+        else:
+            src, dt = img, G.F16
+        G._check(L.gpusq_im2col_patches(_p(src), _p(self.X), dt, B, C, H, W, self.P, self.K_pad, s), "gpusq_im2col_patches")
+        if self.precision == "int8":
+            self.linear.Xq = self.X
+        return self.linear.gemm(self.X, bias)

@@ -73,6 +73,12 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_spgemm_fp16(good, None, None, good, 8, 8, 32, 0, None) == ERR_NULL
     assert lib.gpusq_spgemm_fp16(good, good, None, odd, 8, 8, 32, 0, None) == ERR_ALIGN
     assert lib.gpusq_spgemm_fp16(good, good, None, good, 0, 8, 32, 0, None) == ERR_SHAPE
+    lib.gpusq_im2col_patches.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, i64, vp]
+    assert lib.gpusq_im2col_patches(good, None, 2, 1, 3, 32, 32, 16, 768, None) == ERR_NULL
+    assert lib.gpusq_im2col_patches(good, good, 2, 1, 3, 30, 32, 16, 768, None) == ERR_SHAPE   # H % P
+    assert lib.gpusq_im2col_patches(good, good, 2, 1, 3, 32, 32, 16, 700, None) == ERR_SHAPE   # K_pad < C*P*P
+    assert lib.gpusq_im2col_patches(good, good, 0, 1, 3, 32, 32, 16, 768, None) == ERR_UNSUPPORTED
+    assert lib.gpusq_im2col_patches(odd, good, 2, 1, 3, 32, 32, 16, 768, None) == ERR_ALIGN
     lib.gpusq_packed_bytes.restype = ctypes.c_size_t
     lib.gpusq_packed_bytes.argtypes = [ci, i64, i64]
     # tiles of 256 channels x one 128-byte K step: 16 fragments of 1024 value bytes + 16 x 64 lanes of index bytes

@@ -502,3 +502,63 @@ def test_error_statuses(g):
     with pytest.raises(g.GpusqError) as e:  # misaligned pointer
         g.prune_2to4(dev(np.zeros(20, np.float32))[1:17].view(4, 4))
     assert e.value.status == g.ERR_ALIGN
+
+
+# ---------------------------------------------------------------- patch embedding (Sec. 3.3) on the sparse GEMM
+def _patches_np(img, P, K_pad):
+    B, C, H, W = img.shape
+    X = img.reshape(B, C, H // P, P, W // P, P).transpose(0, 2, 4, 1, 3, 5).reshape(B * (H // P) * (W // P), C * P * P)
+    out = np.zeros((X.shape[0], K_pad), img.dtype)
+    out[:, :X.shape[1]] = X
+    return out
+
+
+@pytest.mark.parametrize("B,C,H,W,P,K_pad", [(2, 3, 32, 48, 16, 768), (3, 3, 28, 42, 14, 592), (2, 3, 16, 24, 4, 48),
+                                             (1, 1, 8, 8, 8, 64), (2, 2, 12, 20, 4, 48), (1, 3, 224, 224, 16, 768)])
+def test_im2col_patches_is_the_index_permutation(g, B, C, H, W, P, K_pad):
+    rng = np.random.default_rng(B * 1000 + P)
+    img8 = rng.integers(-127, 128, (B, C, H, W), dtype=np.int8)
+    assert np.array_equal(host(g.im2col_patches(dev(img8), P, K_pad)), _patches_np(img8, P, K_pad))
+    img16 = rng.standard_normal((B, C, H, W)).astype(np.float16)
+    got = host(g.im2col_patches(dev(img16), P, K_pad))
+    assert np.array_equal(got.view(np.uint16), _patches_np(img16, P, K_pad).view(np.uint16))
+
+
+@pytest.mark.parametrize("B,C,H,W,P,D,seed", [(4, 3, 224, 224, 16, 768, 31), (2, 3, 56, 56, 14, 64, 32), (3, 3, 32, 32, 4, 128, 33)])
+def test_patch_embedding_matches_the_convolution_oracle(g, B, C, H, W, P, D, seed):
+    """2:4-pruned, INT8 patch embedding through im2col + sparse GEMM == the strided convolution of the oracle, bit for bit in
+    the int32 accumulators and in the fp16 output of dequant + bias; the FP16 path within the GEMM tolerance."""
+    rng = np.random.default_rng(seed)
+    K = C * P * P
+    K_pad = -(-K // 16) * 16
+    img = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    Wc = (rng.standard_normal((D, C, P, P)) * 0.02).astype(np.float32)
+    bias = (rng.standard_normal(D) * 0.01).astype(np.float32)
+    Wflat = np.zeros((D, K_pad), np.float32)
+    Wflat[:, :K] = Wc.reshape(D, K)
+    # oracle: prune along the flattened (c, i, j) axis, quantise, convolve
+    Pm, _ = oracle.prune_2to4(Wflat)
+    Wq, s_w = oracle.quantize_rows_int8(Pm)
+    imgq, s_a = oracle.quantize_tensor_int8(img.reshape(1, -1))
+    imgq = imgq.reshape(B, C, H, W)
+    acc, _ = oracle.patch_conv_int8(imgq, Wq[:, :K].reshape(D, C, P, P))
+    # GPU: the same chain through the C ABI
+    Wp = g.prune_2to4(dev(Wflat))
+    Wq_g, s_w_g = g.quantize_int8(Wp, g.PER_ROW)
+    vals, meta = g.compress(Wq_g)
+    packed = g.pack(vals, meta, K_pad)
+    imgq_g, s_a_g = g.quantize_int8(dev(img.reshape(1, -1)), g.PER_TENSOR)
+    assert np.array_equal(host(imgq_g).reshape(B, C, H, W), imgq) and np.array_equal(host(Wq_g), Wq)
+    Xq = g.im2col_patches(imgq_g.reshape(B, C, H, W), P, K_pad)
+    got = g.spgemm_int8(Xq, packed, D, out_dtype=torch.int32)
+    assert np.array_equal(host(got), acc)
+    y = host(g.spgemm_int8(Xq, packed, D, act_scale=s_a_g, w_scale=s_w_g, bias=dev(bias)))
+    assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(acc, s_a, s_w, bias)["y16"].view(np.uint16))
+    # FP16 path
+    img16 = img.astype(np.float16)
+    W16 = Pm.astype(np.float16)
+    a64, _ = oracle.patch_conv_f16(img16, W16[:, :K].reshape(D, C, P, P))
+    ref = oracle.epilogue_fp16_f64(a64, bias, False)["ref"]
+    v16, m16 = g.compress(g.cast_f16(Wp))
+    yh = g.spgemm_fp16(g.im2col_patches(dev(img16), P, K_pad), g.pack(v16, m16, K_pad), D, bias=dev(bias))
+    assert rel_err(host(yh), ref) <= 2e-3
