@@ -401,7 +401,9 @@ __device__ __forceinline__ void batch_epilogue(const GemmArgs& a, const typename
 //   lanes c < 8 : store 1 = own row, first half (own)        store 2 = row c+8, first half (from lane c+8)
 //   lanes c >= 8: store 1 = row c-8, second half (from c-8)  store 2 = own row, second half (own)
 // Needs N % 8 == 0 (a lane's 8 channels are inside or outside together).
-template <bool IS_I8, int GELU>
+// CHECKED = false: the wavefront's 128 channels x 64 rows all lie inside Y (the caller has checked), so the stores carry
+// no per-lane tests and no branches.
+template <bool IS_I8, int GELU, bool CHECKED>
 __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM],
                                               const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active) {
   const int c = lane & 15, q = lane >> 4, up = c >> 3;
@@ -429,7 +431,7 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
     const bool n_ok = n_wave + gp * kRowBlock + up * 32 + q * 8 < a.N;
 #pragma unroll
     for (int mt = 0; mt < kTileTM; ++mt) {
-      if (mt < tm_active) {
+      if (!CHECKED || mt < tm_active) {
         ep_v4i H[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -465,8 +467,8 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
         }
         const int64_t row = m_wave + mt * 16 + (c & 7);
         uint8_t* y = y0 + mt * slab_bytes + gp * (kRowBlock * 2);
-        if (n_ok && row < a.M) __builtin_nontemporal_store(s1, (ep_v4i*)y);
-        if (n_ok && row + 8 < a.M) __builtin_nontemporal_store(s2, (ep_v4i*)(y + half_bytes));
+        if (!CHECKED || (n_ok && row < a.M)) __builtin_nontemporal_store(s1, (ep_v4i*)y);
+        if (!CHECKED || (n_ok && row + 8 < a.M)) __builtin_nontemporal_store(s2, (ep_v4i*)(y + half_bytes));
       }
     }
   }
@@ -624,7 +626,10 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
     // depends on the lanes: then the next tile waits for everything, because a count that is too high would let its
     // copies go unwaited).
     if (OUT == GPUSQ_F16 && (a.N & 7) == 0) {
-      line_epilogue<IS_I8, GELU>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
+      if (t.tm == kTileTM && rows >= kTileTM * 16 && chans >= kTileTN * 16)
+        line_epilogue<IS_I8, GELU, false>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, kTileTM);
+      else
+        line_epilogue<IS_I8, GELU, true>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
       // per pair of batches (64 channels) with a channel inside N: one store per slab with a row inside M among its
       // first 8 rows and one for its last 8 rows
       int n = 0;
