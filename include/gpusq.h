@@ -141,6 +141,19 @@ gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const floa
 gpusq_status gpusq_im2col_patches(const void* img, void* X, gpusq_dtype dt, int64_t B, int64_t C, int64_t H, int64_t W,
                                   int64_t P, int64_t K_pad, void* stream);
 
+/* The same layer without the flattened-patch buffer, for P = 16: the sparse GEMM fetches its activation tiles from the
+ * images directly (for P = 16 a 16-byte piece of a flattened patch is 16 consecutive pixels of one image row).
+ *   img [B][C][H][W] int8 (quantised with gpusq_quantize_int8, scale act_scale[0]) or fp16; Wpacked from
+ *   gpusq_pack(dt, D, C*256) on the weights [D][C][16][16] flattened; Y [B*(H/16)*(W/16)][D] fp16
+ *   = fp16( fma((float)acc, act_scale[0] * w_scale[d], bias[d]) ) (int8) / fp16(acc + bias[d]) (fp16); epilogue: GPUSQ_EPI_NONE
+ *   or GPUSQ_EPI_BIAS.  H % 16 == 0, W % 16 == 0, D % 4 == 0; the image batch must be smaller than 4 GiB.
+ *   GPUSQ_ERR_UNSUPPORTED for problems with B*(H/16)*(W/16)*D <= 262144 (use gpusq_im2col_patches + gpusq_spgemm_*). */
+gpusq_status gpusq_patch_embed16_int8(const int8_t* img, const void* Wpacked, const float* act_scale, const float* w_scale,
+                                      const float* bias, void* Y, int64_t B, int64_t C, int64_t H, int64_t W, int64_t D,
+                                      int epilogue, void* stream);
+gpusq_status gpusq_patch_embed16_fp16(const void* img, const void* Wpacked, const float* bias, void* Y, int64_t B, int64_t C,
+                                      int64_t H, int64_t W, int64_t D, int epilogue, void* stream);
+
 /* ---- host-side introspection (no GPU work, no device access when cus > 0): how gpusq_spgemm_fp16 / gpusq_spgemm_int8
  * (dt = GPUSQ_F16 / GPUSQ_I8 = the operand type) decompose a problem on a device with `cus` compute units (cus <= 0: the
  * current device).  out[0] = kernel (0: small kernel, 64 x 64 tiles; 1: small kernel, 128 x 128 tiles, any K % 16 == 0;

@@ -159,6 +159,36 @@ gpusq_status gpusq_im2col_patches(const void* img, void* X, gpusq_dtype dt, int6
   return launch_im2col_patches(img, X, dt, B, C, H, W, P, K_pad, (hipStream_t)stream);
 }
 
+static gpusq_status patch_embed16(bool is_i8, const void* img, const void* Wpacked, const float* act_scale, const float* w_scale,
+                                  const float* bias, void* Y, int64_t B, int64_t C, int64_t H, int64_t W, int64_t D, int epilogue,
+                                  void* stream) {
+  if (is_i8 && (!act_scale || !w_scale)) return GPUSQ_ERR_NULL;
+  if (B <= 0 || C <= 0 || H <= 0 || W <= 0 || H % 16 != 0 || W % 16 != 0) return GPUSQ_ERR_SHAPE;
+  if (C > 65536 || H > (1 << 20) || W > (1 << 20)) return GPUSQ_ERR_SHAPE;
+  const int64_t M = B * (H / 16) * (W / 16), K = C * 256;
+  gpusq_status st = check_gemm(img, Wpacked, bias, Y, M, D, K, epilogue);
+  if (st != GPUSQ_OK) return st;
+  if (B * C * H * W * (is_i8 ? 1 : 2) >= ((int64_t)1 << 32)) return GPUSQ_ERR_SHAPE;  // 32-bit per-lane byte offsets
+  if (epilogue & GPUSQ_EPI_GELU) return GPUSQ_ERR_UNSUPPORTED;
+  GemmArgs a{img, Wpacked, act_scale, w_scale, bias, nullptr, Y, (int)M, (int)D, (int)K, epilogue, (int)GPUSQ_F16};
+  a.patch_P = 16;
+  a.patch_C = (int)C;
+  a.patch_H = (int)H;
+  a.patch_W = (int)W;
+  return launch_spgemm(is_i8, a, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_patch_embed16_int8(const int8_t* img, const void* Wpacked, const float* act_scale, const float* w_scale,
+                                      const float* bias, void* Y, int64_t B, int64_t C, int64_t H, int64_t W, int64_t D,
+                                      int epilogue, void* stream) {
+  return patch_embed16(true, img, Wpacked, act_scale, w_scale, bias, Y, B, C, H, W, D, epilogue, stream);
+}
+
+gpusq_status gpusq_patch_embed16_fp16(const void* img, const void* Wpacked, const float* bias, void* Y, int64_t B, int64_t C,
+                                      int64_t H, int64_t W, int64_t D, int epilogue, void* stream) {
+  return patch_embed16(false, img, Wpacked, nullptr, nullptr, bias, Y, B, C, H, W, D, epilogue, stream);
+}
+
 gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]) {
   if (!out) return GPUSQ_ERR_NULL;
   if (M <= 0) return GPUSQ_ERR_SHAPE;

@@ -100,6 +100,10 @@ struct GemmArgs {
   int M, N, K;
   int epilogue;
   int out_dt;
+  // Patch-embedding mode (patch_P != 0): X is an image batch [B][C][H][W] and row m = (b, py, px) of the X operand is
+  // patch (py, px) of image b, column (c*P + i)*P + j its pixel (py*P + i, px*P + j) of channel c; M = B*(H/P)*(W/P),
+  // K = C*P*P.  The tile kernel then fetches its X slabs from the image directly (no flattened-patch buffer).
+  int patch_P = 0, patch_C = 0, patch_H = 0, patch_W = 0;
 };
 
 gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s);

@@ -220,6 +220,36 @@ __device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], int64_t m0, 
   }
 }
 
+// The same for the patch-embedding mode with P = 16: the 16-byte chunk kc of row m = (b, py, px) of the X operand is, for
+// int8, the 16 pixels of row py*16 + kc % 16 of patch column px in channel kc / 16 (for fp16, with 2 chunks per patch row:
+// row (kc / 2) % 16, channel kc / 32, half kc % 2).  A K step of 8 chunks stays inside one channel, so a lane's address
+// splits into a per-lane part that does not depend on the step (returned here, relative to the image batch: the patch's
+// first pixel plus the lane's logical chunk inside a step) and a wavefront-uniform part per step (patch_step_offset).
+template <bool IS_I8>
+__device__ __forceinline__ void patch_x_offsets(uint32_t (&xoff)[4], int64_t m0, const GemmArgs& a, int wave, int lane) {
+  constexpr int ES = IS_I8 ? 1 : 2;
+  const int px_n = a.patch_W / 16, py_n = a.patch_H / 16;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 8 * (wave + i * 8) + (lane >> 3);
+    const int ch = (lane & 7) ^ ((r >> 1) & 7);  // logical chunk of the step this lane fetches (see tile_x_offsets)
+    int64_t m = m0 + r;
+    m = m < a.M ? m : (int64_t)a.M - 1;          // rows past the end re-read the last row
+    const int px = (int)(m % px_n), py = (int)((m / px_n) % py_n);
+    const int64_t b = m / ((int64_t)px_n * py_n);
+    const int64_t pixel = ((b * a.patch_C) * a.patch_H + py * 16) * a.patch_W + px * 16;  // first pixel of the patch, channel 0
+    const int row_in_step = IS_I8 ? ch : (ch >> 1), half = IS_I8 ? 0 : (ch & 1);
+    xoff[i] = (uint32_t)((pixel + (int64_t)row_in_step * a.patch_W) * ES + half * 16);
+  }
+}
+// Byte offset (wavefront-uniform) that K step ks adds: channel ks / S, first patch row (ks % S) * (16 / S), where a channel
+// takes S = 2 (int8) or 4 (fp16) steps.
+template <bool IS_I8>
+__device__ __forceinline__ int64_t patch_step_offset(const GemmArgs& a, int ks) {
+  constexpr int ES = IS_I8 ? 1 : 2, S = IS_I8 ? 2 : 4;
+  return ((int64_t)(ks / S) * a.patch_H * a.patch_W + (int64_t)(ks % S) * (16 / S) * a.patch_W) * ES;
+}
+
 // Per-lane byte offsets of the B operand inside an X slab: lane l reads row wm*16*tm + 16*mt + l%16, the 16-byte
 // chunks l/16 and 4 + l/16 of it (at their swizzled positions).
 struct BOffsets {
@@ -474,7 +504,8 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
   }
 }
 
-template <bool IS_I8, int GELU, int OUT>
+// PATCH: the X operand is gathered from an image batch (patch embedding with P = 16, see patch_x_offsets).
+template <bool IS_I8, int GELU, int OUT, bool PATCH = false>
 __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, const TilePlan plan) {
   typedef typename AccT<IS_I8>::type acc_t;
   constexpr int ES = IS_I8 ? 1 : 2;
@@ -540,14 +571,22 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
     pf_ks = 0;
     if (item < my_items) {
       const Tile t = tile_of(item);
-      tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane);
-      pf_x = Xg + t.m0 * k_bytes;
+      if constexpr (PATCH) {
+        patch_x_offsets<IS_I8>(pf_xoff, t.m0, a, wave, lane);
+        pf_x = Xg;
+      } else {
+        tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane);
+        pf_x = Xg + t.m0 * k_bytes;
+      }
       pf_w = Wg + t.n_blk * w_col_bytes;
     }
   };
   auto advance = [&]() {
     ++pf_ks;
-    pf_x += kStepBytes;
+    if constexpr (PATCH)
+      pf_x = Xg + patch_step_offset<IS_I8>(a, pf_ks);
+    else
+      pf_x += kStepBytes;
     pf_w += tile_bytes(IS_I8);
     if (pf_ks == ksteps) seek(pf_item + 1);
   };
@@ -866,15 +905,21 @@ template <bool IS_I8>
 static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
   const int choice = kernel_choice(IS_I8, a.M, a.N, a.K);
+  const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
+  // the fused patch gather exists in the tile kernel only, for 16 x 16 patches, fp16 output, no GELU
+  if (a.patch_P != 0 && (choice != 2 || a.patch_P != 16 || a.out_dt != GPUSQ_F16 || gelu)) return GPUSQ_ERR_UNSUPPORTED;
   if (choice == 0) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);
   if (choice == 1) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);
-  const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
   // persistent grid: one workgroup per CU, never more workgroups than tiles
   const int resident = num_cus();
   const int ksteps = (int)(k_bytes / kStepBytes);
   const TilePlan plan = make_plan(a.M, a.N, resident, ksteps, gelu);
   const dim3 grid((unsigned)grid_for(plan, resident));
   if ((ceil_div(plan.total, grid.x) + 2) * ksteps >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
+  if (a.patch_P != 0) {
+    spgemm_tile_kernel<IS_I8, 0, GPUSQ_F16, true><<<grid, 512, 0, s>>>(a, plan);
+    return check_launch();
+  }
   if constexpr (IS_I8) {
     if (a.out_dt == GPUSQ_I32)
       spgemm_tile_kernel<true, 0, GPUSQ_I32><<<grid, 512, 0, s>>>(a, plan);

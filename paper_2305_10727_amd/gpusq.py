@@ -23,7 +23,7 @@ EXPORTS = [
     "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
     "gpusq_quantize_workspace_bytes",
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
-    "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
+    "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
 ]
 
 
@@ -68,6 +68,8 @@ def lib():
         L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_int8_dense.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
         L.gpusq_im2col_patches.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, i64, vp]
+        L.gpusq_patch_embed16_int8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
+        L.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
         for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
                      "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
@@ -161,6 +163,20 @@ def im2col_patches(img, P, K_pad=None):
     X = torch.empty((B * (H // P) * (W // P), K_pad), dtype=img.dtype, device=img.device)
     _check(lib().gpusq_im2col_patches(_ptr(img), _ptr(X), _TORCH_DT[img.dtype], B, C, H, W, P, K_pad, _stream()), "gpusq_im2col_patches")
     return X
+
+
+def patch_embed16(img, packed, D, act_scale=None, w_scale=None, bias=None):
+    """gpusq_patch_embed16_int8 / _fp16: img [B,C,H,W] int8 or fp16 -> tokens [B*(H/16)*(W/16), D] fp16 (patches gathered by the GEMM)"""
+    B, C, H, W = img.shape
+    Y = torch.empty((B * (H // 16) * (W // 16), D), dtype=torch.float16, device=img.device)
+    epi = EPI_BIAS if bias is not None else 0
+    if img.dtype == torch.int8:
+        st = lib().gpusq_patch_embed16_int8(_ptr(img), _ptr(packed), _ptr(act_scale), _ptr(w_scale), _ptr(bias), _ptr(Y), B, C, H, W, D,
+                                            epi, _stream())
+    else:
+        st = lib().gpusq_patch_embed16_fp16(_ptr(img), _ptr(packed), _ptr(bias), _ptr(Y), B, C, H, W, D, epi, _stream())
+    _check(st, "gpusq_patch_embed16")
+    return Y
 
 
 def spgemm_plan(dtype, M, N, K, epilogue=0, cus=0):

@@ -107,10 +107,15 @@ class SparsePatchEmbed:
     """Patch embedding (a convolution with kernel = stride = P) on the sparse GEMM: images [B,C,H,W] -> tokens
     [B*(H/P)*(W/P), D].  The weight [D,C,P,P] is flattened to [D, C*P*P] (zero-padded to whole 128-byte K steps) and
     prepared like a linear layer's; an image is (quantised per tensor and) cut into flattened patches by
-    gpusq_im2col_patches, then multiplied by gpusq_spgemm_*."""
+    gpusq_im2col_patches, then multiplied by gpusq_spgemm_*; with P = 16 (and a problem large enough for the tile kernel)
+    gpusq_patch_embed16_* lets the GEMM gather the patches itself (fused=True; the default for fp16, where it is measurably
+    faster: a 16-byte piece of an int8 patch row touches a cache line of its own, which costs the int8 GEMM as much as the
+    separate im2col pass saves)."""
 
-    def __init__(self, B, C, H, W, P, D, precision="int8", bias=True, device="cuda"):
+    def __init__(self, B, C, H, W, P, D, precision="int8", bias=True, device="cuda", fused=None):
         self.shape = (B, C, H, W)
+        can_fuse = P == 16 and B * (H // P) * (W // P) * D > 256 * 1024
+        self.fused = (can_fuse and precision == "fp16") if fused is None else (fused and can_fuse)
         self.P, self.D, self.precision = P, D, precision
         self.K = C * P * P
         step = 128 if precision == "int8" else 64  # whole 128-byte K steps: the tile kernel's requirement
@@ -141,6 +146,15 @@ class SparsePatchEmbed:
             src, dt = self.img_q, G.I8
         else:
             src, dt = img, G.F16
+        if self.fused:
+            lin, epi = self.linear, self.linear.epilogue & G.EPI_BIAS
+            if self.precision == "int8":
+                G._check(L.gpusq_patch_embed16_int8(_p(src), _p(lin.packed), _p(lin.act_scale), _p(lin.w_scale), _p(bias), _p(lin.Y),
+                                                    B, C, H, W, self.D, epi, s), "gpusq_patch_embed16_int8")
+            else:
+                G._check(L.gpusq_patch_embed16_fp16(_p(src), _p(lin.packed), _p(bias), _p(lin.Y), B, C, H, W, self.D, epi, s),
+                         "gpusq_patch_embed16_fp16")
+            return lin.Y
         G._check(L.gpusq_im2col_patches(_p(src), _p(self.X), dt, B, C, H, W, self.P, self.K_pad, s), "gpusq_im2col_patches")
         if self.precision == "int8":
             self.linear.Xq = self.X

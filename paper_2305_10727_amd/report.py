@@ -97,8 +97,8 @@ def main():
     for (cfg_name, prec), (ts, td, ops) in totals.items():
         lines.append("| %s | %s | %.3f | %.3f | %.2f | %.0f |" % (cfg_name, prec, ts / 1e3, td / 1e3, td / ts, ops / ts / 1e6))
     lines += ["", "Patch embedding (a convolution with kernel = stride = P, run as quantise + im2col + sparse GEMM; images N(0,1) fp16, "
-              "hot buffers):", "", "| model | images | P | M | K | N | path | quantise us | im2col us | sparse GEMM us | whole layer us |",
-              "|---|---|---|---|---|---|---|---|---|---|---|"]
+              "hot buffers):", "", "| model | images | P | M | K | N | path | quantise us | im2col us | sparse GEMM us | whole layer us | whole layer, patches "
+              "gathered by the GEMM (P = 16) us |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
     dev = torch.device("cuda")
     for model, B, HW, P, D in [("ViT-B/16, batch 64", 64, 224, 16, 768), ("ViT-L/16, batch 256", 256, 224, 16, 1024),
                                ("ViT-H/14, batch 256", 256, 224, 14, 1280)]:
@@ -106,7 +106,13 @@ def main():
         Wc = torch.randn(D, 3, P, P, device=dev) * 0.02
         bias = torch.randn(D, device=dev) * 0.01
         for prec in ("int8", "fp16"):
-            pe = SparsePatchEmbed(B, 3, HW, HW, P, D, prec)
+            t_fused = None
+            if P == 16:
+                pf = SparsePatchEmbed(B, 3, HW, HW, P, D, prec, fused=True)
+                pf.prepare_weights(Wc)
+                t_fused = _time([lambda: pf.forward(img, bias)], a.iters)
+                del pf
+            pe = SparsePatchEmbed(B, 3, HW, HW, P, D, prec, fused=False)
             pe.prepare_weights(Wc)
             pe.forward(img, bias)
             t_all = _time([lambda: pe.forward(img, bias)], a.iters)
@@ -114,8 +120,8 @@ def main():
             src = pe.img_q if prec == "int8" else img
             t_i2c = _time([lambda: G.im2col_patches(src, P, pe.K_pad)], a.iters)
             t_q = _time([lambda: G.quantize_int8(img.reshape(1, -1), G.PER_TENSOR)], a.iters) if prec == "int8" else 0.0
-            lines.append("| %s | %dx3x%dx%d | %d | %d | %d | %d | %s | %.1f | %.1f | %.1f | %.1f |" % (
-                model, B, HW, HW, P, pe.M, pe.K_pad, D, prec, t_q, t_i2c, t_gemm, t_all))
+            lines.append("| %s | %dx3x%dx%d | %d | %d | %d | %d | %s | %.1f | %.1f | %.1f | %.1f | %s |" % (
+                model, B, HW, HW, P, pe.M, pe.K_pad, D, prec, t_q, t_i2c, t_gemm, t_all, "%.1f" % t_fused if t_fused else "-"))
             print(lines[-1], flush=True)
             del pe
             torch.cuda.empty_cache()

@@ -79,6 +79,13 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_im2col_patches(good, good, 2, 1, 3, 32, 32, 16, 700, None) == ERR_SHAPE   # K_pad < C*P*P
     assert lib.gpusq_im2col_patches(good, good, 0, 1, 3, 32, 32, 16, 768, None) == ERR_UNSUPPORTED
     assert lib.gpusq_im2col_patches(odd, good, 2, 1, 3, 32, 32, 16, 768, None) == ERR_ALIGN
+    lib.gpusq_patch_embed16_int8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
+    assert lib.gpusq_patch_embed16_int8(good, good, None, good, None, good, 4, 3, 224, 224, 768, 0, None) == ERR_NULL
+    assert lib.gpusq_patch_embed16_int8(good, good, good, good, None, good, 4, 3, 220, 224, 768, 0, None) == ERR_SHAPE
+    assert lib.gpusq_patch_embed16_int8(good, good, good, good, None, good, 4, 3, 224, 224, 768, 2, None) == ERR_UNSUPPORTED  # GELU
+    assert lib.gpusq_patch_embed16_int8(good, good, good, good, None, good, 1, 3, 32, 32, 64, 0, None) == ERR_UNSUPPORTED   # too small
+    lib.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
+    assert lib.gpusq_patch_embed16_fp16(good, good, None, good, 4, 3, 224, 224, 768, 1, None) == ERR_NULL                  # bias flag
     lib.gpusq_packed_bytes.restype = ctypes.c_size_t
     lib.gpusq_packed_bytes.argtypes = [ci, i64, i64]
     # tiles of 256 channels x one 128-byte K step: 16 fragments of 1024 value bytes + 16 x 64 lanes of index bytes

@@ -562,3 +562,43 @@ def test_patch_embedding_matches_the_convolution_oracle(g, B, C, H, W, P, D, see
     v16, m16 = g.compress(g.cast_f16(Wp))
     yh = g.spgemm_fp16(g.im2col_patches(dev(img16), P, K_pad), g.pack(v16, m16, K_pad), D, bias=dev(bias))
     assert rel_err(host(yh), ref) <= 2e-3
+
+
+@pytest.mark.parametrize("B,C,H,W,D,seed", [(4, 3, 224, 224, 768, 41), (6, 3, 208, 176, 516, 42), (8, 1, 160, 160, 384, 43)])
+def test_fused_patch_embedding_matches_the_convolution_oracle(g, B, C, H, W, D, seed):
+    """gpusq_patch_embed16_*: the sparse GEMM gathers 16 x 16 patches from the images itself; same bars as the im2col route
+    (fp16 output of dequant + bias bit-exact against the oracle's convolution, FP16 path within the GEMM tolerance) and equal,
+    bit for bit, to im2col + gpusq_spgemm_* on the same operands.  Shapes: several tiles per image row block, a ragged last
+    tile, D not a multiple of 256, one and three channels."""
+    rng = np.random.default_rng(seed)
+    P, K = 16, C * 256
+    img = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    Wc = (rng.standard_normal((D, C, P, P)) * 0.02).astype(np.float32)
+    bias = (rng.standard_normal(D) * 0.01).astype(np.float32)
+    Pm, _ = oracle.prune_2to4(Wc.reshape(D, K))
+    Wq, s_w = oracle.quantize_rows_int8(Pm)
+    imgq, s_a = oracle.quantize_tensor_int8(img.reshape(1, -1))
+    acc, _ = oracle.patch_conv_int8(imgq.reshape(B, C, H, W), Wq.reshape(D, C, P, P))
+    Wp = g.prune_2to4(dev(Wc.reshape(D, K)))
+    Wq_g, s_w_g = g.quantize_int8(Wp, g.PER_ROW)
+    vals, meta = g.compress(Wq_g)
+    packed = g.pack(vals, meta, K)
+    imgq_g, s_a_g = g.quantize_int8(dev(img.reshape(1, -1)), g.PER_TENSOR)
+    imgq_g = imgq_g.reshape(B, C, H, W)
+    for b_np, b_t in ((None, None), (bias, dev(bias))):
+        y = g.patch_embed16(imgq_g, packed, D, act_scale=s_a_g, w_scale=s_w_g, bias=b_t)
+        assert np.array_equal(host(y).view(np.uint16), oracle.epilogue_int8_f32(acc, s_a, s_w, b_np)["y16"].view(np.uint16))
+        y2 = g.spgemm_int8(g.im2col_patches(imgq_g, P, K), packed, D, act_scale=s_a_g, w_scale=s_w_g, bias=b_t)
+        assert torch.equal(y, y2)
+    img16 = img.astype(np.float16)
+    a64, _ = oracle.patch_conv_f16(img16, Pm.astype(np.float16).reshape(D, C, P, P))
+    ref = oracle.epilogue_fp16_f64(a64, bias, False)["ref"]
+    v16, m16 = g.compress(g.cast_f16(Wp))
+    p16 = g.pack(v16, m16, K)
+    yh = g.patch_embed16(dev(img16), p16, D, bias=dev(bias))
+    assert rel_err(host(yh), ref) <= 2e-3
+    assert torch.equal(yh, g.spgemm_fp16(g.im2col_patches(dev(img16), P, K), p16, D, bias=dev(bias)))
+    # a problem too small for the tile kernel is refused, not mis-computed
+    small = dev(rng.integers(-5, 5, (1, C, 32, 32), dtype=np.int8))
+    with pytest.raises(g.GpusqError):
+        g.patch_embed16(small, packed, D, act_scale=s_a_g, w_scale=s_w_g)
