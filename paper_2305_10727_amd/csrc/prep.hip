@@ -108,6 +108,47 @@ __global__ void __launch_bounds__(256) im2col_patches_kernel(const T* __restrict
   }
 }
 
+// The same for patch sizes whose rows are not multiples of 16 bytes (P = 14): one workgroup per (image, channel, row of
+// patches).  The P image rows of that strip are one contiguous span of P*W elements: it is read into LDS with 4-byte
+// loads, and written out as W/P runs of P*P consecutive columns (one per patch), 4 bytes per thread and store, each word
+// gathered from LDS.  The workgroups of channel 0 also zero the padding columns of their rows.
+// Needs (W * sizeof(T)) % 4 == 0, (P*P * sizeof(T)) % 4 == 0, (K_pad * sizeof(T)) % 4 == 0 and a span of at most 48 KB.
+template <typename T>
+__global__ void __launch_bounds__(256) im2col_strip_kernel(const T* __restrict__ img, T* __restrict__ X, int C, int H, int W, int P,
+                                                           int K, int K_pad) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t strip_raw[];
+  T* strip = (T*)strip_raw;
+  constexpr int EPW = 4 / (int)sizeof(T);  // elements per 4-byte word
+  const int py_n = H / P, px_n = W / P;
+  const int py = blockIdx.x % py_n, c = (blockIdx.x / py_n) % C;
+  const int64_t b = blockIdx.x / (py_n * C);
+  const int span_words = P * W / EPW;
+  const uint32_t* src = (const uint32_t*)(img + ((b * C + c) * H + (int64_t)py * P) * W);
+  for (int q = threadIdx.x; q < span_words; q += 256) ((uint32_t*)strip)[q] = src[q];
+  __syncthreads();
+  const int wpr = P * P / EPW;  // words per run
+  const int64_t m0 = (b * py_n + py) * px_n;
+  for (int q = threadIdx.x; q < span_words; q += 256) {
+    const int px = q / wpr, rq = q - px * wpr;
+    T e[EPW];
+#pragma unroll
+    for (int t = 0; t < EPW; ++t) {
+      const int r = rq * EPW + t, i = r / P, j = r - i * P;
+      e[t] = strip[i * W + px * P + j];
+    }
+    uint32_t word;
+    __builtin_memcpy(&word, e, 4);
+    *(uint32_t*)(X + (m0 + px) * K_pad + (int64_t)c * P * P + rq * EPW) = word;
+  }
+  if (c == 0) {
+    const int pad_words = (K_pad - K) / EPW;
+    for (int q = threadIdx.x; q < pad_words * px_n; q += 256) {
+      const int px = q / pad_words, w = q - px * pad_words;
+      *(uint32_t*)(X + (m0 + px) * K_pad + K + w * EPW) = 0u;
+    }
+  }
+}
+
 template <typename T>
 static gpusq_status launch_im2col_typed(const T* img, T* X, int64_t B, int64_t C, int64_t H, int64_t W, int64_t P, int64_t K_pad,
                                         hipStream_t s) {
@@ -117,6 +158,12 @@ static gpusq_status launch_im2col_typed(const T* img, T* X, int64_t B, int64_t C
   // divide P (a move stays inside one image row and pixel offsets are multiples of it), W and K_pad
   int vec = 16 / (int)sizeof(T);
   while (vec > 1 && (P % vec != 0 || W % vec != 0 || K_pad % vec != 0)) vec >>= 1;
+  const int64_t span_bytes = P * W * (int64_t)sizeof(T);
+  if (vec * sizeof(T) < 16 && (W * sizeof(T)) % 4 == 0 && (P * P * sizeof(T)) % 4 == 0 && (K_pad * sizeof(T)) % 4 == 0 &&
+      (K * sizeof(T)) % 4 == 0 && span_bytes <= 48 * 1024 && B * C * (H / P) <= INT32_MAX) {
+    im2col_strip_kernel<T><<<(unsigned)(B * C * (H / P)), 256, (size_t)span_bytes, s>>>(img, X, (int)C, (int)H, (int)W, (int)P, K, (int)K_pad);
+    return check_launch();
+  }
   const int64_t units = M * (K_pad / vec);
   const int64_t want = ceil_div(units, 256);
   const unsigned grid = (unsigned)(want < 16384 ? want : 16384);
