@@ -97,10 +97,10 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs& a, const typename 
 // ------------------------------------------------------------------------------------------------ tile kernel
 // One persistent workgroup of 8 wavefronts per CU on tiles of 256 channels x 64*tm rows (tm <= 4): 2 wavefronts along n x
 // 4 along m, 128 channels x 16*tm rows and 128 accumulator registers each.  All wavefronts run the K loop of a tile,
-// then all run its epilogue.  With two wavefronts per SIMD in the same phase, two of them issue matrix instructions in
-// the K loop and two issue the epilogue's vector arithmetic (a lone wavefront cannot issue either kind back to back),
-// and the weight tile is brought into the CU once per 256 rows: 52 KB per K step through the vector-memory path, which
-// at 48-64 bytes per clock and CU is the narrowest pipe of the K loop.
+// then all run its epilogue.  With two wavefronts per SIMD in the same phase, a SIMD always has a second wavefront to
+// issue from while one waits (for LDS data in the K loop, for a free issue slot in the epilogue: a lone wavefront issues
+// a vector instruction only every 6-8 clocks), and the weight tile is brought into the CU once per 256 rows: 52 KB per K
+// step through the vector-memory path, which at 48-64 bytes per clock and CU is the narrowest pipe of the K loop.
 //
 // LDS: a ring of three stages (X slab 32 KB, kept values 16 KB, index words 4/2 KB).  K steps are numbered g = 0, 1, ...
 // over the workgroup's whole sequence of tiles; step g lives in stage g % 3.  One workgroup barrier per K step, in front
