@@ -79,6 +79,36 @@ __device__ __forceinline__ void quantize_codes(const float (&x)[N], float s, flo
 #pragma unroll
   for (int j = 0; j < N; ++j) q[j] = finish_code(x[j], t[j]);
 }
+// The codes of 8 values as bytes, packed into two words (value 0 in the low byte of `lo`): the same codes as
+// quantize_codes, with less arithmetic in the common case, for epilogues that are bound by the vector ALU.
+//   * band test |fract(t) - 0.5| < 2^-14 instead of |t| 2^-21: for |t| < 128 it is the wider of the two, and for
+//     |t| >= 128 the quotient exceeds 127.5 whenever t does, so both clamp to the same code; written as "not >=", it
+//     also sends every NaN to the exact path;
+//   * otherwise clamp first (for finite t, rint and the clamp to whole numbers commute), then add 1.5 * 2^23: the sum is
+//     rounded to a whole number half-to-even by the addition itself, and the low byte of its bit pattern is the
+//     two's-complement code.
+__device__ __forceinline__ void quantize_bytes8(const float (&x)[8], float s, float r, unsigned& lo, unsigned& hi) {
+  float t[8];
+  bool exact_path = false;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    t[j] = x[j] * r;
+    exact_path |= !(fabsf(__builtin_amdgcn_fractf(t[j]) - 0.5f) >= 0x1p-14f);
+  }
+  unsigned b[8];
+  if (__builtin_amdgcn_ballot_w64(exact_path) != 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[j] = (unsigned)finish_code(x[j], __fdiv_rn(x[j], s));
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[j] = __float_as_uint(__builtin_amdgcn_fmed3f(t[j], -127.0f, 127.0f) + 12582912.0f);
+  }
+  // v_perm_b32: selector bytes 0..3 take bytes of the second operand, 4..7 of the first, 0x0c gives zero
+  const unsigned p01 = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), p23 = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+  const unsigned p45 = __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), p67 = __builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u);
+  lo = p01 | (p23 << 16);
+  hi = p45 | (p67 << 16);
+}
 __device__ __forceinline__ int quantize_code(float x, float s, float r) {
   const float xs[1] = {x};
   int q[1];

@@ -6,6 +6,7 @@ namespace gpusq {
 
 typedef int ep_v4i __attribute__((ext_vector_type(4)));
 typedef int ep_v2i __attribute__((ext_vector_type(2)));
+typedef unsigned ep_v2u __attribute__((ext_vector_type(2)));
 typedef _Float16 ep_v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 ep_v4h __attribute__((ext_vector_type(4)));
 

@@ -120,8 +120,9 @@ constexpr int kCopies = 7;  // copy instructions per wavefront and K step: 4 X b
 constexpr int kWaitVm0 = 0x0070;    // vmcnt(0)
 constexpr int kWaitVm7 = 0x0077;    // vmcnt(kCopies)
 constexpr int kWaitVm14 = 0x007E;   // vmcnt(2 * kCopies)
+constexpr int kWaitVm15 = 0x007F;   // vmcnt(kCopies + 8)
 constexpr int kWaitVm23 = 0x4077;   // vmcnt(kCopies + 16)
-static_assert(kCopies == 7, "the wait immediates encode 7, 14 and 7 + 16");
+static_assert(kCopies == 7, "the wait immediates encode 7, 14, 7 + 8 and 7 + 16");
 static_assert(kBarrierFrag + 3 == kTileTN && (kTileTN - kBarrierFrag) * kTileTM >= 2 * kTileTM + 1 &&
                   (kTileTN - kBarrierFrag) * kTileTM >= kCopies, "slot plan of tile_step");
 
@@ -302,7 +303,7 @@ __device__ __forceinline__ void load_step_head(v8i (&b)[kTileTM], v4i (&av)[4], 
 // of the next step's head from `next` into `bn`, `av`, `ai` and the wavefront's kCopies copy requests.  So every other
 // instruction is issued in the shadow of a matrix instruction.
 // wait_mode (wavefront-uniform): what may stay outstanding at the barrier: 0 = nothing, 1 = one step of copies,
-// 2 = one step of copies and 16 output stores.
+// 2 = one step of copies and 16 output stores, 3 = one step of copies and 8 output stores.
 // last (wavefront-uniform): the last step of a tile reads nothing ahead (the head of the next tile's first step is read
 // after the epilogue, which keeps those registers free for the epilogue's arithmetic).
 // behind_barrier(): called once, right behind the barrier and before the step's copy requests.
@@ -326,6 +327,8 @@ __device__ __forceinline__ void tile_step(bool last, int wait_mode, const uint8_
           __builtin_amdgcn_s_waitcnt(kWaitVm0);
         else if (wait_mode == 1)
           __builtin_amdgcn_s_waitcnt(kWaitVm7);
+        else if (wait_mode == 3)
+          __builtin_amdgcn_s_waitcnt(kWaitVm15);
         else
           __builtin_amdgcn_s_waitcnt(kWaitVm23);
         __builtin_amdgcn_s_barrier();
@@ -422,83 +425,157 @@ __device__ __forceinline__ void batch_epilogue(const GemmArgs& a, const typename
   }
 }
 
-// fp16 epilogue that writes whole 128-byte lines.  The accumulator layout gives a lane (c = lane % 16, q = lane / 16) 8
-// consecutive channels of activation row c of a slab, so a plain 16-byte store per lane covers 16 rows x 64 bytes: half
-// lines, which the memory pipeline of a CU accepts at less than a third of the rate of whole lines (measured: 23-30 B/ns
-// per CU against 100 B/ns).  Here two batches of 32 channels (64 consecutive channels = 128 bytes of a row) are paired
-// and lanes c and c+8 of a 16-lane row swap one half through DPP (row_ror:8), after which the first store of the pair
-// covers rows 0..7 of the slab, the second rows 8..15, each lane writing 16 bytes of a whole line:
-//   lanes c < 8 : store 1 = own row, first half (own)        store 2 = row c+8, first half (from lane c+8)
-//   lanes c >= 8: store 1 = row c-8, second half (from c-8)  store 2 = own row, second half (own)
-// Needs N % 8 == 0 (a lane's 8 channels are inside or outside together).
+// Epilogue that writes whole 128-byte lines.  The accumulator layout gives a lane (c = lane % 16, q = lane / 16) 8
+// consecutive channels of activation row c of a slab, so a plain store per lane covers 16 rows x 64 bytes (fp16; 32 for
+// int8 output): partial lines, which the memory pipeline of a CU accepts at less than a third of the rate of whole
+// lines (measured: 23-30 B/ns per CU against 100 B/ns).  Here every lane ends up with two 16-byte pieces, `first` and
+// `second`, that lie in the same line of its row, lanes c and c+8 of a 16-lane row swap one of them through DPP
+// (row_ror:8), and the first store of the pair covers rows 0..7 of the slab, the second rows 8..15, each lane writing 16
+// bytes of a whole line:
+//   lanes c < 8 : store 1 = own row, `first` (own)              store 2 = row c+8, `first` (from lane c+8)
+//   lanes c >= 8: store 1 = row c-8, `second` (from lane c-8)   store 2 = own row, `second` (own)
+// The two pieces and the line they share:
+//   fp16  (N % 8 == 0):  two batches of 32 channels are paired (64 consecutive channels = 128 bytes of a row); the
+//                        lane's 8 channels of the first batch and of the second.
+//   int32 (N % 4 == 0):  one batch of 32 channels is a line; the lane's two accumulator fragments (4 channels each).
+//   int8  (N % 16 == 0): the wavefront's 128 channels are a line, of which a lane holds 8 bytes in each of the 4
+//                        batches.  Lanes q = 2j and 2j+1 exchange halves with v_permlane16_swap (the odd 16-lane rows of
+//                        one register against the even rows of another): the even one then holds 16 consecutive channels
+//                        of batches 0 and 1, the odd one those of batches 2 and 3.
 // CHECKED = false: the wavefront's 128 channels x 64 rows all lie inside Y (the caller has checked), so the stores carry
 // no per-lane tests and no branches.
-template <bool IS_I8, int GELU, bool CHECKED>
+// `y` is wavefront-uniform (it stays in scalar registers) and `off` the lane's 32-bit byte offset: the stores then take the
+// scalar-base addressing form and no lane holds a 64-bit address.
+typedef __attribute__((address_space(1))) uint8_t global_u8;
+typedef __attribute__((address_space(1))) ep_v4i global_v4i;
+__device__ __forceinline__ global_u8* uniform_ptr(const void* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(v >> 32)), lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+  return (global_u8*)(((uint64_t)hi << 32) | lo);  // (the builtin returns a signed int: widened directly it would sign-extend)
+}
+__device__ __forceinline__ void store_line_pair(const ep_v4i& first, const ep_v4i& second, global_u8* y, uint32_t off, int64_t half_bytes,
+                                                bool ok1, bool ok2) {
+  ep_v4i s1, s2;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    // row_ror:8 = 0x128; bank_mask 0xC: lanes 8..15 of a row take the rotated source, 0x3: lanes 0..7
+    s1[d] = __builtin_amdgcn_update_dpp(first[d], second[d], 0x128, 0xF, 0xC, false);
+    s2[d] = __builtin_amdgcn_update_dpp(second[d], first[d], 0x128, 0xF, 0x3, false);
+  }
+  // (the empty asm keeps the widening of `off` next to the stores: hoisted out of the tile loop, the widened offset
+  // would occupy a register pair and the stores would take 64-bit vector addresses)
+  asm volatile("" : "+v"(off));
+  if (ok1) __builtin_nontemporal_store(s1, (global_v4i*)(y + off));
+  if (ok2) __builtin_nontemporal_store(s2, (global_v4i*)(y + half_bytes + off));
+}
+
+template <bool IS_I8, int GELU, int OUT, bool CHECKED>
 __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM],
-                                              const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active) {
+                                              const float* p, float s_a, float so, float rso, int n_wave, int64_t m_wave, int lane,
+                                              int tm_active) {
+  constexpr int OB = dtype_bytes(OUT);
   const int c = lane & 15, q = lane >> 4, up = c >> 3;
-  // byte address of this lane's 16 bytes in the first store of slab 0, pair 0
-  uint8_t* y0 = (uint8_t*)a.Y + ((m_wave + (c & 7)) * a.N + n_wave) * 2 + up * 64 + q * 16;
-  const int64_t slab_bytes = (int64_t)16 * a.N * 2, half_bytes = (int64_t)8 * a.N * 2;
+  const int64_t slab_bytes = (int64_t)16 * a.N * OB, half_bytes = (int64_t)8 * a.N * OB;
+  global_u8* ywave = uniform_ptr((uint8_t*)a.Y + (m_wave * a.N + n_wave) * OB);  // the wavefront's first row and channel
+  const uint32_t row_off = (uint32_t)(c & 7) * (uint32_t)a.N * OB;             // row c % 8 (the host keeps 16 rows of Y below 2 GiB)
+  // values of the lane's 8 channels of batch g (32 channels) in slab mt, dequantised / biased / activated, in fp32
+  auto batch_values = [&](int g, int mt, float (&v)[8]) {
+    const int nl = (g >> 1) * kRowBlock + (g & 1) * 32 + q * 8;
+    float c8[8], b8[8];
 #pragma unroll
-  for (int gp = 0; gp < kTileTN / 4; ++gp) {
-    const int nl = gp * kRowBlock + q * 8;  // first channel (relative to n_wave) of this lane's accumulators in the pair's first batch
-    float c8[2][8], b8[2][8];
+    for (int j = 0; j < 8; j += 4) {
+      const float4 bb = *(const float4*)(p + 128 + nl + j);
+      b8[j] = bb.x; b8[j + 1] = bb.y; b8[j + 2] = bb.z; b8[j + 3] = bb.w;
+      if constexpr (IS_I8) {
+        const float4 cc = *(const float4*)(p + nl + j);
+        c8[j] = s_a * cc.x; c8[j + 1] = s_a * cc.y; c8[j + 2] = s_a * cc.z; c8[j + 3] = s_a * cc.w;
+      }
+    }
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int j = 0; j < 8; j += 4) {
-        const float4 bb = *(const float4*)(p + 128 + nl + 32 * h + j);
-        b8[h][j] = bb.x; b8[h][j + 1] = bb.y; b8[h][j + 2] = bb.z; b8[h][j + 3] = bb.w;
-        if constexpr (IS_I8) {
-          const float4 cc = *(const float4*)(p + nl + 32 * h + j);
-          c8[h][j] = s_a * cc.x; c8[h][j + 1] = s_a * cc.y; c8[h][j + 2] = s_a * cc.z; c8[h][j + 3] = s_a * cc.w;
-        } else {
-          c8[h][j] = c8[h][j + 1] = c8[h][j + 2] = c8[h][j + 3] = 1.0f;
+      for (int r = 0; r < 4; ++r) {
+        const int j = 4 * t + r;
+        if constexpr (IS_I8)
+          v[j] = (float)acc[2 * g + t][mt][r];
+        else
+          v[j] = acc[2 * g + t][mt][r] + b8[j];
+      }
+    if constexpr (IS_I8) {
+      pin8(v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(v[j], c8[j], b8[j]);
+    }
+    if constexpr (GELU != 0) gelu_f32_x8(v);
+  };
+  if constexpr (OUT == GPUSQ_F16) {
+#pragma unroll
+    for (int gp = 0; gp < kTileTN / 4; ++gp) {
+      // the channels this lane stores: those of its own half of the line
+      const bool n_ok = n_wave + gp * kRowBlock + up * 32 + q * 8 < a.N;
+#pragma unroll
+      for (int mt = 0; mt < kTileTM; ++mt) {
+        if (!CHECKED || mt < tm_active) {
+          ep_v4i H[2];
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            float v[8];
+            batch_values(2 * gp + h, mt, v);
+            pin8(v);  // the fp32 result is rounded to fp32 before it is rounded to fp16 (no fused fma-and-convert)
+            ep_v8h hh;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) hh[j] = (_Float16)v[j];
+            H[h] = __builtin_bit_cast(ep_v4i, hh);
+          }
+          const int64_t row = m_wave + mt * 16 + (c & 7);
+          store_line_pair(H[0], H[1], ywave + mt * slab_bytes, row_off + gp * (kRowBlock * 2) + up * 64 + q * 16, half_bytes,
+                          !CHECKED || (n_ok && row < a.M), !CHECKED || (n_ok && row + 8 < a.M));
         }
       }
-    // the channels this lane stores: those of its own half of the line
-    const bool n_ok = n_wave + gp * kRowBlock + up * 32 + q * 8 < a.N;
+    }
+  } else if constexpr (OUT == GPUSQ_I32) {
+#pragma unroll
+    for (int g = 0; g < kTileTN / 2; ++g) {
+      const int nb = (g >> 1) * kRowBlock + (g & 1) * 32 + q * 8 + up * 4;  // first of the 4 channels this lane stores
+      const bool n_ok = n_wave + nb < a.N;
+#pragma unroll
+      for (int mt = 0; mt < kTileTM; ++mt) {
+        if (!CHECKED || mt < tm_active) {
+          const int64_t row = m_wave + mt * 16 + (c & 7);
+          store_line_pair(acc[2 * g][mt], acc[2 * g + 1][mt], ywave + mt * slab_bytes, row_off + nb * 4, half_bytes,
+                          !CHECKED || (n_ok && row < a.M), !CHECKED || (n_ok && row + 8 < a.M));
+        }
+      }
+    }
+  } else {
+    // so, rso: the output scale and its reciprocal (the same code rule as the quantiser of the activations)
+    // 16-byte piece (of the 8 in a line) that this lane stores: lanes c < 8 their `first`, lanes c >= 8 the `second`
+    // of lane c - 8; even q hold batches 0 (first) and 1 (second), odd q batches 2 and 3, channels 16 * (q / 2) ...
+    const int piece = 4 * (q & 1) + 2 * up + (q >> 1);
+    const bool n_ok = n_wave + piece * 16 < a.N;
 #pragma unroll
     for (int mt = 0; mt < kTileTM; ++mt) {
       if (!CHECKED || mt < tm_active) {
-        ep_v4i H[2];
+        unsigned d[4][2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int g = 0; g < 4; ++g) {
           float v[8];
-#pragma unroll
-          for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int j = 4 * t + r;
-              if constexpr (IS_I8)
-                v[j] = (float)acc[4 * gp + 2 * h + t][mt][r];
-              else
-                v[j] = acc[4 * gp + 2 * h + t][mt][r] + b8[h][j];
-            }
-          if constexpr (IS_I8) {
-            pin8(v);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(v[j], c8[h][j], b8[h][j]);
-          }
-          if constexpr (GELU != 0) gelu_f32_x8(v);
-          pin8(v);  // the fp32 result is rounded to fp32 before it is rounded to fp16 (no fused fma-and-convert)
-          ep_v8h hh;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) hh[j] = (_Float16)v[j];
-          H[h] = __builtin_bit_cast(ep_v4i, hh);
+          batch_values(g, mt, v);
+          quantize_bytes8(v, so, rso, d[g][0], d[g][1]);
         }
-        ep_v4i s1, s2;
+        ep_v4i first, second;
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          // row_ror:8 = 0x128; bank_mask 0xC: lanes 8..15 of a row take the rotated source, 0x3: lanes 0..7
-          s1[d] = __builtin_amdgcn_update_dpp(H[0][d], H[1][d], 0x128, 0xF, 0xC, false);
-          s2[d] = __builtin_amdgcn_update_dpp(H[1][d], H[0][d], 0x128, 0xF, 0x3, false);
+        for (int w = 0; w < 2; ++w) {
+          // result 0: even q keep their own register, odd q receive the second register of lane q - 1;
+          // result 1: even q receive the first register of lane q + 1, odd q keep their own second register
+          const ep_v2u x = __builtin_amdgcn_permlane16_swap(d[0][w], d[2][w], false, false);
+          const ep_v2u y = __builtin_amdgcn_permlane16_swap(d[1][w], d[3][w], false, false);
+          first[w] = (int)x[0]; first[2 + w] = (int)x[1];
+          second[w] = (int)y[0]; second[2 + w] = (int)y[1];
         }
         const int64_t row = m_wave + mt * 16 + (c & 7);
-        uint8_t* y = y0 + mt * slab_bytes + gp * (kRowBlock * 2);
-        if (!CHECKED || (n_ok && row < a.M)) __builtin_nontemporal_store(s1, (ep_v4i*)y);
-        if (!CHECKED || (n_ok && row + 8 < a.M)) __builtin_nontemporal_store(s2, (ep_v4i*)(y + half_bytes));
+        store_line_pair(first, second, ywave + mt * slab_bytes, row_off + piece * 16, half_bytes, !CHECKED || (n_ok && row < a.M),
+                        !CHECKED || (n_ok && row + 8 < a.M));
       }
     }
   }
@@ -534,6 +611,7 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
   };
   const bool has_bias = !RAW && (a.epilogue & GPUSQ_EPI_BIAS) != 0;
   const float s_a = (IS_I8 && !RAW) ? a.act_scale[0] : 1.0f;
+  const float s_out = OUT == GPUSQ_I8 ? a.out_scale[0] : 1.0f, r_out = scale_reciprocal(s_out);  // read once: a load in the epilogue would wait for the copies in flight
   if (!has_bias && wm == 0) {  // the bias halves stay zero for the whole launch (visible after the first barrier)
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
@@ -640,7 +718,7 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
       // to memory while the K loop goes on.  The third barrier of a tile then waits for copies that were requested after
       // those stores.  (Only the common count, the 16 stores of a wavefront whose 128 x 64 outputs all lie inside Y, is
       // exploited; any other count waits for the stores as well, which is only stricter.)
-      const int wait_mode = g + 2 >= total_steps ? 0 : (ks < 2 ? (stores_pending < 0 ? 0 : (stores_pending >= 16 ? 2 : 1)) : 1);
+      const int wait_mode = g + 2 >= total_steps ? 0 : (ks < 2 ? (stores_pending < 0 ? 0 : (stores_pending >= 16 ? 2 : (stores_pending >= 8 ? 3 : 1))) : 1);
       tile_step<IS_I8>(ks + 1 == ksteps, wait_mode, ring + (size_t)slot * STAGE, ring + (size_t)nslot * STAGE, bo, acc, b, bn, av, ai,
                        a_off, i_off, requested, ring_lds + (uint32_t)slot * STAGE, pf_x, pf_w, pf_xoff, wave, loff, [&]() {
                          // The next tile's constants go into the other constants array, which was last read in the
@@ -664,16 +742,18 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
     // The epilogue, and the number of store instructions this wavefront issues in it (with N % 8 != 0 that number
     // depends on the lanes: then the next tile waits for everything, because a count that is too high would let its
     // copies go unwaited).
-    if (OUT == GPUSQ_F16 && (a.N & 7) == 0) {
+    const bool lines = OUT == GPUSQ_F16 ? (a.N & 7) == 0 : (OUT == GPUSQ_I8 ? (a.N & 15) == 0 : true);
+    if (lines) {
       if (t.tm == kTileTM && rows >= kTileTM * 16 && chans >= kTileTN * 16)
-        line_epilogue<IS_I8, GELU, false>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, kTileTM);
+        line_epilogue<IS_I8, GELU, OUT, false>(a, acc, prm[item & 1][wn], s_a, s_out, r_out, n_wave, m_wave, lane, kTileTM);
       else
-        line_epilogue<IS_I8, GELU, true>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
-      // per pair of batches (64 channels) with a channel inside N: one store per slab with a row inside M among its
-      // first 8 rows and one for its last 8 rows
+        line_epilogue<IS_I8, GELU, OUT, true>(a, acc, prm[item & 1][wn], s_a, s_out, r_out, n_wave, m_wave, lane, t.tm);
+      // per line of the wavefront's 128 channels with a channel inside N (fp16: 64 channels, int32: 32, int8: all 128):
+      // one store per slab with a row inside M among its first 8 rows and one for its last 8 rows
       int n = 0;
       for (int mt = 0; mt < t.tm; ++mt) n += (16 * mt < rows) + (16 * mt + 8 < rows);
-      stores_pending = n * (chans <= 0 ? 0 : (chans > kRowBlock ? 2 : 1));
+      const int per_line = OUT == GPUSQ_F16 ? kRowBlock : (OUT == GPUSQ_I8 ? 128 : 32);
+      stores_pending = n * (chans <= 0 ? 0 : (chans >= 128 ? 128 / per_line : (chans + per_line - 1) / per_line));
     } else {
       batch_epilogue<IS_I8, GELU, OUT>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
       // one (two for 2 x 16 bytes of int32) per batch of 32 channels x 16 rows with a row inside M and a channel inside N
@@ -916,6 +996,7 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const TilePlan plan = make_plan(a.M, a.N, resident, ksteps, gelu);
   const dim3 grid((unsigned)grid_for(plan, resident));
   if ((ceil_div(plan.total, grid.x) + 2) * ksteps >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
+  if ((int64_t)a.N * 16 * 4 >= ((int64_t)1 << 31)) return GPUSQ_ERR_UNSUPPORTED;  // 32-bit lane offsets inside 16 rows of Y
   if (a.patch_P != 0) {
     spgemm_tile_kernel<IS_I8, 0, GPUSQ_F16, true><<<grid, 512, 0, s>>>(a, plan);
     return check_launch();
