@@ -63,9 +63,11 @@ class SparseLinear:
         G._check(L.gpusq_pack(_p(self.values), _p(self.meta), _p(self.packed), dt, N, K, s), "gpusq_pack")
 
     # ---- activation side + GEMM (a4, a5, a6) --------------------------------------------------------------------
-    def quantize_activations(self, X):
-        G._check(G.lib().gpusq_quantize_int8(_p(X), G._TORCH_DT[X.dtype], _p(self.Xq), _p(self.act_scale), G.PER_TENSOR, 0,
-                                             self.M, self.K, _p(self.workspace), G._stream()), "gpusq_quantize_int8")
+    def quantize_activations(self, X, static=False):
+        """static=True: act_scale already holds a calibrated scale and is used as it is (one launch, no range pass)"""
+        G._check(G.lib().gpusq_quantize_int8(_p(X), G._TORCH_DT[X.dtype], _p(self.Xq), _p(self.act_scale), G.PER_TENSOR,
+                                             1 if static else 0, self.M, self.K, _p(self.workspace), G._stream()),
+                 "gpusq_quantize_int8")
 
     def gemm(self, X, bias, out_scale=None):
         L, s = G.lib(), G._stream()
@@ -159,3 +161,61 @@ class SparsePatchEmbed:
         if self.precision == "int8":
             self.linear.Xq = self.X
         return self.linear.gemm(self.X, bias)
+
+
+class EncoderBlockLinears:
+    """The four linear layers of one encoder block (qkv, proj, fc1, fc2) on the INT8 path with static, calibrated
+    activation scales, the deployment form with quantise / dequantise nodes around every linear layer: the
+    re-quantisation of a layer's output with the next layer's input scale is fused into its epilogue (qkv -> int8,
+    fc1 -> GELU -> int8, which fc2 reads directly), so one block is six launches of the library:
+        quantise x, qkv, [attention], proj, [residual + norm], quantise h, fc1 (GELU), fc2.
+    Attention and the normalisation are not part of the library: `attention(qkv_int8 [M,3D], out_int8 [M,D])` and
+    `norm(proj_fp16 [M,D]) -> fp16 [M,D]` are the caller's (stubs in the tests and the report).  capture() records the
+    whole sequence into a HIP graph, which removes the launch gaps that dominate at batch 1.
+
+    scales: dict of 1-element fp32 device tensors: x (block input), qkv (qkv output), attn (attention output),
+    h (fc1 input), g (GELU output = fc2 input)."""
+
+    def __init__(self, M, D, hidden, scales, device="cuda"):
+        self.M, self.D, self.hidden = M, D, hidden
+        self.qkv = SparseLinear(M, D, 3 * D, "int8", out_dtype=torch.int8, device=device)
+        self.proj = SparseLinear(M, D, D, "int8", out_dtype=torch.float16, device=device)
+        self.fc1 = SparseLinear(M, D, hidden, "int8", gelu=True, out_dtype=torch.int8, device=device)
+        self.fc2 = SparseLinear(M, hidden, D, "int8", out_dtype=torch.float16, device=device)
+        self.scales = scales
+        self.qkv.act_scale = scales["x"]
+        self.proj.act_scale = scales["attn"]
+        self.fc1.act_scale = scales["h"]
+        self.fc2.act_scale = scales["g"]
+        self.fc2.Xq = self.fc1.Y  # fc2 reads the codes fc1's epilogue wrote: no pass in between
+        self.graph = None
+
+    def prepare_weights(self, Wqkv, Wproj, Wfc1, Wfc2):
+        for lin, W in ((self.qkv, Wqkv), (self.proj, Wproj), (self.fc1, Wfc1), (self.fc2, Wfc2)):
+            lin.prepare_weights(W)
+
+    def forward(self, x, biases, attention, norm=None):
+        """x fp16 [M,D]; biases: (b_qkv, b_proj, b_fc1, b_fc2); returns fc2's fp16 output [M,D] (a buffer of this object)"""
+        self.qkv.quantize_activations(x, static=True)
+        self.qkv.gemm(None, biases[0], self.scales["qkv"])
+        attention(self.qkv.Y, self.proj.Xq)
+        h = self.proj.gemm(None, biases[1])
+        if norm is not None:
+            h = norm(h)
+        self.fc1.quantize_activations(h, static=True)
+        self.fc1.gemm(None, biases[2], self.scales["g"])
+        return self.fc2.gemm(None, biases[3])
+
+    def capture(self, x, biases, attention, norm=None):
+        """Records forward() on these buffers into a HIP graph (after one eager run that loads every kernel); replay()
+        then reruns it on whatever x and the biases hold at that time."""
+        self.forward(x, biases, attention, norm)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.forward(x, biases, attention, norm)
+        return self.graph
+
+    def replay(self):
+        self.graph.replay()
+        return self.fc2.Y

@@ -11,7 +11,7 @@ import torch
 
 from . import gpusq as G
 from . import synth
-from .pipeline import SparseLinear, SparsePatchEmbed
+from .pipeline import EncoderBlockLinears, SparseLinear, SparsePatchEmbed
 
 SPARSE_PEAK = {"int8": 10070.0, "fp16": 5030.0}  # nominal dense-equivalent T(FL)OP/s of the gfx950 sparse matrix instructions
 INFINITY_CACHE = 256 << 20
@@ -73,12 +73,13 @@ def main():
     ap.add_argument("--out", default="")
     ap.add_argument("--iters", type=int, default=30)
     ap.add_argument("--configs", default="c0,c1,c2,c3,c4_vitl,c4_vith")
+    ap.add_argument("--only-blocks", action="store_true", help="skip the per-layer and patch-embedding tables")
     a = ap.parse_args()
     lines = ["| config | layer | M | K | N | GELU | path | sparse cold us | sparse hot us | dense cold us | dense hot us | speedup (cold) | "
              "TOPS dense-equiv. (cold) | of sparse peak | of 8 TB/s (algorithmic bytes) |",
              "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     totals = {}
-    for cfg_name in a.configs.split(","):
+    for cfg_name in ([] if a.only_blocks else a.configs.split(",")):
         cfg = synth.CONFIGS[cfg_name]
         M = cfg["M"]
         for name, K, N, gelu, _dist in cfg["layers"]:
@@ -100,8 +101,8 @@ def main():
               "hot buffers):", "", "| model | images | P | M | K | N | path | quantise us | im2col us | sparse GEMM us | whole layer us | whole layer, patches "
               "gathered by the GEMM (P = 16) us |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
     dev = torch.device("cuda")
-    for model, B, HW, P, D in [("ViT-B/16, batch 64", 64, 224, 16, 768), ("ViT-L/16, batch 256", 256, 224, 16, 1024),
-                               ("ViT-H/14, batch 256", 256, 224, 14, 1280)]:
+    for model, B, HW, P, D in [] if a.only_blocks else [("ViT-B/16, batch 64", 64, 224, 16, 768), ("ViT-L/16, batch 256", 256, 224, 16, 1024),
+                                                      ("ViT-H/14, batch 256", 256, 224, 14, 1280)]:
         img = torch.randn(B, 3, HW, HW, device=dev).half()
         Wc = torch.randn(D, 3, P, P, device=dev) * 0.02
         bias = torch.randn(D, device=dev) * 0.01
@@ -125,6 +126,39 @@ def main():
             print(lines[-1], flush=True)
             del pe
             torch.cuda.empty_cache()
+    lines += ["", "Linear layers of one encoder block on the INT8 path (qkv, proj, fc1 + GELU, fc2; attention and normalisation left out: "
+              "proj and fc1 read buffers that nothing refreshes), us per block, hot buffers.  Unchained: every layer writes fp16 and the next "
+              "one quantises it with a dynamic per-tensor scale (12 launches).  Chained: static scales, the re-quantisation fused into the "
+              "producer's epilogue (6 launches), launched one by one or replayed as one HIP graph:", "",
+              "| model | M | D | hidden | unchained us | chained us | chained, HIP graph us |", "|---|---|---|---|---|---|---|"]
+    for model, M, D, hidden in [("DeiT-Tiny, batch 1", 197, 192, 768), ("DeiT-Small, batch 1", 197, 384, 1536), ("ViT-B/16, batch 1", 197, 768, 3072),
+                                ("ViT-B/16, batch 8", 1576, 768, 3072), ("ViT-B/16, batch 64", 12608, 768, 3072)]:
+        shapes = [(3 * D, D), (D, D), (hidden, D), (D, hidden)]
+        Ws = [torch.randn(n, k, device=dev) * 0.02 for n, k in shapes]
+        bs = [torch.randn(n, device=dev) * 0.01 for n, k in shapes]
+        x = torch.randn(M, D, device=dev).half()
+        sc = {k: torch.full((1,), v, dtype=torch.float32, device=dev) for k, v in dict(x=0.03, qkv=0.01, attn=0.01, h=0.01, g=0.01).items()}
+        blk = EncoderBlockLinears(M, D, hidden, sc)
+        blk.prepare_weights(*Ws)
+        nothing = lambda q, out: None
+        t_chain = _time([lambda: blk.forward(x, bs, nothing)], a.iters)
+        blk.capture(x, bs, nothing)
+        t_graph = _time([blk.replay], a.iters)
+        lins = [SparseLinear(M, k, n, "int8", gelu=(i == 2)) for i, (n, k) in enumerate(shapes)]
+        for lin, W in zip(lins, Ws):
+            lin.prepare_weights(W)
+        xin = [x, torch.randn(M, D, device=dev).half(), torch.randn(M, D, device=dev).half(), None]
+
+        def unchained():
+            lins[0].forward(xin[0], bs[0])
+            lins[1].forward(xin[1], bs[1])
+            h = lins[2].forward(xin[2], bs[2])
+            lins[3].forward(h, bs[3])
+        t_un = _time([unchained], a.iters)
+        lines.append("| %s | %d | %d | %d | %.1f | %.1f | %.1f |" % (model, M, D, hidden, t_un, t_chain, t_graph))
+        print(lines[-1], flush=True)
+        del blk, lins
+        torch.cuda.empty_cache()
     text = "\n".join(lines) + "\n"
     print(text)
     if a.out:

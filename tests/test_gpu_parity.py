@@ -602,3 +602,82 @@ def test_fused_patch_embedding_matches_the_convolution_oracle(g, B, C, H, W, D, 
     small = dev(rng.integers(-5, 5, (1, C, 32, 32), dtype=np.int8))
     with pytest.raises(g.GpusqError):
         g.patch_embed16(small, packed, D, act_scale=s_a_g, w_scale=s_w_g)
+
+
+# ------------------------------------------------------------------------------------------------ chained INT8 block
+def _oracle_weights(W):
+    P, _ = oracle.prune_2to4(W)
+    Wq, s_w = oracle.quantize_rows_int8(P)
+    vals, meta, viol = oracle.compress(Wq)
+    assert viol == 0
+    return Wq, s_w, vals, meta
+
+
+@pytest.mark.parametrize("M,D,hidden,seed", [(197, 192, 768, 51), (1576, 384, 1536, 52)])
+def test_encoder_block_chain_and_its_graph(g, M, D, hidden, seed):
+    """qkv -> [attention stub: V passes through] -> proj -> quantise -> fc1 (GELU, int8 out) -> fc2 with static scales,
+    against the same chain composed from the oracle's layer functions.  Everything up to fc1's input has no GELU and is
+    bit-exact; the GELU codes may differ by one in rare near-ties (the kernel's GELU is a fit, the oracle's is erf), and
+    the final output is then bounded by what those flipped codes can contribute.  Then the whole sequence as a HIP graph:
+    every replay equals the eager run on the same inputs."""
+    from paper_2305_10727_amd.pipeline import EncoderBlockLinears
+    X = synth.activations(M, D, "normal_clip4", seed=seed, ids=(20,)).astype(np.float16)
+    shapes = [(3 * D, D), (D, D), (hidden, D), (D, hidden)]
+    Ws = [synth.weights(n, k, seed=seed, ids=(21 + i,), sigma=0.05) for i, (n, k) in enumerate(shapes)]
+    bs = [synth.bias(n, seed=seed, ids=(25 + i,)) for i, (n, k) in enumerate(shapes)]
+    ow = [_oracle_weights(W) for W in Ws]
+    f32 = np.float32
+
+    def amax_scale(ref):
+        return f32(np.abs(ref).max() / 127.0)
+
+    # ---- the oracle's chain; every static scale is calibrated on its own (fp64) intermediate
+    s_x = amax_scale(X.astype(np.float64))
+    Xq, _ = oracle.quantize_tensor_int8(X.astype(f32), scale=float(s_x))
+    acc = oracle.spgemm_int8(Xq, ow[0][2], ow[0][3])
+    s_qkv = amax_scale(oracle.epilogue_int8_f64(acc, float(s_x), ow[0][1], bs[0])["ref"])
+    qkv = oracle.epilogue_int8_f32(acc, float(s_x), ow[0][1], bs[0], out_scale=float(s_qkv))["q8"]
+    attn = np.ascontiguousarray(qkv[:, 2 * D:])  # the stub: attention returns V; its scale is the qkv output's
+    acc = oracle.spgemm_int8(attn, ow[1][2], ow[1][3])
+    proj = oracle.epilogue_int8_f32(acc, float(s_qkv), ow[1][1], bs[1])["y16"]
+    s_h = amax_scale(proj.astype(np.float64))
+    hq, _ = oracle.quantize_tensor_int8(proj.astype(f32), scale=float(s_h))
+    acc = oracle.spgemm_int8(hq, ow[2][2], ow[2][3])
+    s_g = amax_scale(oracle.epilogue_int8_f64(acc, float(s_h), ow[2][1], bs[2], gelu=True)["ref"])
+    gq = oracle.epilogue_int8_f32(acc, float(s_h), ow[2][1], bs[2], gelu=True, out_scale=float(s_g))["q8"]
+    acc = oracle.spgemm_int8(gq, ow[3][2], ow[3][3])
+    y_ref = oracle.epilogue_int8_f64(acc, float(s_g), ow[3][1], bs[3])
+
+    # ---- the library's chain
+    sc = {k: dev(np.array([v], f32)) for k, v in dict(x=s_x, qkv=s_qkv, attn=s_qkv, h=s_h, g=s_g).items()}
+    blk = EncoderBlockLinears(M, D, hidden, sc)
+    blk.prepare_weights(*[dev(W) for W in Ws])
+    x, biases = dev(X), [dev(b) for b in bs]
+    stub = lambda q, out: out.copy_(q[:, 2 * D:])
+    y = host(blk.forward(x, biases, stub))
+    assert np.array_equal(host(blk.qkv.Xq), Xq) and np.array_equal(host(blk.qkv.Y), qkv)
+    assert np.array_equal(host(blk.proj.Y).view(np.uint16), proj.view(np.uint16)) and np.array_equal(host(blk.fc1.Xq), hq)
+    g_hip = host(blk.fc1.Y).astype(np.int32)
+    flips = g_hip != gq.astype(np.int32)
+    assert np.abs(g_hip - gq).max() <= 1 and flips.mean() < 5e-3
+    # a flipped code in row m moves y[m, n] by at most s_g * s_w[n] * max_k |Wq[n, k]|; plus one fp16 rounding
+    per_flip = float(s_g) * ow[3][1].astype(np.float64) * np.abs(ow[3][0].astype(np.int32)).max(axis=1)
+    bound = flips.sum(axis=1)[:, None] * per_flip[None, :] + np.abs(y_ref["ref"]) * 2.0 ** -10 + 1e-7
+    assert (np.abs(y.astype(np.float64) - y_ref["ref"]) <= bound).all()
+    rows_without_flips = ~flips.any(axis=1)
+    assert rows_without_flips.sum() > M // 2
+    assert ulp_diff_f16(y[rows_without_flips], y_ref["y16"][rows_without_flips]).max() <= 1
+
+    # ---- the same sequence recorded into a HIP graph: replays between eager work, each checked against the eager result
+    blk.capture(x, biases, stub)
+    for i in range(3):
+        X2 = synth.activations(M, D, "normal_clip4", seed=seed, ids=(30 + i,)).astype(np.float16)
+        x.copy_(dev(X2))
+        y_eager = blk.forward(x, biases, stub).clone()
+        codes_eager = blk.fc1.Y.clone()
+        blk.fc2.Y.zero_()
+        blk.fc1.Y.zero_()
+        torch.cuda.synchronize()
+        y_graph = blk.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager) and torch.equal(blk.fc1.Y, codes_eager)
