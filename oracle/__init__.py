@@ -115,6 +115,52 @@ def quantize_tensor_int8(X, scale=None):
     return Q, float(s[0])
 
 
+# ---------------------------------------------------------------- INT4 pair-wise 4:8
+def meta4_row_bytes(K):
+    return (K // 8 + 1) // 2
+
+
+def prune_4to8_pairs(W):
+    """W [N,K] float32, K % 8 == 0 -> (pruned W, mask bytes [N,K/8]); two of the four 2-wide sub-chunks of every chunk
+    of 8 are kept (highest |a| + |b|)."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    out = np.empty_like(W)
+    mask = np.empty((N, K // 8), np.uint8)
+    assert lib().oracle_prune_4to8_pairs_f32(_p(W), _p(out), _p(mask), _i64(N), _i64(K)) == 0
+    return out, mask
+
+
+def quantize_rows_int4(X, scale=None):
+    """per-row symmetric 4-bit codes (-7..7) in int8 containers, scale = amax / 7"""
+    X = _c(X, np.float32)
+    rows, cols = X.shape
+    Q = np.empty((rows, cols), np.int8)
+    given = scale is not None
+    s = _c(scale, np.float32).copy() if given else np.empty(rows, np.float32)
+    lib().oracle_quantize_rows_int4(_p(X), _p(Q), _p(s), int(given), _i64(rows), _i64(cols))
+    return Q, s
+
+
+def compress_int4_pairs(Wq):
+    """Wq [N,K] int8 holding 4-bit codes -> (values [N,K/4] uint8, meta [N,ceil(K/16)] uint8, violations)"""
+    Wq = _c(Wq, np.int8)
+    N, K = Wq.shape
+    values = np.empty((N, K // 4), np.uint8)
+    meta = np.empty((N, meta4_row_bytes(K)), np.uint8)
+    viol = ctypes.c_int32(0)
+    assert lib().oracle_compress_int4_pairs(_p(Wq), _p(values), _p(meta), ctypes.byref(viol), _i64(N), _i64(K)) == 0
+    return values, meta, int(viol.value)
+
+
+def decompress_int4_pairs(values, meta, K):
+    values, meta = _c(values, np.uint8), _c(meta, np.uint8)
+    N = values.shape[0]
+    W = np.empty((N, K), np.int8)
+    assert lib().oracle_decompress_int4_pairs(_p(values), _p(meta), _p(W), _i64(N), _i64(K)) == 0
+    return W
+
+
 # ---------------------------------------------------------------- a3 compress / decompress
 def compress(W):
     """W [N,K] float16 or int8 -> (values [N,K/2], meta [N,ceil(K/8)] uint8, violations)."""

@@ -12,7 +12,9 @@
  *     position inside its group of 4 [Sec. 3.1, Fig. 2 caption];
  *   - the sparse GEMM, which must give the same C as the dense GEMM on the zero-filled operand [Sec. 3.1];
  *   - symmetric INT8 quantisation with a scale factor [Sec. 2.2; Sec. 3.4], order "prune first, then quantise"
- *     [Sec. 3.1, last sentence of the storage-format paragraph].
+ *     [Sec. 3.1, last sentence of the storage-format paragraph];
+ *   - the pair-wise 4:8 pattern of INT4 operands and its storage (4 kept 4-bit values + two 2-bit indices per chunk
+ *     of 8) [Sec. 3.1, paragraph on the INT4 instruction], decoded to INT8 for the multiply-accumulate.
  * The paper does not state the pruning criterion, tie-break, rounding mode or scale granularity; the readings
  * taken here (magnitude top-2, ties to the lower index, scale = amax/127, round-half-even, per-output-channel
  * weights, per-tensor activations) are listed in the design notes of the repository.
@@ -24,7 +26,9 @@
  * exhaustive small-integer grids, compress/decompress round trip, the storage-saving closed forms printed in
  * Sec. 3.1 (43.75 % / 37.5 %), sparse GEMM == dense GEMM on masked weights, numpy int64 / float64 matmul,
  * quantiser error bound, GELU closed-form values; the patch-embedding convolution against the reshape-and-matmul
- * form computed by numpy and against the operation count printed in Sec. 3.3.  No function here is "parity unpinned".
+ * form computed by numpy and against the operation count printed in Sec. 3.3; the INT4 pair-wise format against a brute
+ * force over the 6 choices of two sub-chunks, the worked example of Sec. 3.1 (w, x, y, z), the 37.5 % saving printed there,
+ * round trips and numpy's quantiser formula.  No function here is "parity unpinned".
  *
  * Loops are the definitions written out; the only parallelism is an OpenMP "for" over independent output rows.
  */
@@ -291,6 +295,131 @@ int oracle_decompress_i8(const int8_t* values, const uint8_t* meta, int8_t* W, i
       nibble_positions(meta, mrb, n, g, &p0, &p1);
       W[n * K + 4 * g + p0] = values[n * (K / 2) + 2 * g];
       W[n * K + 4 * g + p1] = values[n * (K / 2) + 2 * g + 1];
+    }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ INT4: pair-wise 4:8 pattern and its storage */
+
+/* The pattern the paper describes for INT4 operands [Sec. 3.1, paragraph on the INT4 instruction]: a row is cut into
+ * chunks of 8 adjacent elements, a chunk into 4 sub-chunks of 2; every sub-chunk is all zero or all non-zero and
+ * exactly two of the four are kept.  The compressed row stores the 4 kept values of a chunk and two 2-bit indices
+ * with the positions of the two kept sub-chunks.
+ * The paper gives no selection rule; as for 2:4, magnitude decides: a sub-chunk's score is |a| + |b| (one fp32
+ * addition; an integer sum for integer operands), the two highest scores are kept, ties go to the lower index.
+ * Scores are compared as totally ordered keys (the sign-cleared bit pattern of the fp32 sum). */
+static void top2_pairs_f32(const float* w, int* p0, int* p1) {
+  uint32_t key[4];
+  for (int p = 0; p < 4; ++p) {
+    float sum = fabsf(w[2 * p]) + fabsf(w[2 * p + 1]);
+    uint32_t b;
+    memcpy(&b, &sum, 4);
+    key[p] = b & 0x7FFFFFFFu;
+  }
+  top2_of_4(key, p0, p1);
+}
+
+static void top2_pairs_i8(const int8_t* w, int* p0, int* p1) {
+  uint32_t key[4];
+  for (int p = 0; p < 4; ++p) key[p] = (uint32_t)(abs((int)w[2 * p]) + abs((int)w[2 * p + 1]));
+  top2_of_4(key, p0, p1);
+}
+
+/* W, Wout: [N][K] fp32 (may alias), K % 8 == 0.  mask (optional): N*K/8 bytes, bit p of byte c = sub-chunk p of chunk c kept. */
+int oracle_prune_4to8_pairs_f32(const float* W, float* Wout, uint8_t* mask, int64_t N, int64_t K) {
+  if (K % 8) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t c = 0; c < K / 8; ++c) {
+      float v[8];
+      for (int i = 0; i < 8; ++i) v[i] = W[n * K + 8 * c + i];
+      int p0, p1;
+      top2_pairs_f32(v, &p0, &p1);
+      for (int i = 0; i < 8; ++i) Wout[n * K + 8 * c + i] = (i / 2 == p0 || i / 2 == p1) ? v[i] : 0.0f;
+      if (mask) mask[n * (K / 8) + c] = (uint8_t)((1u << p0) | (1u << p1));
+    }
+  return 0;
+}
+
+/* symmetric INT4 codes in int8 containers: q = clamp(rint(x / s), -7, 7), s = max|row| / 7 (1 for an all-zero row)
+ * unless scale_is_input: the INT8 quantiser of Sec. 2.2 / 3.4 with the 4-bit range. */
+int oracle_quantize_rows_int4(const float* X, int8_t* Q, float* scale, int scale_is_input, int64_t rows, int64_t cols) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r) {
+    float s;
+    if (scale_is_input) {
+      s = scale[r];
+    } else {
+      float amax = 0.0f;
+      for (int64_t c = 0; c < cols; ++c) {
+        float a = fabsf(X[r * cols + c]);
+        if (a > amax) amax = a;
+      }
+      s = (amax == 0.0f) ? 1.0f : amax / 7.0f;
+      scale[r] = s;
+    }
+    for (int64_t c = 0; c < cols; ++c) {
+      float q = rintf(X[r * cols + c] / s);
+      if (q > 7.0f) q = 7.0f;
+      if (q < -7.0f) q = -7.0f;
+      if (q != q) q = 0.0f;
+      Q[r * cols + c] = (int8_t)q;
+    }
+  }
+  return 0;
+}
+
+/* W [N][K] int8 holding INT4 codes (-8..7), K % 8 == 0.
+ * values: [N][K/4] bytes; the 4 kept codes of chunk c, in ascending position, as two's-complement nibbles: kept code j
+ *         in byte 2c + j/2, low nibble for even j.
+ * meta:   [N][ceil(K/16)] bytes; chunk c in the low (c even) or high (c odd) nibble of byte c/2; in the nibble,
+ *         bits 0..1 = first kept sub-chunk, bits 2..3 = second (first < second).
+ * violations (optional): chunks in which a dropped element was non-zero or a code was outside -8..7. */
+static int64_t meta4_row_bytes(int64_t K) { return (K / 8 + 1) / 2; }
+
+int oracle_compress_int4_pairs(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N, int64_t K) {
+  if (K % 8) return -1;
+  int64_t mrb = meta4_row_bytes(K);
+  int32_t viol = 0;
+  memset(meta, 0, (size_t)(N * mrb));
+#pragma omp parallel for schedule(static) reduction(+ : viol)
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t c = 0; c < K / 8; ++c) {
+      const int8_t* w = W + n * K + 8 * c;
+      int p0, p1;
+      top2_pairs_i8(w, &p0, &p1);
+      const int8_t kept[4] = {w[2 * p0], w[2 * p0 + 1], w[2 * p1], w[2 * p1 + 1]};
+      for (int j = 0; j < 4; j += 2)
+        values[n * (K / 4) + 2 * c + j / 2] = (uint8_t)((kept[j] & 0xF) | ((kept[j + 1] & 0xF) << 4));
+      uint8_t nib = (uint8_t)(p0 | (p1 << 2));
+      meta[n * mrb + c / 2] |= (uint8_t)((c & 1) ? (nib << 4) : nib);
+      int bad = 0;
+      for (int i = 0; i < 8; ++i) {
+        if (i / 2 != p0 && i / 2 != p1 && w[i] != 0) bad = 1;
+        if (w[i] < -8 || w[i] > 7) bad = 1;
+      }
+      viol += bad;
+    }
+  if (violations) *violations = viol;
+  return 0;
+}
+
+/* inverse: the dense INT8 operand [N][K] (zero-filled, codes sign-extended): what the multiply-accumulate consumes */
+int oracle_decompress_int4_pairs(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K) {
+  if (K % 8) return -1;
+  int64_t mrb = meta4_row_bytes(K);
+  memset(W, 0, (size_t)(N * K));
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t c = 0; c < K / 8; ++c) {
+      uint8_t byte = meta[n * mrb + c / 2];
+      uint8_t nib = (c & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xF);
+      int p[2] = {nib & 3, (nib >> 2) & 3};
+      for (int j = 0; j < 4; ++j) {
+        uint8_t b = values[n * (K / 4) + 2 * c + j / 2];
+        int code = (j & 1) ? (b >> 4) : (b & 0xF);
+        if (code >= 8) code -= 16;
+        W[n * K + 8 * c + 2 * p[j / 2] + (j & 1)] = (int8_t)code;
+      }
     }
   return 0;
 }

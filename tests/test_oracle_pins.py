@@ -445,3 +445,83 @@ def test_patch_convolution_special_cases():
     assert np.array_equal(a1[6] - a0[6], Wc[:, 2, 1, 2].astype(np.int32))   # by exactly the weight at (c=2, i=1, j=2)
     # shape errors
     assert oracle.lib().oracle_patch_conv_int8(None, None, None, 1, 1, 5, 4, 2, 1) == -1
+
+
+# ------------------------------------------------------------------ INT4 pair-wise 4:8 [Sec. 3.1]
+def test_int4_pairwise_prune_matches_brute_force_and_keeps_whole_sub_chunks():
+    rng = np.random.default_rng(41)
+    N, K = 24, 64
+    cases = [rng.standard_normal((N, K)).astype(np.float32),
+             rng.integers(-3, 4, (N, K)).astype(np.float32)]  # a small grid: many tied scores
+    for W in cases:
+        P, mask = oracle.prune_4to8_pairs(W)
+        for n in range(N):
+            for c in range(K // 8):
+                w = W[n, 8 * c:8 * c + 8]
+                score = [float(np.float32(abs(w[2 * p])) + np.float32(abs(w[2 * p + 1]))) for p in range(4)]
+                best = max(score[i] + score[j] for i, j in PAIRS)
+                i, j = min(pr for pr in PAIRS if score[pr[0]] + score[pr[1]] == best)
+                assert mask[n, c] == (1 << i) | (1 << j)
+                exp = np.zeros(8, np.float32)
+                exp[2 * i:2 * i + 2] = w[2 * i:2 * i + 2]
+                exp[2 * j:2 * j + 2] = w[2 * j:2 * j + 2]
+                assert np.array_equal(P[n, 8 * c:8 * c + 8], exp)
+        # pattern invariants: exactly two sub-chunks kept, the kept ones never score below a dropped one
+        assert all(bin(int(b)).count("1") == 2 for b in mask.ravel())
+        nz = (P.reshape(N, K // 2, 2) != 0).any(axis=2).reshape(N, K // 8, 4).sum(axis=2)
+        assert (nz <= 2).all()
+
+
+def test_int4_pairwise_worked_example_and_storage_saving():
+    """w, x, y, z = the non-zeros of a chunk, clustered in two sub-chunks (Sec. 3.1): the compressed row holds w x y z and
+    the two sub-chunk positions.  Bytes written out by hand from the format's definition."""
+    row = np.array([[0, 0, 3, -2, 0, 0, 7, 1, 5, -6, 0, 0, -1, 4, 0, 0]], np.int8)
+    values, meta, viol = oracle.compress_int4_pairs(row)
+    assert viol == 0
+    assert values.tolist() == [[0xE3, 0x17, 0xA5, 0x4F]]   # (3,-2) (7,1) | (5,-6) (-1,4): low nibble first, two's complement
+    assert meta.tolist() == [[0x0D | (0x08 << 4)]]          # sub-chunks (1,3) -> 1 | 3<<2 ; (0,2) -> 0 | 2<<2, second chunk high
+    assert np.array_equal(oracle.decompress_int4_pairs(values, meta, 16), row)
+    # a non-zero outside the two kept sub-chunks, and a code outside the 4-bit range, are violations
+    bad = row.copy()
+    bad[0, 0] = 1
+    assert oracle.compress_int4_pairs(bad)[2] == 1
+    bad = row.copy()
+    bad[0, 9] = -9
+    assert oracle.compress_int4_pairs(bad)[2] == 1
+    g = read_golden("storage_savings.txt")
+    N, K = 64, 256
+    v, m, _ = oracle.compress_int4_pairs(np.zeros((N, K), np.int8))
+    dense_int4_bytes = N * K // 2
+    assert m.nbytes * 8 == (N * K // 8) * g["int4_index_bits_per_chunk_of_8"]
+    assert 100.0 * (1.0 - (v.nbytes + m.nbytes) / dense_int4_bytes) == pytest.approx(g["int4_saving_percent"], abs=1e-12)
+    # whole models also hold uncompressed parts, so the printed ratio lies a little below the format's own 12.8
+    assert (N * K * 4) / (v.nbytes + m.nbytes) == pytest.approx(g["fp32_dense_over_int4_size_ratio_printed"], abs=0.15)
+
+
+def test_int4_quantiser_and_round_trip_and_product():
+    rng = np.random.default_rng(42)
+    N, K, M = 48, 96, 20
+    W = rng.standard_normal((N, K)).astype(np.float32) * np.float32(0.02)
+    W[5] = 0.0
+    P, _ = oracle.prune_4to8_pairs(W)
+    Q, s = oracle.quantize_rows_int4(P)
+    amax = np.abs(P).max(axis=1)
+    s_np = np.where(amax == 0, np.float32(1), amax / np.float32(7)).astype(np.float32)
+    assert np.array_equal(s, s_np)
+    q_np = np.clip(np.rint(P / s_np[:, None]), -7, 7).astype(np.int8)  # numpy's float32 division and half-even rint
+    assert np.array_equal(Q, q_np)
+    assert (np.abs(Q).max(axis=1)[amax > 0] == 7).all() and (Q[5] == 0).all()
+    assert np.abs(Q.astype(np.float64) * s[:, None] - P).max() <= s.max() / 2 * (1 + 1e-6)
+    # the quantised tensor keeps the pattern, so it compresses without violations and decodes to itself
+    v, m, viol = oracle.compress_int4_pairs(Q)
+    assert viol == 0 and v.shape == (N, K // 4) and m.shape == (N, K // 16)
+    D = oracle.decompress_int4_pairs(v, m, K)
+    assert np.array_equal(D, Q)
+    # the product on the decoded operand is the plain integer matrix product
+    X = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    assert np.array_equal(oracle.gemm_int8_dense(X, D), X.astype(np.int64) @ Q.astype(np.int64).T)
+    # K that is a multiple of 8 but not of 16: the last index byte holds one chunk
+    Q2 = Q[:, :88]
+    v2, m2, viol2 = oracle.compress_int4_pairs(Q2)
+    assert viol2 == 0 and m2.shape == (N, 6) and (m2[:, 5] >> 4 == 0).all()
+    assert np.array_equal(oracle.decompress_int4_pairs(v2, m2, 88), Q2)
