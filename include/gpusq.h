@@ -95,6 +95,30 @@ gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t*
 gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt,
                               int64_t N, int64_t K, void* stream);
 
+/* ---- INT4 operands: the pair-wise 4:8 pattern [Sec. 3.1, the paragraph on the INT4 instruction: every chunk of 8
+ * adjacent elements of a row holds four zeros and four non-zeros, clustered in 2-wide sub-chunks that are all zero or
+ * all non-zero; the compressed row stores the four non-zero values and two 2-bit indices with the positions of the two
+ * kept sub-chunks].  The paper prints no selection rule; this library keeps the two sub-chunks with the largest
+ * |a| + |b| (one fp32 addition; ties: the lower index).  gfx950 has no 4-bit integer matrix instruction and the pattern
+ * is not a 2:4 pattern, so the product runs on the decoded INT8 operand (gpusq_gemm_int8_dense with the 4-bit scales);
+ * the format's gain here is storage: 2.5 bits per weight.  K % 8 == 0 for all four calls (GPUSQ_ERR_SHAPE otherwise).
+ *   gpusq_prune_4to8_pairs : W_in, W_out [N][K] fp32 (may alias); mask_out optional [N][K/8] bytes, bit p = sub-chunk p kept.
+ *   gpusq_quantize_rows_int4 : q = clamp(rint(x / s), -7, 7) in int8 containers, s = max|row| / 7 (1 for an all-zero
+ *       row) written to scale[rows], or the caller's scales when scale_is_input != 0; X of dt GPUSQ_F32 or GPUSQ_F16.
+ *   gpusq_compress_int4 : W [N][K] int8 holding 4-bit codes -> values [N][K/4] bytes (the 4 kept codes of chunk c in
+ *       ascending position as two's-complement nibbles: code j in byte 2c + j/2, low nibble for even j) and meta
+ *       [N][ceil(K/16)] bytes (chunk c in the low nibble of byte c/2 for even c, the high nibble for odd c; bits 0..1 =
+ *       first kept sub-chunk, bits 2..3 = second, first < second).  Positions follow the selection rule applied to W
+ *       itself.  violations (optional device int32): chunks with a dropped non-zero or a code outside -8..7.
+ *   gpusq_decompress_int4 : the inverse, W [N][K] int8 zero-filled with the codes sign-extended. */
+gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int64_t N, int64_t K, void* stream);
+gpusq_status gpusq_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input,
+                                      int64_t rows, int64_t cols, void* stream);
+gpusq_status gpusq_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N,
+                                 int64_t K, void* stream);
+gpusq_status gpusq_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K,
+                                   void* stream);
+
 /* ---- kernel-native packing of the compressed operand: re-tiles (values, meta) into the per-lane register order
  * of the gfx950 sparse matrix instructions (v_smfmac_*), rows and K zero-padded to whole tiles.  The packed buffer
  * is opaque; its size is gpusq_packed_bytes(dt, N, K) bytes (0 for invalid arguments). */

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgpusq.so")
-SOURCES = ["api.hip", "prep.hip", "spgemm.hip", "dense.hip"]
+SOURCES = ["api.hip", "prep.hip", "int4.hip", "spgemm.hip", "dense.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
     # packed-fp32 instructions are kept out of the generated code on the test machines

@@ -116,6 +116,43 @@ gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, 
   return launch_decompress(values, meta, W, dt, N, K, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int64_t N, int64_t K, void* stream) {
+  if (!W_in || !W_out) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (K % 8 != 0) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(W_in) || !aligned16(W_out)) return GPUSQ_ERR_ALIGN;
+  return launch_prune_pairs(W_in, W_out, mask_out, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input, int64_t rows,
+                                      int64_t cols, void* stream) {
+  if (!X || !Xq || !scale) return GPUSQ_ERR_NULL;
+  if (rows <= 0 || cols <= 0 || rows > INT32_MAX || cols > INT32_MAX || rows * cols > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (dt != GPUSQ_F32 && dt != GPUSQ_F16) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(X) || !aligned16(Xq)) return GPUSQ_ERR_ALIGN;
+  return launch_quantize_rows_int4(X, dt, Xq, scale, scale_is_input, rows, cols, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N, int64_t K,
+                                 void* stream) {
+  if (!W || !values || !meta) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (K % 8 != 0) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(values) || !aligned16(meta)) return GPUSQ_ERR_ALIGN;
+  return launch_compress_int4(W, values, meta, violations, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K, void* stream) {
+  if (!W || !values || !meta) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (K % 8 != 0) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(W) || !aligned16(values) || !aligned16(meta)) return GPUSQ_ERR_ALIGN;
+  return launch_decompress_int4(values, meta, W, N, K, (hipStream_t)stream);
+}
+
 size_t gpusq_packed_bytes(gpusq_dtype dt, int64_t N, int64_t K) {
   if (check_nk(N, K) != GPUSQ_OK || (dt != GPUSQ_F16 && dt != GPUSQ_I8)) return 0;
   const bool is_i8 = dt == GPUSQ_I8;

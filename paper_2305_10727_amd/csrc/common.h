@@ -55,16 +55,16 @@ __host__ __device__ inline int packed_row_to_channel(int t, int r) { return 32 *
 // least |t| 2^-21 away from every half-integer (t - floor(t) is exact in fp32).  Only the rare element inside that
 // band (about 1 in 10^5 for |t| near 100) pays for the division; |t| >= 2^20, where the test always fails, is clamped
 // either way.  +-inf and tiny or zero t take the multiply path and give the same code as the division.
-__device__ __forceinline__ int finish_code(float x, float q) {
+__device__ __forceinline__ int finish_code(float x, float q, float qmax = 127.0f) {
   q = rintf(q);
-  q = fminf(fmaxf(q, -127.0f), 127.0f);  // NaN -> -127 -> handled below
+  q = fminf(fmaxf(q, -qmax), qmax);  // NaN -> -qmax -> handled below
   return (x != x) ? 0 : (int)q;
 }
 // N values at once: the band test of all N values of all lanes is folded into one wavefront-uniform branch, so the
 // common case executes no division at all (a per-element conditional is turned into a select by the compiler, which
 // then evaluates the division for every element).
 template <int N>
-__device__ __forceinline__ void quantize_codes(const float (&x)[N], float s, float r, int (&q)[N]) {
+__device__ __forceinline__ void quantize_codes(const float (&x)[N], float s, float r, int (&q)[N], float qmax = 127.0f) {
   float t[N];
   bool near_half = false;
 #pragma unroll
@@ -109,13 +109,32 @@ __device__ __forceinline__ void quantize_bytes8(const float (&x)[8], float s, fl
   lo = p01 | (p23 << 16);
   hi = p45 | (p67 << 16);
 }
-__device__ __forceinline__ int quantize_code(float x, float s, float r) {
+__device__ __forceinline__ int quantize_code(float x, float s, float r, float qmax = 127.0f) {
   const float xs[1] = {x};
   int q[1];
-  quantize_codes<1>(xs, s, r, q);
+  quantize_codes<1>(xs, s, r, q, qmax);
   return q[0];
 }
 __device__ __forceinline__ float scale_reciprocal(float s) { return __fdiv_rn(1.0f, s); }
+
+// Selection rule inside one group of 4 [Sec. 3.1: two of every four contiguous elements are zero; the rule is this
+// library's reading]: element i is kept iff fewer than two elements beat it, where j beats i when |w_j| > |w_i|, or
+// |w_j| == |w_i| and j < i.  Magnitudes are compared as sign-cleared bit patterns (a total order).
+// Returns the 4-bit keep mask (exactly two bits set).
+__device__ __forceinline__ unsigned keep_mask_of_4(unsigned k0, unsigned k1, unsigned k2, unsigned k3) {
+  const unsigned r0 = (k1 > k0) + (k2 > k0) + (k3 > k0);
+  const unsigned r1 = (k0 >= k1) + (k2 > k1) + (k3 > k1);
+  const unsigned r2 = (k0 >= k2) + (k1 >= k2) + (k3 > k2);
+  const unsigned r3 = (k0 >= k3) + (k1 >= k3) + (k2 >= k3);
+  return (r0 < 2u) | ((r1 < 2u) << 1) | ((r2 < 2u) << 2) | ((r3 < 2u) << 3);
+}
+
+// positions of the two set bits of a keep mask, packed as the metadata nibble p0 | p1 << 2 (p0 < p1)
+__device__ __forceinline__ unsigned nibble_of_mask(unsigned m) {
+  const unsigned p0 = __builtin_ctz(m);
+  const unsigned p1 = 31u - __builtin_clz(m);
+  return p0 | (p1 << 2);
+}
 
 void set_last_hip_error(hipError_t e);
 
@@ -146,6 +165,12 @@ gpusq_status launch_im2col_patches(const void* img, void* X, gpusq_dtype dt, int
                                    int64_t K_pad, hipStream_t s);
 gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
                              int64_t rows, int64_t cols, void* workspace, hipStream_t s);
+gpusq_status launch_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input, int64_t rows,
+                                       int64_t cols, hipStream_t s);
+gpusq_status launch_prune_pairs(const float* Win, float* Wout, uint8_t* mask, int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N, int64_t K,
+                                  hipStream_t s);
+gpusq_status launch_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,
                              int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt, int64_t N, int64_t K,

@@ -6,26 +6,6 @@
 
 namespace gpusq {
 
-// ------------------------------------------------------------------------------------------------------------
-// Selection rule inside one group of 4 [Sec. 3.1: two of every four contiguous elements are zero; the rule is this
-// library's reading]: element i is kept iff fewer than two elements beat it, where j beats i when |w_j| > |w_i|, or
-// |w_j| == |w_i| and j < i.  Magnitudes are compared as sign-cleared bit patterns (a total order).
-// Returns the 4-bit keep mask (exactly two bits set).
-__device__ __forceinline__ unsigned keep_mask_of_4(unsigned k0, unsigned k1, unsigned k2, unsigned k3) {
-  const unsigned r0 = (k1 > k0) + (k2 > k0) + (k3 > k0);
-  const unsigned r1 = (k0 >= k1) + (k2 > k1) + (k3 > k1);
-  const unsigned r2 = (k0 >= k2) + (k1 >= k2) + (k3 > k2);
-  const unsigned r3 = (k0 >= k3) + (k1 >= k3) + (k2 >= k3);
-  return (r0 < 2u) | ((r1 < 2u) << 1) | ((r2 < 2u) << 2) | ((r3 < 2u) << 3);
-}
-
-// positions of the two set bits of a keep mask, packed as the metadata nibble p0 | p1 << 2 (p0 < p1)
-__device__ __forceinline__ unsigned nibble_of_mask(unsigned m) {
-  const unsigned p0 = __builtin_ctz(m);
-  const unsigned p1 = 31u - __builtin_clz(m);
-  return p0 | (p1 << 2);
-}
-
 // ------------------------------------------------------------------------------------------------------------ prune
 __global__ void __launch_bounds__(256) prune_f32_kernel(const float4* __restrict__ in, float4* __restrict__ out,
                                                         uint8_t* __restrict__ mask, int64_t groups) {
@@ -210,7 +190,7 @@ __device__ __forceinline__ float wave_max(float v) {
 template <typename T>
 __global__ void __launch_bounds__(256) quantize_rows_kernel(const T* __restrict__ X, int8_t* __restrict__ Q,
                                                             float* __restrict__ scale, int scale_is_input,
-                                                            int64_t rows, int64_t cols) {
+                                                            int64_t rows, int64_t cols, float qmax) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -222,7 +202,7 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const T* __restrict_
     float amax = 0.0f;
     for (int64_t c = lane; c < cols; c += 64) amax = fmaxf(amax, fabsf(load_as_f32(x, c)));
     amax = wave_max(amax);
-    s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, 127.0f);
+    s = (amax == 0.0f) ? 1.0f : __fdiv_rn(amax, qmax);
     if (lane == 0) scale[row] = s;
   }
   const float rs = scale_reciprocal(s);
@@ -231,12 +211,12 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const T* __restrict_
     for (int64_t c = (int64_t)lane * 4; c < cols; c += 256) {
       const float xs[4] = {load_as_f32(x, c), load_as_f32(x, c + 1), load_as_f32(x, c + 2), load_as_f32(x, c + 3)};
       int qc[4];
-      quantize_codes<4>(xs, s, rs, qc);
+      quantize_codes<4>(xs, s, rs, qc, qmax);
       *(uint32_t*)(q + c) = (uint32_t)(qc[0] & 0xFF) | ((uint32_t)(qc[1] & 0xFF) << 8) | ((uint32_t)(qc[2] & 0xFF) << 16) |
                             ((uint32_t)(qc[3] & 0xFF) << 24);
     }
   } else {
-    for (int64_t c = lane; c < cols; c += 64) q[c] = (int8_t)quantize_code(load_as_f32(x, c), s, rs);
+    for (int64_t c = lane; c < cols; c += 64) q[c] = (int8_t)quantize_code(load_as_f32(x, c), s, rs, qmax);
   }
 }
 
@@ -323,7 +303,7 @@ template <typename T>
 static gpusq_status quantize_typed(const T* X, int8_t* Xq, float* scale, int mode, int scale_is_input, int64_t rows,
                                    int64_t cols, void* workspace, hipStream_t s) {
   if (mode == GPUSQ_PER_ROW) {
-    quantize_rows_kernel<T><<<(unsigned)ceil_div(rows, 4), 256, 0, s>>>(X, Xq, scale, scale_is_input, rows, cols);
+    quantize_rows_kernel<T><<<(unsigned)ceil_div(rows, 4), 256, 0, s>>>(X, Xq, scale, scale_is_input, rows, cols, 127.0f);
     return check_launch();
   }
   const int64_t n = rows * cols;
@@ -343,6 +323,17 @@ gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* s
                              int64_t rows, int64_t cols, void* workspace, hipStream_t s) {
   if (dt == GPUSQ_F32) return quantize_typed<float>((const float*)X, Xq, scale, mode, scale_is_input, rows, cols, workspace, s);
   return quantize_typed<_Float16>((const _Float16*)X, Xq, scale, mode, scale_is_input, rows, cols, workspace, s);
+}
+
+// The same per-row quantiser with the 4-bit range: codes -7..7 in int8 containers, scale = max|row| / 7.
+gpusq_status launch_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input, int64_t rows,
+                                       int64_t cols, hipStream_t s) {
+  const unsigned blocks = (unsigned)ceil_div(rows, 4);
+  if (dt == GPUSQ_F32)
+    quantize_rows_kernel<float><<<blocks, 256, 0, s>>>((const float*)X, Xq, scale, scale_is_input, rows, cols, 7.0f);
+  else
+    quantize_rows_kernel<_Float16><<<blocks, 256, 0, s>>>((const _Float16*)X, Xq, scale, scale_is_input, rows, cols, 7.0f);
+  return check_launch();
 }
 
 // ------------------------------------------------------------------------------------------------------------ compress

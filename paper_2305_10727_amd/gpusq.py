@@ -24,6 +24,7 @@ EXPORTS = [
     "gpusq_quantize_workspace_bytes",
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
+    "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
 ]
 
 
@@ -71,6 +72,10 @@ def lib():
         L.gpusq_patch_embed16_int8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
+        L.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.gpusq_quantize_rows_int4.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
+        L.gpusq_compress_int4.argtypes = [vp, vp, vp, vp, i64, i64, vp]
+        L.gpusq_decompress_int4.argtypes = [vp, vp, vp, i64, i64, vp]
         for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
                      "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
             getattr(L, name).restype = ci
@@ -152,6 +157,44 @@ def decompress(values, meta, K):
     W = torch.empty((N, K), dtype=values.dtype, device=values.device)
     _check(lib().gpusq_decompress(_ptr(values), _ptr(meta), _ptr(W), _TORCH_DT[values.dtype], N, K, _stream()),
            "gpusq_decompress")
+    return W
+
+
+def prune_4to8_pairs(W, want_mask=False):
+    """gpusq_prune_4to8_pairs: W [N,K] fp32 -> pruned copy (and the keep mask [N,K/8] uint8)"""
+    N, K = W.shape
+    out = torch.empty_like(W)
+    mask = torch.empty((N, K // 8), dtype=torch.uint8, device=W.device) if want_mask else None
+    _check(lib().gpusq_prune_4to8_pairs(_ptr(W), _ptr(out), _ptr(mask), N, K, _stream()), "gpusq_prune_4to8_pairs")
+    return (out, mask) if want_mask else out
+
+
+def quantize_rows_int4(X, scale=None):
+    """gpusq_quantize_rows_int4: returns (4-bit codes in an int8 tensor, scale [rows])"""
+    rows, cols = X.shape
+    Xq = torch.empty((rows, cols), dtype=torch.int8, device=X.device)
+    given = scale is not None
+    if not given:
+        scale = torch.empty(rows, dtype=torch.float32, device=X.device)
+    _check(lib().gpusq_quantize_rows_int4(_ptr(X), _TORCH_DT[X.dtype], _ptr(Xq), _ptr(scale), int(given), rows, cols, _stream()),
+           "gpusq_quantize_rows_int4")
+    return Xq, scale
+
+
+def compress_int4(Wq, want_violations=False):
+    """gpusq_compress_int4: Wq [N,K] int8 (4-bit codes) -> (values [N,K/4] uint8, meta [N,ceil(K/16)] uint8[, violations])"""
+    N, K = Wq.shape
+    values = torch.empty((N, K // 4), dtype=torch.uint8, device=Wq.device)
+    meta = torch.empty((N, (K // 8 + 1) // 2), dtype=torch.uint8, device=Wq.device)
+    viol = torch.empty(1, dtype=torch.int32, device=Wq.device) if want_violations else None
+    _check(lib().gpusq_compress_int4(_ptr(Wq), _ptr(values), _ptr(meta), _ptr(viol), N, K, _stream()), "gpusq_compress_int4")
+    return (values, meta, viol) if want_violations else (values, meta)
+
+
+def decompress_int4(values, meta, K):
+    N = values.shape[0]
+    W = torch.empty((N, K), dtype=torch.int8, device=values.device)
+    _check(lib().gpusq_decompress_int4(_ptr(values), _ptr(meta), _ptr(W), N, K, _stream()), "gpusq_decompress_int4")
     return W
 
 

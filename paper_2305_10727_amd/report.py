@@ -74,12 +74,13 @@ def main():
     ap.add_argument("--iters", type=int, default=30)
     ap.add_argument("--configs", default="c0,c1,c2,c3,c4_vitl,c4_vith")
     ap.add_argument("--only-blocks", action="store_true", help="skip the per-layer and patch-embedding tables")
+    ap.add_argument("--only-int4", action="store_true", help="only the INT4 format table")
     a = ap.parse_args()
     lines = ["| config | layer | M | K | N | GELU | path | sparse cold us | sparse hot us | dense cold us | dense hot us | speedup (cold) | "
              "TOPS dense-equiv. (cold) | of sparse peak | of 8 TB/s (algorithmic bytes) |",
              "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     totals = {}
-    for cfg_name in ([] if a.only_blocks else a.configs.split(",")):
+    for cfg_name in ([] if a.only_blocks or a.only_int4 else a.configs.split(",")):
         cfg = synth.CONFIGS[cfg_name]
         M = cfg["M"]
         for name, K, N, gelu, _dist in cfg["layers"]:
@@ -101,7 +102,7 @@ def main():
               "hot buffers):", "", "| model | images | P | M | K | N | path | quantise us | im2col us | sparse GEMM us | whole layer us | whole layer, patches "
               "gathered by the GEMM (P = 16) us |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
     dev = torch.device("cuda")
-    for model, B, HW, P, D in [] if a.only_blocks else [("ViT-B/16, batch 64", 64, 224, 16, 768), ("ViT-L/16, batch 256", 256, 224, 16, 1024),
+    for model, B, HW, P, D in [] if a.only_blocks or a.only_int4 else [("ViT-B/16, batch 64", 64, 224, 16, 768), ("ViT-L/16, batch 256", 256, 224, 16, 1024),
                                                       ("ViT-H/14, batch 256", 256, 224, 14, 1280)]:
         img = torch.randn(B, 3, HW, HW, device=dev).half()
         Wc = torch.randn(D, 3, P, P, device=dev) * 0.02
@@ -131,7 +132,7 @@ def main():
               "one quantises it with a dynamic per-tensor scale (12 launches).  Chained: static scales, the re-quantisation fused into the "
               "producer's epilogue (6 launches), launched one by one or replayed as one HIP graph:", "",
               "| model | M | D | hidden | unchained us | chained us | chained, HIP graph us |", "|---|---|---|---|---|---|---|"]
-    for model, M, D, hidden in [("DeiT-Tiny, batch 1", 197, 192, 768), ("DeiT-Small, batch 1", 197, 384, 1536), ("ViT-B/16, batch 1", 197, 768, 3072),
+    for model, M, D, hidden in [] if a.only_int4 else [("DeiT-Tiny, batch 1", 197, 192, 768), ("DeiT-Small, batch 1", 197, 384, 1536), ("ViT-B/16, batch 1", 197, 768, 3072),
                                 ("ViT-B/16, batch 8", 1576, 768, 3072), ("ViT-B/16, batch 64", 12608, 768, 3072)]:
         shapes = [(3 * D, D), (D, D), (hidden, D), (D, hidden)]
         Ws = [torch.randn(n, k, device=dev) * 0.02 for n, k in shapes]
@@ -158,6 +159,42 @@ def main():
         lines.append("| %s | %d | %d | %d | %.1f | %.1f | %.1f |" % (model, M, D, hidden, t_un, t_chain, t_graph))
         print(lines[-1], flush=True)
         del blk, lins
+        torch.cuda.empty_cache()
+    lines += ["", "INT4 weights in the pair-wise 4:8 format (4 kept 4-bit codes + two 2-bit indices per chunk of 8 = 2.5 bits per weight); the "
+              "product runs on the decoded INT8 operand with the dense kernel.  Weight-side kernels (us, and GB/s over the bytes each must "
+              "move), then one layer at M rows: decode + dense INT8 GEMM against the 2:4 INT8 sparse GEMM:", "",
+              "| layer | N | K | prune us (GB/s) | quantise us (GB/s) | compress us (GB/s) | decode us (GB/s) | compressed bytes | M | "
+              "decode + dense GEMM us | 2:4 INT8 sparse GEMM us |", "|---|---|---|---|---|---|---|---|---|---|---|"]
+    for layer, N, K, M in [("ViT-B fc1", 3072, 768, 12608), ("ViT-B fc2", 768, 3072, 12608), ("ViT-H fc1", 5120, 1280, 65792)]:
+        W = torch.randn(N, K, device=dev) * 0.02
+        bias = torch.randn(N, device=dev) * 0.01
+        P = G.prune_4to8_pairs(W)
+        Q, s4 = G.quantize_rows_int4(P)
+        v, m = G.compress_int4(Q)
+        D = G.decompress_int4(v, m, K)
+        L, st = G.lib(), G._stream
+        from .pipeline import _p
+        t_p = _time([lambda: L.gpusq_prune_4to8_pairs(_p(W), _p(P), None, N, K, st())], a.iters)
+        t_q = _time([lambda: L.gpusq_quantize_rows_int4(_p(P), G.F32, _p(Q), _p(s4), 0, N, K, st())], a.iters)
+        t_c = _time([lambda: L.gpusq_compress_int4(_p(Q), _p(v), _p(m), None, N, K, st())], a.iters)
+        t_d = _time([lambda: L.gpusq_decompress_int4(_p(v), _p(m), _p(D), N, K, st())], a.iters)
+        comp = v.numel() + m.numel()
+        lin = SparseLinear(M, K, N, "int8", gelu=False, bias=True)
+        lin.prepare_weights(W, fused=K * 4 <= 64 * 1024)
+        X = torch.randn(M, K, device=dev).half()
+        lin.quantize_activations(X)
+        t_sparse = _time([lambda: lin.gemm(X, bias)], a.iters)
+
+        def int4_layer():
+            L.gpusq_decompress_int4(_p(v), _p(m), _p(D), N, K, st())
+            L.gpusq_gemm_int8_dense(_p(lin.Xq), _p(D), _p(lin.act_scale), _p(s4), _p(bias), _p(lin.Y), G.F16, None, M, N, K, G.EPI_BIAS, st())
+        t_int4 = _time([int4_layer], a.iters)
+        gbs = lambda nbytes, us: nbytes / us / 1e3
+        lines.append("| %s | %d | %d | %.1f (%.0f) | %.1f (%.0f) | %.1f (%.0f) | %.1f (%.0f) | %d | %d | %.1f | %.1f |" % (
+            layer, N, K, t_p, gbs(8 * N * K, t_p), t_q, gbs(9 * N * K, t_q), t_c, gbs(N * K + comp, t_c), t_d, gbs(N * K + comp, t_d),
+            comp, M, t_int4, t_sparse))
+        print(lines[-1], flush=True)
+        del lin
         torch.cuda.empty_cache()
     text = "\n".join(lines) + "\n"
     print(text)

@@ -681,3 +681,45 @@ def test_encoder_block_chain_and_its_graph(g, M, D, hidden, seed):
         y_graph = blk.replay()
         torch.cuda.synchronize()
         assert torch.equal(y_graph, y_eager) and torch.equal(blk.fc1.Y, codes_eager)
+
+
+# ------------------------------------------------------------------------------------------------ INT4 pair-wise 4:8
+@pytest.mark.parametrize("N,K,grid", [(1, 8, False), (3, 24, True), (64, 192, False), (100, 136, True), (768, 768, False),
+                                      (512, 3072, False), (257, 1032, True)])
+def test_int4_pairwise_path_bit_exact(g, N, K, grid):
+    """prune (pair-wise 4:8) -> 4-bit per-channel codes -> compressed storage -> decode, each step against the oracle;
+    then the layer on the decoded operand (dense INT8 kernel with the 4-bit scales) against the oracle's product.
+    grid: weights on a small integer grid, so that many sub-chunk scores tie."""
+    if grid:
+        W = synth.small_integers((N, K), -3, 3, seed=N + K, ids=(60,)).astype(np.float32)
+    else:
+        W = synth.weights(N, K, seed=N + K, ids=(60,))
+    P_o, mask_o = oracle.prune_4to8_pairs(W)
+    P_g, mask_g = g.prune_4to8_pairs(dev(W), want_mask=True)
+    assert np.array_equal(host(P_g).view(np.uint32), P_o.view(np.uint32)) and np.array_equal(host(mask_g), mask_o)
+    Q_o, s_o = oracle.quantize_rows_int4(P_o)
+    Q_g, s_g = g.quantize_rows_int4(P_g)
+    assert np.array_equal(host(Q_g), Q_o) and np.array_equal(host(s_g), s_o)
+    Q_h, _ = g.quantize_rows_int4(P_g.half(), scale=s_g)  # fp16 input, caller's scales
+    assert np.array_equal(host(Q_h), oracle.quantize_rows_int4(P_o.astype(np.float16).astype(np.float32), scale=s_o)[0])
+    v_o, m_o, viol_o = oracle.compress_int4_pairs(Q_o)
+    v_g, m_g, viol_g = g.compress_int4(Q_g, want_violations=True)
+    assert viol_o == 0 and int(host(viol_g)[0]) == 0
+    assert np.array_equal(host(v_g), v_o) and np.array_equal(host(m_g), m_o)
+    D_g = g.decompress_int4(v_g, m_g, K)
+    assert np.array_equal(host(D_g), Q_o)
+    # a tensor that does not follow the pattern (and holds codes beyond 4 bits): same positions, same violation count
+    R = synth.small_integers((N, K), -9, 9, seed=N + K, ids=(61,)).astype(np.int8)
+    rv_o, rm_o, rviol_o = oracle.compress_int4_pairs(R)
+    rv_g, rm_g, rviol_g = g.compress_int4(dev(R), want_violations=True)
+    assert np.array_equal(host(rv_g), rv_o) and np.array_equal(host(rm_g), rm_o) and int(host(rviol_g)[0]) == rviol_o > 0
+    if K % 16 == 0 and N % 4 == 0:
+        M = 77
+        X = synth.activations(M, K, "normal_clip4", seed=N + K, ids=(62,))
+        bias = synth.bias(N, seed=N + K, ids=(62,))
+        Xq_o, s_a = oracle.quantize_tensor_int8(X)
+        Xq_g, s_a_g = g.quantize_int8(dev(X), g.PER_TENSOR)
+        acc_o = oracle.gemm_int8_dense(Xq_o, oracle.decompress_int4_pairs(v_o, m_o, K))
+        assert np.array_equal(host(g.gemm_int8_dense(Xq_g, D_g, out_dtype=torch.int32)), acc_o)
+        y = host(g.gemm_int8_dense(Xq_g, D_g, act_scale=s_a_g, w_scale=s_g, bias=dev(bias)))
+        assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(acc_o, s_a, s_o, bias)["y16"].view(np.uint16))
