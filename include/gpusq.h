@@ -184,7 +184,10 @@ gpusq_status gpusq_patch_embed16_fp16(const void* img, const void* Wpacked, cons
  * 2: tile kernel); for the tile kernel out[1] = rows per tile unit u, out[2] = 256-channel blocks, out[3] = full_tm
  * (a full tile has u * full_tm rows), out[4] = row chunks covered by full tiles, out[5] = tail_tm (the remaining rows
  * are cut into tiles of u * tail_tm rows), out[6] = tiles in all, out[7] = workgroups launched.  Same argument checks
- * as the GEMM calls (sizes only). */
+ * as the GEMM calls (sizes only).
+ * The environment variable GPUSQ_FORCE_KERNEL (0, 1 or 2; read at every call) overrides out[0] and the kernel the
+ * GEMM entry points launch, where the forced kernel can run the problem: a testing aid, so that both kernels can be
+ * checked on the same shapes. */
 gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]);
 
 /* ---- dense twins: the same computation from the masked but uncompressed W [N][K], on dense matrix instructions,

@@ -19,6 +19,8 @@
 //                       global->LDS copies (no staging registers), one persistent workgroup of 8 wavefronts per CU.
 //                       Needs K*elemsize % 128 == 0.
 //   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
+#include <cstdlib>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -807,71 +809,109 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
 #pragma unroll
     for (int j = 0; j < TM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
 
-  v4i xr[XCH];
-  v4i av[2][TN];
-  int ai[2][TN];
+  // Operands are requested D - 1 K steps ahead, each step into its own set of registers: at these sizes a K step is a
+  // few matrix instructions, and what a step costs is the memory latency divided by the number of steps in flight.
+  constexpr int D = TM == 1 ? 6 : 3;
+  v4i xr[D][XCH];
+  v4i av[D][TN];
+  int ai[D][TN];
 
-  auto load_x = [&](int ks) {
+  // Addresses: a wavefront-uniform base that advances by a constant per K step (scalar arithmetic) plus a 32-bit lane
+  // offset fixed for the whole tile, so a K step issues its loads with next to no vector arithmetic: with one wavefront
+  // per SIMD (a lone wavefront issues a vector instruction only every 6-8 clocks) address arithmetic per load is what a
+  // step would otherwise cost.
+  const global_u8* Xtile = uniform_ptr(Xg + (int64_t)m_blk * BM * k_bytes);
+  uint32_t xoff[XCH];
+  int xcol[XCH];  // first K byte (inside a step) of the lane's chunk, or past any K for rows beyond M
 #pragma unroll
-    for (int j = 0; j < XCH; ++j) {
-      const int c = tid + 256 * j;
-      const int row = c >> 3, cc = c & 7;
-      const int64_t m = (int64_t)m_blk * BM + row;
-      const int64_t off = (int64_t)ks * kStepBytes + cc * 16;
-      xr[j] = (m < M && off < k_bytes) ? *(const v4i*)(Xg + m * k_bytes + off) : v4i{0, 0, 0, 0};
-    }
+  for (int j = 0; j < XCH; ++j) {
+    const int c = tid + 256 * j;
+    const int row = c >> 3, cc = c & 7;
+    xoff[j] = (uint32_t)row * (uint32_t)k_bytes + cc * 16;  // the host keeps 128 rows of X below 4 GiB
+    xcol[j] = ((int64_t)m_blk * BM + row < M) ? cc * 16 : 0x7FFFFFFF;
+  }
+  static_assert(TN == 4, "a wavefront's fragments are the four of one 64-channel row block");
+  const int rb = rb0;
+  const bool rb_ok = rb < row_blocks;  // wavefront-uniform
+  const int f0 = (rb & 3) * 4;
+  const global_u8* Wrow = uniform_ptr(Wg + (int64_t)(rb >> 2) * ksteps * tile_bytes(IS_I8));
+  const uint32_t a_lane = (uint32_t)(f0 * kFragValueBytes + lane * 16);
+  const uint32_t i_lane = (uint32_t)index_offset(IS_I8, f0, lane);  // the index words of fragments f0 .. f0+3 are adjacent
+  auto load_x = [&](int ks, int slot) {
+    const global_u8* base = Xtile + (int64_t)ks * kStepBytes;
+    const int k_left = (int)(k_bytes - (int64_t)ks * kStepBytes < kStepBytes ? k_bytes - (int64_t)ks * kStepBytes : kStepBytes);
+#pragma unroll
+    for (int j = 0; j < XCH; ++j)
+      xr[slot][j] = xcol[j] < k_left ? *(const __attribute__((address_space(1))) v4i*)(base + xoff[j]) : v4i{0, 0, 0, 0};
   };
-  auto store_x = [&](int buf) {
+  auto store_x = [&](int buf, int slot) {
 #pragma unroll
     for (int j = 0; j < XCH; ++j) {
       const int c = tid + 256 * j;
-      *(v4i*)(&Xs[buf][(c >> 3) * kLdsRow + (c & 7) * 16]) = xr[j];
+      *(v4i*)(&Xs[buf][(c >> 3) * kLdsRow + (c & 7) * 16]) = xr[slot][j];
     }
   };
   auto load_a = [&](int ks, int slot) {
+    if (rb_ok) {
+      const global_u8* t = Wrow + (int64_t)ks * tile_bytes(IS_I8);
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      const int rb = rb0 + tn / 4;
-      if (rb < row_blocks) {
-        const uint8_t* t = Wg + ((int64_t)(rb >> 2) * ksteps + ks) * tile_bytes(IS_I8);
-        const int f = (rb & 3) * 4 + (tn & 3);
-        av[slot][tn] = *(const v4i*)(t + f * kFragValueBytes + lane * 16);
-        if constexpr (IS_I8)
-          ai[slot][tn] = *(const int*)(t + index_offset(true, f, lane));
-        else
-          ai[slot][tn] = (int)*(const uint16_t*)(t + index_offset(false, f, lane));
+      for (int tn = 0; tn < TN; ++tn)
+        av[slot][tn] = *(const __attribute__((address_space(1))) v4i*)(t + a_lane + tn * kFragValueBytes);
+      if constexpr (IS_I8) {
+        const v4i w = *(const __attribute__((address_space(1))) v4i*)(t + i_lane);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) ai[slot][tn] = w[tn];
       } else {
+        const ep_v2u w = *(const __attribute__((address_space(1))) ep_v2u*)(t + i_lane);
+        ai[slot][0] = (int)(w[0] & 0xFFFFu);
+        ai[slot][1] = (int)(w[0] >> 16);
+        ai[slot][2] = (int)(w[1] & 0xFFFFu);
+        ai[slot][3] = (int)(w[1] >> 16);
+      }
+    } else {
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) {
         av[slot][tn] = v4i{0, 0, 0, 0};
         ai[slot][tn] = 0;
       }
     }
   };
 
-  load_x(0);
-  load_a(0, 0);
-  store_x(0);
-  __syncthreads();
+#pragma unroll
+  for (int d = 0; d < D - 1; ++d)
+    if (d < ksteps) {
+      load_x(d, d);
+      load_a(d, d);
+    }
 
   const int b_row = wm * TM * 16 + (lane & 15);
   const int b_col = (lane >> 4) * 16;
-  for (int ks = 0; ks < ksteps; ++ks) {
-    const int cur = ks & 1;
-    const bool more = ks + 1 < ksteps;
-    if (more) {
-      load_x(ks + 1);
-      load_a(ks + 1, cur ^ 1);
-    }
+  for (int ks0 = 0; ks0 < ksteps; ks0 += D) {
 #pragma unroll
-    for (int mt = 0; mt < TM; ++mt) {
-      const uint8_t* p = &Xs[cur][(b_row + mt * 16) * kLdsRow + b_col];
-      const v4i lo = *(const v4i*)p, hi = *(const v4i*)(p + 64);
-      const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    for (int j = 0; j < D; ++j) {
+      const int ks = ks0 + j;
+      if (ks < ksteps) {  // workgroup-uniform
+        if (ks + D - 1 < ksteps) {
+          load_x(ks + D - 1, (j + D - 1) % D);
+          load_a(ks + D - 1, (j + D - 1) % D);
+        }
+        // The X slab alternates between two LDS buffers; the barrier of step ks - 1 lies behind every wavefront's
+        // reads of step ks - 2, which used this buffer last.
+        const int cur = ks & 1;
+        store_x(cur, j);
+        __syncthreads();
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[cur][tn], b, acc[tn][mt], ai[cur][tn]);
+        for (int mt = 0; mt < TM; ++mt) {
+          const uint8_t* p = &Xs[cur][(b_row + mt * 16) * kLdsRow + b_col];
+          const v4i lo = *(const v4i*)p, hi = *(const v4i*)(p + 64);
+          const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+          for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[j][tn], b, acc[tn][mt], ai[j][tn]);
+        }
+      }
     }
-    if (more) store_x(cur ^ 1);
-    __syncthreads();
   }
+  __syncthreads();  // the per-channel constants written at the top are read below (also when K has no step at all)
   wave_epilogue<IS_I8, TN, TM>(a, acc, cs, bs, n_blk * BN, n_blk * BN + wn * TN * 16, (int64_t)m_blk * BM + wm * TM * 16, lane);
 }
 
@@ -881,6 +921,7 @@ static gpusq_status launch_small(const GemmArgs& a, hipStream_t s) {
   const int tiles_n = (int)ceil_div(a.N, BN), tiles_m = (int)ceil_div(a.M, BM);
   const int total = tiles_n * tiles_m;
   const int grid = (int)ceil_div(total, 8) * 8;  // whole rounds over the 8 XCDs; surplus workgroups exit at once
+  if ((int64_t)a.K * (IS_I8 ? 1 : 2) * BM >= ((int64_t)1 << 32)) return GPUSQ_ERR_UNSUPPORTED;  // 32-bit lane offsets inside a tile's rows of X
   spgemm_small_kernel<IS_I8, TN, TM, WN, WM><<<grid, 256, 0, s>>>(a, tiles_n, total);
   return check_launch();
 }
@@ -955,20 +996,43 @@ static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
   return best;
 }
 
-// Which kernel a problem takes: 0 = small kernel with 64 x 64 tiles (latency-bound sizes), 1 = small kernel with
-// 128 x 128 tiles (ragged K: zero-filling path), 2 = tile kernel.
-static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K) {
+// Which kernel a problem takes: 0 = small kernel with 64 x 64 tiles, 1 = small kernel with 128 x 128 tiles, 2 = tile
+// kernel.  K that is not a whole number of 128-byte steps needs the zero-filling small kernel.  Otherwise the estimated
+// run times decide (microseconds, fitted to graph-replayed launches on MI355X for M = 197 ... 6304): the small kernel
+// keeps two workgroups per CU busy, costs about 0.8 us per K step and round of 512 workgroups and never less than what
+// one workgroup's chain of loads takes; the tile kernel costs its plan's makespan plus the start-up of its pipeline.
+// With few rows (one image: M = 197) the tile kernel has too few tiles for the chip and the small kernel is about
+// twice as fast; from a few thousand rows on the tile kernel wins.  fused_patches: the patch gather exists in the tile
+// kernel only, so that mode keeps the plain size rule.
+static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu, int resident, bool fused_patches = false) {
+  const int64_t k_bytes = K * (is_i8 ? 1 : 2);
+  const int64_t ksteps = ceil_div(k_bytes, kStepBytes);
+  const int64_t wgs64 = ceil_div(M, 64) * ceil_div(N, 64);
+  // Testing aid: GPUSQ_FORCE_KERNEL = 0, 1 or 2 overrides the choice (2 only where the tile kernel can run the problem).
+  if (const char* f = getenv("GPUSQ_FORCE_KERNEL")) {
+    if (f[0] >= '0' && f[0] <= '2' && f[1] == 0) {
+      const int c = f[0] - '0';
+      if (c != 2 || k_bytes % kStepBytes == 0) return c;
+    }
+  }
   if (M * N <= (int64_t)256 * 1024) return 0;
-  if ((K * (is_i8 ? 1 : 2)) % kStepBytes != 0) return 1;
-  return 2;
+  if (k_bytes % kStepBytes != 0) return wgs64 <= 2 * resident ? 0 : 1;
+  if (fused_patches) return 2;
+  if (wgs64 > 16 * resident) return 2;  // far beyond the crossover: skip the planning
+  const double per_round = 0.8 * ksteps, chain = 2.2 + 0.6 * ksteps;
+  const double throughput = 3.3 + per_round * (double)wgs64 / (2.0 * resident);
+  const double est_small = chain > throughput ? chain : throughput;
+  const TilePlan p = make_plan((int)M, (int)N, resident, (int)ksteps, gelu);
+  const double est_tile = plan_makespan(p, grid_for(p, resident), (int)ksteps, gelu) + 2.8;
+  return est_small < est_tile ? 0 : 2;
 }
 
 gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t* out) {
-  const int choice = kernel_choice(is_i8, M, N, K);
+  const int resident = cus > 0 ? cus : num_cus();
+  const int choice = kernel_choice(is_i8, M, N, K, (epilogue & GPUSQ_EPI_GELU) != 0, resident);
   for (int i = 0; i < 8; ++i) out[i] = 0;
   out[0] = choice;
   if (choice != 2) return GPUSQ_OK;
-  const int resident = cus > 0 ? cus : num_cus();
   const int ksteps = (int)(K * (is_i8 ? 1 : 2) / kStepBytes);
   const TilePlan p = make_plan((int)M, (int)N, resident, ksteps, (epilogue & GPUSQ_EPI_GELU) != 0);
   out[1] = 64;
@@ -984,14 +1048,14 @@ gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilog
 template <bool IS_I8>
 static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
-  const int choice = kernel_choice(IS_I8, a.M, a.N, a.K);
   const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
+  const int resident = num_cus();
+  const int choice = kernel_choice(IS_I8, a.M, a.N, a.K, gelu, resident, a.patch_P != 0);
   // the fused patch gather exists in the tile kernel only, for 16 x 16 patches, fp16 output, no GELU
   if (a.patch_P != 0 && (choice != 2 || a.patch_P != 16 || a.out_dt != GPUSQ_F16 || gelu)) return GPUSQ_ERR_UNSUPPORTED;
   if (choice == 0) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);
   if (choice == 1) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);
   // persistent grid: one workgroup per CU, never more workgroups than tiles
-  const int resident = num_cus();
   const int ksteps = (int)(k_bytes / kStepBytes);
   const TilePlan plan = make_plan(a.M, a.N, resident, ksteps, gelu);
   const dim3 grid((unsigned)grid_for(plan, resident));

@@ -398,8 +398,23 @@ TILE_SHAPES = [(2100, 128, 520, 11), (1500, 256, 388, 12), (4500, 640, 1024, 13)
                (50003, 256, 512, 16), (41000, 128, 776, 17)]
 
 
+@pytest.fixture
+def force_kernel(monkeypatch):
+    """the library's testing aid: run the sparse GEMM entry points on a chosen kernel (0 / 1: small kernel with 64 x 64 /
+    128 x 128 tiles, 2: tile kernel) whatever the sizes would pick"""
+    def force(k):
+        if k is None:
+            monkeypatch.delenv("GPUSQ_FORCE_KERNEL", raising=False)
+        else:
+            monkeypatch.setenv("GPUSQ_FORCE_KERNEL", str(k))
+    return force
+
+
+@pytest.mark.parametrize("kernel", [2, 0, 1])
 @pytest.mark.parametrize("M,K,N,seed", TILE_SHAPES)
-def test_tile_kernel_corner_shapes(g, M, K, N, seed):
+def test_tile_kernel_corner_shapes(g, force_kernel, M, K, N, seed, kernel):
+    force_kernel(kernel)
+    assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] == kernel
     p = Int8Problem(M, K, N, seed)
     d = gpu_prepare_int8(g, p.W32, p.X32)
     exp = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
