@@ -480,10 +480,9 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
   const int64_t slab_bytes = (int64_t)16 * a.N * OB, half_bytes = (int64_t)8 * a.N * OB;
   global_u8* ywave = uniform_ptr((uint8_t*)a.Y + (m_wave * a.N + n_wave) * OB);  // the wavefront's first row and channel
   const uint32_t row_off = (uint32_t)(c & 7) * (uint32_t)a.N * OB;             // row c % 8 (the host keeps 16 rows of Y below 2 GiB)
-  // values of the lane's 8 channels of batch g (32 channels) in slab mt, dequantised / biased / activated, in fp32
-  auto batch_values = [&](int g, int mt, float (&v)[8]) {
+  // per-channel constants of the lane's 8 channels of batch g (32 channels): read once per batch, used for every slab
+  auto batch_constants = [&](int g, float (&c8)[8], float (&b8)[8]) {
     const int nl = (g >> 1) * kRowBlock + (g & 1) * 32 + q * 8;
-    float c8[8], b8[8];
 #pragma unroll
     for (int j = 0; j < 8; j += 4) {
       const float4 bb = *(const float4*)(p + 128 + nl + j);
@@ -491,8 +490,15 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
       if constexpr (IS_I8) {
         const float4 cc = *(const float4*)(p + nl + j);
         c8[j] = s_a * cc.x; c8[j + 1] = s_a * cc.y; c8[j + 2] = s_a * cc.z; c8[j + 3] = s_a * cc.w;
+      } else {
+        c8[j] = c8[j + 1] = c8[j + 2] = c8[j + 3] = 1.0f;
       }
     }
+    pin8(c8);  // (keeps the products in registers: recomputing them per slab costs an instruction per output)
+    pin8(b8);
+  };
+  // values of those channels in slab mt, dequantised / biased / activated, in fp32
+  auto batch_values = [&](int g, int mt, const float (&c8)[8], const float (&b8)[8], float (&v)[8]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -515,6 +521,9 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
     for (int gp = 0; gp < kTileTN / 4; ++gp) {
       // the channels this lane stores: those of its own half of the line
       const bool n_ok = n_wave + gp * kRowBlock + up * 32 + q * 8 < a.N;
+      float c8[2][8], b8[2][8];
+      batch_constants(2 * gp, c8[0], b8[0]);
+      batch_constants(2 * gp + 1, c8[1], b8[1]);
 #pragma unroll
       for (int mt = 0; mt < kTileTM; ++mt) {
         if (!CHECKED || mt < tm_active) {
@@ -522,7 +531,7 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
             float v[8];
-            batch_values(2 * gp + h, mt, v);
+            batch_values(2 * gp + h, mt, c8[h], b8[h], v);
             pin8(v);  // the fp32 result is rounded to fp32 before it is rounded to fp16 (no fused fma-and-convert)
             ep_v8h hh;
 #pragma unroll
@@ -555,23 +564,30 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
     // of lane c - 8; even q hold batches 0 (first) and 1 (second), odd q batches 2 and 3, channels 16 * (q / 2) ...
     const int piece = 4 * (q & 1) + 2 * up + (q >> 1);
     const bool n_ok = n_wave + piece * 16 < a.N;
+    unsigned d[kTileTM][4][2];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float c8[8], b8[8];
+      batch_constants(g, c8, b8);
+#pragma unroll
+      for (int mt = 0; mt < kTileTM; ++mt) {
+        if (!CHECKED || mt < tm_active) {
+          float v[8];
+          batch_values(g, mt, c8, b8, v);
+          quantize_bytes8(v, so, rso, d[mt][g][0], d[mt][g][1]);
+        }
+      }
+    }
 #pragma unroll
     for (int mt = 0; mt < kTileTM; ++mt) {
       if (!CHECKED || mt < tm_active) {
-        unsigned d[4][2];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float v[8];
-          batch_values(g, mt, v);
-          quantize_bytes8(v, so, rso, d[g][0], d[g][1]);
-        }
         ep_v4i first, second;
 #pragma unroll
         for (int w = 0; w < 2; ++w) {
           // result 0: even q keep their own register, odd q receive the second register of lane q - 1;
           // result 1: even q receive the first register of lane q + 1, odd q keep their own second register
-          const ep_v2u x = __builtin_amdgcn_permlane16_swap(d[0][w], d[2][w], false, false);
-          const ep_v2u y = __builtin_amdgcn_permlane16_swap(d[1][w], d[3][w], false, false);
+          const ep_v2u x = __builtin_amdgcn_permlane16_swap(d[mt][0][w], d[mt][2][w], false, false);
+          const ep_v2u y = __builtin_amdgcn_permlane16_swap(d[mt][1][w], d[mt][3][w], false, false);
           first[w] = (int)x[0]; first[2 + w] = (int)x[1];
           second[w] = (int)y[0]; second[2 + w] = (int)y[1];
         }
