@@ -120,15 +120,28 @@ def meta4_row_bytes(K):
     return (K // 8 + 1) // 2
 
 
-def prune_4to8_pairs(W):
+def prune_4to8_pairs(W, one_per_group=False):
     """W [N,K] float32, K % 8 == 0 -> (pruned W, mask bytes [N,K/8]); two of the four 2-wide sub-chunks of every chunk
-    of 8 are kept (highest |a| + |b|)."""
+    of 8 are kept (highest |a| + |b|); one_per_group: one of them in each group of 4, which makes the row 2:4 as well."""
     W = _c(W, np.float32)
     N, K = W.shape
     out = np.empty_like(W)
     mask = np.empty((N, K // 8), np.uint8)
-    assert lib().oracle_prune_4to8_pairs_f32(_p(W), _p(out), _p(mask), _i64(N), _i64(K)) == 0
+    assert lib().oracle_prune_4to8_pairs_f32(_p(W), _p(out), _p(mask), int(one_per_group), _i64(N), _i64(K)) == 0
     return out, mask
+
+
+def int4_pairs_to_sparse_int8(values4, meta4, K):
+    """INT4 pair-wise storage with one kept sub-chunk per group of 4 -> the INT8 2:4 compressed form
+    (values [N,K/2] int8, meta [N,ceil(K/8)] uint8, chunks without that shape)"""
+    values4, meta4 = _c(values4, np.uint8), _c(meta4, np.uint8)
+    N = values4.shape[0]
+    values8 = np.empty((N, K // 2), np.int8)
+    meta8 = np.empty((N, meta_row_bytes(K)), np.uint8)
+    bad = ctypes.c_int32(0)
+    assert lib().oracle_int4_pairs_to_sparse_int8(_p(values4), _p(meta4), _p(values8), _p(meta8), ctypes.byref(bad), _i64(N),
+                                                  _i64(K)) == 0
+    return values8, meta8, int(bad.value)
 
 
 def quantize_rows_int4(X, scale=None):

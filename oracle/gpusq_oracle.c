@@ -325,8 +325,29 @@ static void top2_pairs_i8(const int8_t* w, int* p0, int* p1) {
   top2_of_4(key, p0, p1);
 }
 
-/* W, Wout: [N][K] fp32 (may alias), K % 8 == 0.  mask (optional): N*K/8 bytes, bit p of byte c = sub-chunk p of chunk c kept. */
-int oracle_prune_4to8_pairs_f32(const float* W, float* Wout, uint8_t* mask, int64_t N, int64_t K) {
+/* The same pattern with one more constraint, chosen for hardware whose sparse matrix instructions know 2:4 only: of the
+ * two kept sub-chunks one lies in the first group of 4 and one in the second (4 of the 6 choices), so that the tensor
+ * obeys the pair-wise 4:8 pattern and the 2:4 pattern at once.  In each group of 4 the sub-chunk with the higher score
+ * is kept (ties: the lower index). */
+static void one_pair_per_group_f32(const float* w, int* p0, int* p1) {
+  int keep[2];
+  for (int h = 0; h < 2; ++h) {
+    uint32_t key[2];
+    for (int p = 0; p < 2; ++p) {
+      float sum = fabsf(w[4 * h + 2 * p]) + fabsf(w[4 * h + 2 * p + 1]);
+      uint32_t b;
+      memcpy(&b, &sum, 4);
+      key[p] = b & 0x7FFFFFFFu;
+    }
+    keep[h] = 2 * h + (key[1] > key[0] ? 1 : 0);
+  }
+  *p0 = keep[0];
+  *p1 = keep[1];
+}
+
+/* W, Wout: [N][K] fp32 (may alias), K % 8 == 0.  mask (optional): N*K/8 bytes, bit p of byte c = sub-chunk p of chunk c kept.
+ * one_per_group != 0: the constrained choice above. */
+int oracle_prune_4to8_pairs_f32(const float* W, float* Wout, uint8_t* mask, int one_per_group, int64_t N, int64_t K) {
   if (K % 8) return -1;
 #pragma omp parallel for schedule(static)
   for (int64_t n = 0; n < N; ++n)
@@ -334,7 +355,10 @@ int oracle_prune_4to8_pairs_f32(const float* W, float* Wout, uint8_t* mask, int6
       float v[8];
       for (int i = 0; i < 8; ++i) v[i] = W[n * K + 8 * c + i];
       int p0, p1;
-      top2_pairs_f32(v, &p0, &p1);
+      if (one_per_group)
+        one_pair_per_group_f32(v, &p0, &p1);
+      else
+        top2_pairs_f32(v, &p0, &p1);
       for (int i = 0; i < 8; ++i) Wout[n * K + 8 * c + i] = (i / 2 == p0 || i / 2 == p1) ? v[i] : 0.0f;
       if (mask) mask[n * (K / 8) + c] = (uint8_t)((1u << p0) | (1u << p1));
     }
@@ -421,6 +445,44 @@ int oracle_decompress_int4_pairs(const uint8_t* values, const uint8_t* meta, int
         W[n * K + 8 * c + 2 * p[j / 2] + (j & 1)] = (int8_t)code;
       }
     }
+  return 0;
+}
+
+/* A pair-wise 4:8 row in which no group of 4 holds two non-zero sub-chunks is also a 2:4 row: its INT8 compressed form
+ * (values [N][K/2] = the codes of the group's non-zero sub-chunk, sign-extended; metadata nibble per group of 4 = the
+ * two positions of that sub-chunk; a group without non-zeros takes its first sub-chunk) follows from the INT4 form
+ * chunk by chunk.  mismatches = groups of 4 with two non-zero sub-chunks (they keep the second one only). */
+int oracle_int4_pairs_to_sparse_int8(const uint8_t* values4, const uint8_t* meta4, int8_t* values8, uint8_t* meta8,
+                                     int32_t* mismatches, int64_t N, int64_t K) {
+  if (K % 8) return -1;
+  int64_t mrb4 = meta4_row_bytes(K), mrb8 = meta_row_bytes(K);
+  int32_t bad = 0;
+  memset(meta8, 0, (size_t)(N * mrb8));
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t c = 0; c < K / 8; ++c) {
+      uint8_t byte = meta4[n * mrb4 + c / 2];
+      uint8_t nib = (c & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xF);
+      int p[2] = {nib & 3, (nib >> 2) & 3};
+      int8_t dense[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int j = 0; j < 4; ++j) {
+        uint8_t b = values4[n * (K / 4) + 2 * c + j / 2];
+        int code = (j & 1) ? (b >> 4) : (b & 0xF);
+        if (code >= 8) code -= 16;
+        dense[2 * p[j / 2] + (j & 1)] = (int8_t)code;
+      }
+      for (int h = 0; h < 2; ++h) {
+        int64_t g = 2 * c + h;
+        int nz0 = dense[4 * h] != 0 || dense[4 * h + 1] != 0;
+        int nz1 = dense[4 * h + 2] != 0 || dense[4 * h + 3] != 0;
+        bad += nz0 && nz1;
+        int local = nz1 ? 1 : 0;
+        uint8_t nib8 = (uint8_t)((2 * local) | ((2 * local + 1) << 2));
+        meta8[n * mrb8 + g / 2] |= (uint8_t)((g & 1) ? (nib8 << 4) : nib8);
+        values8[n * (K / 2) + 2 * g] = dense[4 * h + 2 * local];
+        values8[n * (K / 2) + 2 * g + 1] = dense[4 * h + 2 * local + 1];
+      }
+    }
+  if (mismatches) *mismatches = bad;
   return 0;
 }
 

@@ -525,3 +525,50 @@ def test_int4_quantiser_and_round_trip_and_product():
     v2, m2, viol2 = oracle.compress_int4_pairs(Q2)
     assert viol2 == 0 and m2.shape == (N, 6) and (m2[:, 5] >> 4 == 0).all()
     assert np.array_equal(oracle.decompress_int4_pairs(v2, m2, 88), Q2)
+
+
+def test_int4_one_sub_chunk_per_group_is_both_patterns_and_decodes_to_the_2to4_form():
+    """The constrained choice (one kept sub-chunk in each group of 4): brute force over its 4 allowed combinations, the
+    result obeys the pair-wise 4:8 pattern and the 2:4 pattern, and its INT8 2:4 compressed form derived from the INT4
+    storage decompresses (with the 2:4 decompressor) to the same matrix as the INT4 decoder gives."""
+    rng = np.random.default_rng(43)
+    N, K = 32, 96
+    for W in (rng.standard_normal((N, K)).astype(np.float32), rng.integers(-3, 4, (N, K)).astype(np.float32)):
+        P, mask = oracle.prune_4to8_pairs(W, one_per_group=True)
+        for n in range(N):
+            for c in range(K // 8):
+                w = W[n, 8 * c:8 * c + 8]
+                score = [float(np.float32(abs(w[2 * p])) + np.float32(abs(w[2 * p + 1]))) for p in range(4)]
+                allowed = [(i, j) for i in (0, 1) for j in (2, 3)]
+                best = max(score[i] + score[j] for i, j in allowed)
+                i, j = min(pr for pr in allowed if score[pr[0]] + score[pr[1]] == best)
+                assert mask[n, c] == (1 << i) | (1 << j)
+        assert ((P.reshape(N, K // 4, 4) != 0).sum(axis=2) <= 2).all()             # 2:4
+        nzp = (P.reshape(N, K // 2, 2) != 0).any(axis=2).reshape(N, K // 8, 4)
+        assert (nzp.sum(axis=2) <= 2).all()                                         # pair-wise 4:8
+        # never better than the free choice, which keeps the two best of all four sub-chunks
+        F, _ = oracle.prune_4to8_pairs(W)
+        assert np.abs(P).sum() <= np.abs(F).sum() + 1e-3
+        Q, s = oracle.quantize_rows_int4(P)
+        v4, m4, viol = oracle.compress_int4_pairs(Q)
+        assert viol == 0 and oracle.compress(Q)[2] == 0
+        v8, m8, bad = oracle.int4_pairs_to_sparse_int8(v4, m4, K)
+        # (a chunk with codes that quantised to zero may carry other positions than the pruning chose: the matrix is the
+        # same, and the matrix is what both decoders must agree on)
+        D4 = oracle.decompress_int4_pairs(v4, m4, K)
+        assert bad == 0 and np.array_equal(oracle.decompress(v8, m8, K), D4) and np.array_equal(D4, Q)
+    # with codes that are all non-zero the positions are forced, so the shape test must pass everywhere
+    W = (rng.integers(1, 4, (N, K)) * rng.choice([-1, 1], (N, K))).astype(np.float32)
+    P, _ = oracle.prune_4to8_pairs(W, one_per_group=True)
+    Q = P.astype(np.int8)
+    v4, m4, viol = oracle.compress_int4_pairs(Q)
+    v8, m8, bad = oracle.int4_pairs_to_sparse_int8(v4, m4, K)
+    assert viol == 0 and bad == 0
+    assert np.array_equal(oracle.decompress(v8, m8, K), Q)
+    X = rng.integers(-127, 128, (9, K)).astype(np.int8)
+    assert np.array_equal(oracle.spgemm_int8(X, v8, m8), X.astype(np.int64) @ Q.astype(np.int64).T)
+    # a free-choice row with both kept sub-chunks in one group of 4 is reported; zeros inside a kept sub-chunk are fine
+    row = np.array([[1, 2, 3, 4, 0, 0, 0, 0, 0, 5, 0, 0, 0, 0, 0, 0]], np.int8)
+    v4, m4, _ = oracle.compress_int4_pairs(row)
+    v8, m8, bad = oracle.int4_pairs_to_sparse_int8(v4, m4, 16)
+    assert bad == 1 and np.array_equal(oracle.decompress(v8, m8, 16)[0, 8:], row[0, 8:])
