@@ -103,6 +103,10 @@ gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, 
  * is not a 2:4 pattern, so the product runs on the decoded INT8 operand (gpusq_gemm_int8_dense with the 4-bit scales);
  * the format's gain here is storage: 2.5 bits per weight.  K % 8 == 0 for all four calls (GPUSQ_ERR_SHAPE otherwise).
  *   gpusq_prune_4to8_pairs : W_in, W_out [N][K] fp32 (may alias); mask_out optional [N][K/8] bytes, bit p = sub-chunk p kept.
+ *       one_per_group != 0: of the two kept sub-chunks one lies in each group of 4 (the one with the larger |a| + |b|;
+ *       4 of the 6 choices): the tensor then obeys the pair-wise 4:8 pattern and the 2:4 pattern at once, and its INT4
+ *       storage can be turned into the INT8 2:4 operand of gpusq_spgemm_int8 (gpusq_int4_to_sparse_int8 + gpusq_pack):
+ *       4-bit storage at the speed of the 2:4 INT8 path.
  *   gpusq_quantize_rows_int4 : q = clamp(rint(x / s), -7, 7) in int8 containers, s = max|row| / 7 (1 for an all-zero
  *       row) written to scale[rows], or the caller's scales when scale_is_input != 0; X of dt GPUSQ_F32 or GPUSQ_F16.
  *   gpusq_compress_int4 : W [N][K] int8 holding 4-bit codes -> values [N][K/4] bytes (the 4 kept codes of chunk c in
@@ -110,8 +114,15 @@ gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, 
  *       [N][ceil(K/16)] bytes (chunk c in the low nibble of byte c/2 for even c, the high nibble for odd c; bits 0..1 =
  *       first kept sub-chunk, bits 2..3 = second, first < second).  Positions follow the selection rule applied to W
  *       itself.  violations (optional device int32): chunks with a dropped non-zero or a code outside -8..7.
- *   gpusq_decompress_int4 : the inverse, W [N][K] int8 zero-filled with the codes sign-extended. */
-gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int64_t N, int64_t K, void* stream);
+ *   gpusq_decompress_int4 : the inverse, W [N][K] int8 zero-filled with the codes sign-extended.
+ *   gpusq_int4_to_sparse_int8 : (values, meta) of gpusq_compress_int4 -> the 2:4 compressed INT8 form of gpusq_compress
+ *       (values8 [N][K/2] int8, meta8 [N][K/8] bytes), chunk by chunk without the dense matrix; a group of 4 keeps its
+ *       non-zero sub-chunk (its first one if it has none).  mismatches (optional device int32): groups of 4 with two
+ *       non-zero sub-chunks (not a 2:4 row; they keep the second sub-chunk only), 0 for tensors pruned with one_per_group. */
+gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int one_per_group, int64_t N, int64_t K,
+                                    void* stream);
+gpusq_status gpusq_int4_to_sparse_int8(const uint8_t* values4, const uint8_t* meta4, int8_t* values8, uint8_t* meta8,
+                                       int32_t* mismatches, int64_t N, int64_t K, void* stream);
 gpusq_status gpusq_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input,
                                       int64_t rows, int64_t cols, void* stream);
 gpusq_status gpusq_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N,

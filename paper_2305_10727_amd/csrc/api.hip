@@ -116,13 +116,14 @@ gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, 
   return launch_decompress(values, meta, W, dt, N, K, (hipStream_t)stream);
 }
 
-gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int64_t N, int64_t K, void* stream) {
+gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int one_per_group, int64_t N, int64_t K,
+                                    void* stream) {
   if (!W_in || !W_out) return GPUSQ_ERR_NULL;
   gpusq_status st = check_nk(N, K);
   if (st != GPUSQ_OK) return st;
   if (K % 8 != 0) return GPUSQ_ERR_SHAPE;
   if (!aligned16(W_in) || !aligned16(W_out)) return GPUSQ_ERR_ALIGN;
-  return launch_prune_pairs(W_in, W_out, mask_out, N, K, (hipStream_t)stream);
+  return launch_prune_pairs(W_in, W_out, mask_out, one_per_group != 0, N, K, (hipStream_t)stream);
 }
 
 gpusq_status gpusq_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input, int64_t rows,
@@ -142,6 +143,16 @@ gpusq_status gpusq_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta
   if (K % 8 != 0) return GPUSQ_ERR_SHAPE;
   if (!aligned16(W) || !aligned16(values) || !aligned16(meta)) return GPUSQ_ERR_ALIGN;
   return launch_compress_int4(W, values, meta, violations, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_int4_to_sparse_int8(const uint8_t* values4, const uint8_t* meta4, int8_t* values8, uint8_t* meta8,
+                                       int32_t* mismatches, int64_t N, int64_t K, void* stream) {
+  if (!values4 || !meta4 || !values8 || !meta8) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (K % 8 != 0) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(values4) || !aligned16(meta4) || !aligned16(values8) || !aligned16(meta8)) return GPUSQ_ERR_ALIGN;
+  return launch_int4_to_sparse_int8(values4, meta4, values8, meta8, mismatches, N, K, (hipStream_t)stream);
 }
 
 gpusq_status gpusq_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K, void* stream) {

@@ -167,7 +167,9 @@ gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* s
                              int64_t rows, int64_t cols, void* workspace, hipStream_t s);
 gpusq_status launch_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input, int64_t rows,
                                        int64_t cols, hipStream_t s);
-gpusq_status launch_prune_pairs(const float* Win, float* Wout, uint8_t* mask, int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_prune_pairs(const float* Win, float* Wout, uint8_t* mask, int one_per_group, int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_int4_to_sparse_int8(const uint8_t* values4, const uint8_t* meta4, int8_t* values8, uint8_t* meta8,
+                                        int32_t* mismatches, int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N, int64_t K,
                                   hipStream_t s);
 gpusq_status launch_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K, hipStream_t s);

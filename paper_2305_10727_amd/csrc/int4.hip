@@ -13,12 +13,15 @@ namespace gpusq {
 // scores are kept, ties to the lower index: the rule of the 2:4 pattern applied to the four sub-chunks.
 __device__ __forceinline__ unsigned pair_key(float a, float b) { return __float_as_uint(fabsf(a) + fabsf(b)) & 0x7FFFFFFFu; }
 
+// one_per_group: of the two kept sub-chunks one lies in each group of 4 (the better of its two; ties: the lower index),
+// which makes the row a 2:4 row as well: the form that the sparse matrix instructions of this hardware can consume.
 __global__ void __launch_bounds__(256) prune_pairs_f32_kernel(const float4* __restrict__ in, float4* __restrict__ out,
-                                                              uint8_t* __restrict__ mask, int64_t chunks) {
+                                                              uint8_t* __restrict__ mask, int one_per_group, int64_t chunks) {
   const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= chunks) return;
   const float4 lo = in[2 * c], hi = in[2 * c + 1];
-  const unsigned m = keep_mask_of_4(pair_key(lo.x, lo.y), pair_key(lo.z, lo.w), pair_key(hi.x, hi.y), pair_key(hi.z, hi.w));
+  const unsigned k0 = pair_key(lo.x, lo.y), k1 = pair_key(lo.z, lo.w), k2 = pair_key(hi.x, hi.y), k3 = pair_key(hi.z, hi.w);
+  const unsigned m = one_per_group ? ((k1 > k0 ? 2u : 1u) | (k3 > k2 ? 8u : 4u)) : keep_mask_of_4(k0, k1, k2, k3);
   float4 o0, o1;
   o0.x = (m & 1u) ? lo.x : 0.0f; o0.y = (m & 1u) ? lo.y : 0.0f;
   o0.z = (m & 2u) ? lo.z : 0.0f; o0.w = (m & 2u) ? lo.w : 0.0f;
@@ -29,9 +32,9 @@ __global__ void __launch_bounds__(256) prune_pairs_f32_kernel(const float4* __re
   if (mask) mask[c] = (uint8_t)m;
 }
 
-gpusq_status launch_prune_pairs(const float* Win, float* Wout, uint8_t* mask, int64_t N, int64_t K, hipStream_t s) {
+gpusq_status launch_prune_pairs(const float* Win, float* Wout, uint8_t* mask, int one_per_group, int64_t N, int64_t K, hipStream_t s) {
   const int64_t chunks = N * (K / 8);
-  prune_pairs_f32_kernel<<<(unsigned)ceil_div(chunks, 256), 256, 0, s>>>((const float4*)Win, (float4*)Wout, mask, chunks);
+  prune_pairs_f32_kernel<<<(unsigned)ceil_div(chunks, 256), 256, 0, s>>>((const float4*)Win, (float4*)Wout, mask, one_per_group, chunks);
   return check_launch();
 }
 
@@ -125,6 +128,53 @@ __global__ void __launch_bounds__(256) decompress_int4_kernel(const uint8_t* __r
       *(uint2*)(W + n * K + 8 * c) = uint2{(unsigned)chunk, (unsigned)(chunk >> 32)};
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------------------- to 2:4
+// INT4 storage -> the INT8 2:4 compressed form (values [N][K/2], one metadata byte per chunk = two groups of 4), for rows
+// in which no group of 4 holds two non-zero sub-chunks (what pruning with one_per_group produces).  A group keeps its
+// non-zero sub-chunk (the first one if it has none); a group with two non-zero sub-chunks keeps the second and is counted.
+__global__ void __launch_bounds__(256) int4_to_sparse_int8_kernel(const uint8_t* __restrict__ values4, const uint8_t* __restrict__ meta4,
+                                                                  int8_t* __restrict__ values8, uint8_t* __restrict__ meta8,
+                                                                  int32_t* __restrict__ mismatches, int64_t N, int64_t K) {
+  const int64_t chunks_per_row = K / 8;
+  const int64_t mrb4 = (chunks_per_row + 1) / 2;
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int bad = 0;
+  if (id < N * chunks_per_row) {
+    const int64_t n = id / chunks_per_row, c = id % chunks_per_row;
+    const unsigned nib = (meta4[n * mrb4 + (c >> 1)] >> (4 * (c & 1))) & 0xFu;
+    const unsigned p0 = nib & 3u, p1 = nib >> 2;
+    const unsigned v = *(const uint16_t*)(values4 + n * (K / 4) + 2 * c);
+    auto byte_of = [](unsigned nibble) { return (unsigned)((int)(nibble << 28) >> 28) & 0xFFu; };
+    const uint64_t first = byte_of(v & 0xFu) | (byte_of((v >> 4) & 0xFu) << 8);
+    const uint64_t second = byte_of((v >> 8) & 0xFu) | (byte_of((v >> 12) & 0xFu) << 8);
+    const uint64_t chunk = (first << (16 * p0)) | (second << (16 * p1));  // the 8 dense codes, one byte each
+    unsigned vals = 0, meta = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const unsigned group = (unsigned)(chunk >> (32 * h));
+      const unsigned pair0 = group & 0xFFFFu, pair1 = group >> 16;
+      bad += (int)(pair0 != 0 && pair1 != 0);
+      const unsigned local = pair1 != 0 ? 1u : 0u;
+      vals |= (local ? pair1 : pair0) << (16 * h);
+      meta |= ((2 * local) | ((2 * local + 1) << 2)) << (4 * h);
+    }
+    *(uint32_t*)(values8 + n * (K / 2) + 4 * c) = vals;
+    meta8[n * chunks_per_row + c] = (uint8_t)meta;
+  }
+  if (mismatches) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) bad += __shfl_xor(bad, o, 64);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(mismatches, bad);
+  }
+}
+
+gpusq_status launch_int4_to_sparse_int8(const uint8_t* values4, const uint8_t* meta4, int8_t* values8, uint8_t* meta8,
+                                        int32_t* mismatches, int64_t N, int64_t K, hipStream_t s) {
+  if (mismatches) clear_i32_kernel<<<1, 1, 0, s>>>(mismatches);
+  int4_to_sparse_int8_kernel<<<(unsigned)ceil_div(N * (K / 8), 256), 256, 0, s>>>(values4, meta4, values8, meta8, mismatches, N, K);
+  return check_launch();
 }
 
 gpusq_status launch_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K, hipStream_t s) {

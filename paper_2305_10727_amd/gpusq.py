@@ -25,6 +25,7 @@ EXPORTS = [
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
     "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
+    "gpusq_int4_to_sparse_int8",
 ]
 
 
@@ -72,7 +73,8 @@ def lib():
         L.gpusq_patch_embed16_int8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
-        L.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_int4_to_sparse_int8.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp]
         L.gpusq_quantize_rows_int4.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
         L.gpusq_compress_int4.argtypes = [vp, vp, vp, vp, i64, i64, vp]
         L.gpusq_decompress_int4.argtypes = [vp, vp, vp, i64, i64, vp]
@@ -160,13 +162,25 @@ def decompress(values, meta, K):
     return W
 
 
-def prune_4to8_pairs(W, want_mask=False):
+def prune_4to8_pairs(W, want_mask=False, one_per_group=False):
     """gpusq_prune_4to8_pairs: W [N,K] fp32 -> pruned copy (and the keep mask [N,K/8] uint8)"""
     N, K = W.shape
     out = torch.empty_like(W)
     mask = torch.empty((N, K // 8), dtype=torch.uint8, device=W.device) if want_mask else None
-    _check(lib().gpusq_prune_4to8_pairs(_ptr(W), _ptr(out), _ptr(mask), N, K, _stream()), "gpusq_prune_4to8_pairs")
+    _check(lib().gpusq_prune_4to8_pairs(_ptr(W), _ptr(out), _ptr(mask), int(one_per_group), N, K, _stream()),
+           "gpusq_prune_4to8_pairs")
     return (out, mask) if want_mask else out
+
+
+def int4_to_sparse_int8(values4, meta4, K, want_mismatches=False):
+    """gpusq_int4_to_sparse_int8: INT4 pair-wise storage -> (values [N,K/2] int8, meta [N,K/8] uint8[, mismatches int32[1]])"""
+    N = values4.shape[0]
+    values8 = torch.empty((N, K // 2), dtype=torch.int8, device=values4.device)
+    meta8 = torch.empty((N, K // 8), dtype=torch.uint8, device=values4.device)
+    bad = torch.empty(1, dtype=torch.int32, device=values4.device) if want_mismatches else None
+    _check(lib().gpusq_int4_to_sparse_int8(_ptr(values4), _ptr(meta4), _ptr(values8), _ptr(meta8), _ptr(bad), N, K, _stream()),
+           "gpusq_int4_to_sparse_int8")
+    return (values8, meta8, bad) if want_mismatches else (values8, meta8)
 
 
 def quantize_rows_int4(X, scale=None):

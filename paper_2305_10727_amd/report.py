@@ -161,10 +161,12 @@ def main():
         del blk, lins
         torch.cuda.empty_cache()
     lines += ["", "INT4 weights in the pair-wise 4:8 format (4 kept 4-bit codes + two 2-bit indices per chunk of 8 = 2.5 bits per weight); the "
-              "product runs on the decoded INT8 operand with the dense kernel.  Weight-side kernels (us, and GB/s over the bytes each must "
+              "product runs on the decoded INT8 operand with the dense kernel, or, for tensors pruned with one kept sub-chunk per group of 4 (pair-wise "
+              "4:8 and 2:4 at once), on the sparse kernel after a direct conversion of the INT4 storage into its 2:4 INT8 operand.  Weight-side kernels (us, and GB/s over the bytes each must "
               "move), then one layer at M rows: decode + dense INT8 GEMM against the 2:4 INT8 sparse GEMM:", "",
               "| layer | N | K | prune us (GB/s) | quantise us (GB/s) | compress us (GB/s) | decode us (GB/s) | compressed bytes | M | "
-              "decode + dense GEMM us | 2:4 INT8 sparse GEMM us |", "|---|---|---|---|---|---|---|---|---|---|---|"]
+              "decode + dense GEMM us | 2:4 INT8 sparse GEMM us | one kept sub-chunk per group of 4: INT4 storage -> 2:4 form us | pack us | "
+              "sparse GEMM on it us |", "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for layer, N, K, M in [("ViT-B fc1", 3072, 768, 12608), ("ViT-B fc2", 768, 3072, 12608), ("ViT-H fc1", 5120, 1280, 65792)]:
         W = torch.randn(N, K, device=dev) * 0.02
         bias = torch.randn(N, device=dev) * 0.01
@@ -174,7 +176,7 @@ def main():
         D = G.decompress_int4(v, m, K)
         L, st = G.lib(), G._stream
         from .pipeline import _p
-        t_p = _time([lambda: L.gpusq_prune_4to8_pairs(_p(W), _p(P), None, N, K, st())], a.iters)
+        t_p = _time([lambda: L.gpusq_prune_4to8_pairs(_p(W), _p(P), None, 0, N, K, st())], a.iters)
         t_q = _time([lambda: L.gpusq_quantize_rows_int4(_p(P), G.F32, _p(Q), _p(s4), 0, N, K, st())], a.iters)
         t_c = _time([lambda: L.gpusq_compress_int4(_p(Q), _p(v), _p(m), None, N, K, st())], a.iters)
         t_d = _time([lambda: L.gpusq_decompress_int4(_p(v), _p(m), _p(D), N, K, st())], a.iters)
@@ -189,10 +191,19 @@ def main():
             L.gpusq_decompress_int4(_p(v), _p(m), _p(D), N, K, st())
             L.gpusq_gemm_int8_dense(_p(lin.Xq), _p(D), _p(lin.act_scale), _p(s4), _p(bias), _p(lin.Y), G.F16, None, M, N, K, G.EPI_BIAS, st())
         t_int4 = _time([int4_layer], a.iters)
+        # the 2:4-compatible variant: the INT4 storage becomes the sparse kernel's operand
+        Q1, s41 = G.quantize_rows_int4(G.prune_4to8_pairs(W, one_per_group=True))
+        v1, m1 = G.compress_int4(Q1)
+        v8, m8 = G.int4_to_sparse_int8(v1, m1, K)
+        packed = G.pack(v8, m8, K)
+        t_24 = _time([lambda: L.gpusq_int4_to_sparse_int8(_p(v1), _p(m1), _p(v8), _p(m8), None, N, K, st())], a.iters)
+        t_pk = _time([lambda: L.gpusq_pack(_p(v8), _p(m8), _p(packed), G.I8, N, K, st())], a.iters)
+        t_sp4 = _time([lambda: L.gpusq_spgemm_int8(_p(lin.Xq), _p(packed), _p(lin.act_scale), _p(s41), _p(bias), _p(lin.Y), G.F16, None,
+                                                   M, N, K, G.EPI_BIAS, st())], a.iters)
         gbs = lambda nbytes, us: nbytes / us / 1e3
-        lines.append("| %s | %d | %d | %.1f (%.0f) | %.1f (%.0f) | %.1f (%.0f) | %.1f (%.0f) | %d | %d | %.1f | %.1f |" % (
+        lines.append("| %s | %d | %d | %.1f (%.0f) | %.1f (%.0f) | %.1f (%.0f) | %.1f (%.0f) | %d | %d | %.1f | %.1f | %.1f | %.1f | %.1f |" % (
             layer, N, K, t_p, gbs(8 * N * K, t_p), t_q, gbs(9 * N * K, t_q), t_c, gbs(N * K + comp, t_c), t_d, gbs(N * K + comp, t_d),
-            comp, M, t_int4, t_sparse))
+            comp, M, t_int4, t_sparse, t_24, t_pk, t_sp4))
         print(lines[-1], flush=True)
         del lin
         torch.cuda.empty_cache()

@@ -86,10 +86,14 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_patch_embed16_int8(good, good, good, good, None, good, 1, 3, 32, 32, 64, 0, None) == ERR_UNSUPPORTED   # too small
     lib.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
     assert lib.gpusq_patch_embed16_fp16(good, good, None, good, 4, 3, 224, 224, 768, 1, None) == ERR_NULL                  # bias flag
-    lib.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, i64, i64, vp]
-    assert lib.gpusq_prune_4to8_pairs(good, None, None, 4, 8, None) == ERR_NULL
-    assert lib.gpusq_prune_4to8_pairs(good, good, None, 4, 12, None) == ERR_SHAPE   # K % 8
-    assert lib.gpusq_prune_4to8_pairs(odd, good, None, 4, 8, None) == ERR_ALIGN
+    lib.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+    assert lib.gpusq_prune_4to8_pairs(good, None, None, 0, 4, 8, None) == ERR_NULL
+    assert lib.gpusq_prune_4to8_pairs(good, good, None, 1, 4, 12, None) == ERR_SHAPE   # K % 8
+    assert lib.gpusq_prune_4to8_pairs(odd, good, None, 0, 4, 8, None) == ERR_ALIGN
+    lib.gpusq_int4_to_sparse_int8.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp]
+    assert lib.gpusq_int4_to_sparse_int8(good, good, good, None, None, 4, 8, None) == ERR_NULL
+    assert lib.gpusq_int4_to_sparse_int8(good, good, good, good, None, 4, 12, None) == ERR_SHAPE
+    assert lib.gpusq_int4_to_sparse_int8(good, good, odd, good, None, 4, 8, None) == ERR_ALIGN
     lib.gpusq_quantize_rows_int4.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
     assert lib.gpusq_quantize_rows_int4(good, 0, good, None, 0, 4, 8, None) == ERR_NULL
     assert lib.gpusq_quantize_rows_int4(good, 2, good, good, 0, 4, 8, None) == ERR_UNSUPPORTED

@@ -738,3 +738,45 @@ def test_int4_pairwise_path_bit_exact(g, N, K, grid):
         assert np.array_equal(host(g.gemm_int8_dense(Xq_g, D_g, out_dtype=torch.int32)), acc_o)
         y = host(g.gemm_int8_dense(Xq_g, D_g, act_scale=s_a_g, w_scale=s_g, bias=dev(bias)))
         assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(acc_o, s_a, s_o, bias)["y16"].view(np.uint16))
+
+
+@pytest.mark.parametrize("N,K,grid", [(4, 8, True), (64, 192, False), (100, 136, True), (768, 768, False), (3072, 768, False)])
+def test_int4_storage_on_the_sparse_int8_path(g, N, K, grid):
+    """Pair-wise 4:8 pruning with one kept sub-chunk per group of 4 (pair-wise 4:8 and 2:4 at once): INT4 storage, turned
+    into the 2:4 INT8 operand without the dense matrix, then the sparse GEMM; every step against the oracle."""
+    if grid:
+        W = synth.small_integers((N, K), -3, 3, seed=N + K, ids=(70,)).astype(np.float32)
+    else:
+        W = synth.weights(N, K, seed=N + K, ids=(70,))
+    P_o, mask_o = oracle.prune_4to8_pairs(W, one_per_group=True)
+    P_g, mask_g = g.prune_4to8_pairs(dev(W), want_mask=True, one_per_group=True)
+    assert np.array_equal(host(P_g).view(np.uint32), P_o.view(np.uint32)) and np.array_equal(host(mask_g), mask_o)
+    Q_o, s_o = oracle.quantize_rows_int4(P_o)
+    Q_g, s_g = g.quantize_rows_int4(P_g)
+    v4_o, m4_o, viol = oracle.compress_int4_pairs(Q_o)
+    v4_g, m4_g = g.compress_int4(Q_g)
+    assert viol == 0 and np.array_equal(host(v4_g), v4_o) and np.array_equal(host(m4_g), m4_o)
+    v8_o, m8_o, bad_o = oracle.int4_pairs_to_sparse_int8(v4_o, m4_o, K)
+    v8_g, m8_g, bad_g = g.int4_to_sparse_int8(v4_g, m4_g, K, want_mismatches=True)
+    assert bad_o == 0 and int(host(bad_g)[0]) == 0
+    assert np.array_equal(host(v8_g), v8_o) and np.array_equal(host(m8_g), m8_o)
+    assert np.array_equal(host(g.decompress(v8_g, m8_g, K)), Q_o)
+    # a free-choice tensor has groups with two kept sub-chunks: both sides count the same ones and keep the same values
+    F_o, _ = oracle.prune_4to8_pairs(W)
+    Fq_o, _ = oracle.quantize_rows_int4(F_o)
+    fv_o, fm_o, _ = oracle.compress_int4_pairs(Fq_o)
+    fv8_o, fm8_o, fbad_o = oracle.int4_pairs_to_sparse_int8(fv_o, fm_o, K)
+    fv8_g, fm8_g, fbad_g = g.int4_to_sparse_int8(dev(fv_o), dev(fm_o), K, want_mismatches=True)
+    assert int(host(fbad_g)[0]) == fbad_o and np.array_equal(host(fv8_g), fv8_o) and np.array_equal(host(fm8_g), fm8_o)
+    if K % 16 == 0 and N % 4 == 0:
+        M = 300
+        X = synth.activations(M, K, "normal_clip4", seed=N + K, ids=(71,))
+        bias = synth.bias(N, seed=N + K, ids=(71,))
+        Xq_o, s_a = oracle.quantize_tensor_int8(X)
+        Xq_g, s_a_g = g.quantize_int8(dev(X), g.PER_TENSOR)
+        acc_o = oracle.spgemm_int8(Xq_o, v8_o, m8_o)
+        assert np.array_equal(acc_o, oracle.gemm_int8_dense(Xq_o, Q_o))
+        packed = g.pack(v8_g, m8_g, K)
+        assert np.array_equal(host(g.spgemm_int8(Xq_g, packed, N, out_dtype=torch.int32)), acc_o)
+        y = host(g.spgemm_int8(Xq_g, packed, N, act_scale=s_a_g, w_scale=s_g, bias=dev(bias)))
+        assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(acc_o, s_a, s_o, bias)["y16"].view(np.uint16))
