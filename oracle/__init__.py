@@ -95,6 +95,15 @@ def prune_2to4(W):
     return out, mask
 
 
+def prune_n_of_m(W, n, m):
+    """W [N,K] float32, K % m == 0: keep the n largest magnitudes of every m contiguous elements of a row"""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    out = np.empty_like(W)
+    assert lib().oracle_prune_n_of_m_f32(_p(W), _p(out), int(n), int(m), _i64(N), _i64(K)) == 0
+    return out
+
+
 # ---------------------------------------------------------------- a2 / a4 quantise
 def quantize_rows_int8(X, scale=None):
     X = _c(X, np.float32)

@@ -153,6 +153,35 @@ int oracle_prune_2to4_f16(const uint16_t* W, uint16_t* Wout, uint8_t* mask, int6
   return 0;
 }
 
+/* Other n:m patterns [Sec. 5, the limitation paragraph names 1:4 and 2:16 as patterns a later hardware generation might
+ * support]: the n largest magnitudes of every m contiguous elements of a row are kept (ties: the lower index), the
+ * others become +0.  n = 2, m = 4 is oracle_prune_2to4_f32.  1:4 and 2:16 tensors are 2:4 tensors as well. */
+int oracle_prune_n_of_m_f32(const float* W, float* Wout, int n_keep, int m, int64_t N, int64_t K) {
+  if (m < 2 || m > 64 || n_keep < 1 || n_keep >= m || K % m) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < N; ++r)
+    for (int64_t g = 0; g < K / m; ++g) {
+      float v[64];
+      uint32_t key[64];
+      int kept[64];
+      for (int i = 0; i < m; ++i) {
+        v[i] = W[r * K + g * m + i];
+        uint32_t b;
+        memcpy(&b, &v[i], 4);
+        key[i] = b & 0x7FFFFFFFu;
+        kept[i] = 0;
+      }
+      for (int round = 0; round < n_keep; ++round) { /* pick the largest remaining, lowest index first among equals */
+        int best = -1;
+        for (int i = 0; i < m; ++i)
+          if (!kept[i] && (best < 0 || key[i] > key[best])) best = i;
+        kept[best] = 1;
+      }
+      for (int i = 0; i < m; ++i) Wout[r * K + g * m + i] = kept[i] ? v[i] : 0.0f;
+    }
+  return 0;
+}
+
 /* ------------------------------------------------------------------ a2 / a4: symmetric INT8 quantisation */
 
 static int8_t quantize_one(float x, float s) {

@@ -572,3 +572,24 @@ def test_int4_one_sub_chunk_per_group_is_both_patterns_and_decodes_to_the_2to4_f
     v4, m4, _ = oracle.compress_int4_pairs(row)
     v8, m8, bad = oracle.int4_pairs_to_sparse_int8(v4, m4, 16)
     assert bad == 1 and np.array_equal(oracle.decompress(v8, m8, 16)[0, 8:], row[0, 8:])
+
+
+def test_n_of_m_pruning_against_sorting_and_the_2to4_rule():
+    """n:m patterns of the limitation paragraph (1:4, 2:16) and a few more: a stable argsort written here picks the same
+    elements; 2:4 is the original rule; 1:4 and 2:16 tensors obey 2:4 (the compressor reports no violation)."""
+    rng = np.random.default_rng(44)
+    N, K = 16, 64
+    for W in (rng.standard_normal((N, K)).astype(np.float32), rng.integers(-2, 3, (N, K)).astype(np.float32)):
+        for n, m in ((1, 4), (2, 16), (2, 4), (4, 8), (1, 2), (3, 16)):
+            P = oracle.prune_n_of_m(W, n, m)
+            G = W.reshape(N, K // m, m)
+            order = np.argsort(-np.abs(G), axis=2, kind="stable")   # descending magnitude, lower index first among equals
+            keep = np.zeros(G.shape, bool)
+            np.put_along_axis(keep, order[:, :, :n], True, axis=2)
+            assert np.array_equal(P, np.where(keep, G, np.float32(0)).reshape(N, K))
+            assert ((P.reshape(N, K // m, m) != 0).sum(axis=2) <= n).all()
+        assert np.array_equal(oracle.prune_n_of_m(W, 2, 4), oracle.prune_2to4(W)[0])
+        for n, m in ((1, 4), (2, 16)):
+            P = oracle.prune_n_of_m(W, n, m)
+            assert oracle.compress(P.astype(np.float16))[2] == 0
+            assert np.array_equal(oracle.prune_2to4(P)[0], P)      # already 2:4: pruning again changes nothing
