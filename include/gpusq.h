@@ -95,6 +95,13 @@ gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t*
 gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt,
                               int64_t N, int64_t K, void* stream);
 
+/* ---- other n:m patterns [Sec. 5, limitation paragraph: a hardware generation might support 1:4 or 2:16 instead]: the
+ * n largest magnitudes of every m contiguous elements of a row are kept (ties: the lower index), the rest become +0.
+ * W_in, W_out [N][K] fp32 (may alias); m = 4, 8 or 16 (GPUSQ_ERR_UNSUPPORTED otherwise), 1 <= n < m, K % m == 0
+ * (GPUSQ_ERR_SHAPE otherwise).  n = 2, m = 4 gives what gpusq_prune_2to4 gives; 1:4 and 2:16 tensors are 2:4 tensors as
+ * well and go through gpusq_compress / gpusq_spgemm_* unchanged (with half or more of the kept slots holding zeros). */
+gpusq_status gpusq_prune_n_of_m(const float* W_in, float* W_out, int n, int m, int64_t N, int64_t K, void* stream);
+
 /* ---- INT4 operands: the pair-wise 4:8 pattern [Sec. 3.1, the paragraph on the INT4 instruction: every chunk of 8
  * adjacent elements of a row holds four zeros and four non-zeros, clustered in 2-wide sub-chunks that are all zero or
  * all non-zero; the compressed row stores the four non-zero values and two 2-bit indices with the positions of the two

@@ -116,6 +116,16 @@ gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, 
   return launch_decompress(values, meta, W, dt, N, K, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_prune_n_of_m(const float* W_in, float* W_out, int n, int m, int64_t N, int64_t K, void* stream) {
+  if (!W_in || !W_out) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (m != 4 && m != 8 && m != 16) return GPUSQ_ERR_UNSUPPORTED;
+  if (n < 1 || n >= m || K % m != 0) return GPUSQ_ERR_SHAPE;
+  if (!aligned16(W_in) || !aligned16(W_out)) return GPUSQ_ERR_ALIGN;
+  return launch_prune_n_of_m(W_in, W_out, n, m, N, K, (hipStream_t)stream);
+}
+
 gpusq_status gpusq_prune_4to8_pairs(const float* W_in, float* W_out, uint8_t* mask_out, int one_per_group, int64_t N, int64_t K,
                                     void* stream) {
   if (!W_in || !W_out) return GPUSQ_ERR_NULL;

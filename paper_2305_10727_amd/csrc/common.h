@@ -160,6 +160,7 @@ gpusq_status launch_dense(bool is_i8, const GemmArgs& a, hipStream_t s);
 gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t* out);
 
 gpusq_status launch_prune(const void* Win, void* Wout, uint8_t* mask, gpusq_dtype dt, int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_prune_n_of_m(const float* Win, float* Wout, int n_keep, int m, int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_cast_f16(const float* in, void* out, int64_t n, hipStream_t s);
 gpusq_status launch_im2col_patches(const void* img, void* X, gpusq_dtype dt, int64_t B, int64_t C, int64_t H, int64_t W, int64_t P,
                                    int64_t K_pad, hipStream_t s);

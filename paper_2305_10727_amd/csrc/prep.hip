@@ -176,6 +176,46 @@ gpusq_status launch_cast_f16(const float* in, void* out, int64_t n, hipStream_t 
   return check_launch();
 }
 
+// n:m pruning [Sec. 5, limitation paragraph: 1:4, 2:16]: the n largest magnitudes of every M contiguous elements are kept
+// (ties: the lower index).  One thread per group; an element is kept iff fewer than n elements beat it.
+template <int M>
+__global__ void __launch_bounds__(256) prune_n_of_m_kernel(const float4* __restrict__ in, float4* __restrict__ out, int n_keep,
+                                                           int64_t groups) {
+  const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= groups) return;
+  float v[M];
+#pragma unroll
+  for (int q = 0; q < M / 4; ++q) {
+    const float4 w = in[g * (M / 4) + q];
+    v[4 * q] = w.x; v[4 * q + 1] = w.y; v[4 * q + 2] = w.z; v[4 * q + 3] = w.w;
+  }
+  unsigned key[M];
+#pragma unroll
+  for (int i = 0; i < M; ++i) key[i] = __float_as_uint(v[i]) & 0x7FFFFFFFu;
+#pragma unroll
+  for (int i = 0; i < M; ++i) {
+    int beaten = 0;
+#pragma unroll
+    for (int j = 0; j < M; ++j)
+      if (j != i) beaten += (j < i) ? (key[j] >= key[i]) : (key[j] > key[i]);
+    if (beaten >= n_keep) v[i] = 0.0f;
+  }
+#pragma unroll
+  for (int q = 0; q < M / 4; ++q) out[g * (M / 4) + q] = float4{v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+}
+
+gpusq_status launch_prune_n_of_m(const float* Win, float* Wout, int n_keep, int m, int64_t N, int64_t K, hipStream_t s) {
+  const int64_t groups = N * (K / m);
+  const unsigned blocks = (unsigned)ceil_div(groups, 256);
+  if (m == 4)
+    prune_n_of_m_kernel<4><<<blocks, 256, 0, s>>>((const float4*)Win, (float4*)Wout, n_keep, groups);
+  else if (m == 8)
+    prune_n_of_m_kernel<8><<<blocks, 256, 0, s>>>((const float4*)Win, (float4*)Wout, n_keep, groups);
+  else
+    prune_n_of_m_kernel<16><<<blocks, 256, 0, s>>>((const float4*)Win, (float4*)Wout, n_keep, groups);
+  return check_launch();
+}
+
 // ------------------------------------------------------------------------------------------------------------ quantise
 __device__ __forceinline__ float load_as_f32(const float* p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float load_as_f32(const _Float16* p, int64_t i) { return (float)p[i]; }

@@ -25,7 +25,7 @@ EXPORTS = [
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
     "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
-    "gpusq_int4_to_sparse_int8",
+    "gpusq_int4_to_sparse_int8", "gpusq_prune_n_of_m",
 ]
 
 
@@ -74,6 +74,7 @@ def lib():
         L.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
         L.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_prune_n_of_m.argtypes = [vp, vp, ci, ci, i64, i64, vp]
         L.gpusq_int4_to_sparse_int8.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp]
         L.gpusq_quantize_rows_int4.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
         L.gpusq_compress_int4.argtypes = [vp, vp, vp, vp, i64, i64, vp]
@@ -160,6 +161,14 @@ def decompress(values, meta, K):
     _check(lib().gpusq_decompress(_ptr(values), _ptr(meta), _ptr(W), _TORCH_DT[values.dtype], N, K, _stream()),
            "gpusq_decompress")
     return W
+
+
+def prune_n_of_m(W, n, m):
+    """gpusq_prune_n_of_m: W [N,K] fp32 -> copy with the n largest magnitudes of every m contiguous elements kept"""
+    N, K = W.shape
+    out = torch.empty_like(W)
+    _check(lib().gpusq_prune_n_of_m(_ptr(W), _ptr(out), n, m, N, K, _stream()), "gpusq_prune_n_of_m")
+    return out
 
 
 def prune_4to8_pairs(W, want_mask=False, one_per_group=False):

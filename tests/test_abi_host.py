@@ -86,6 +86,11 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_patch_embed16_int8(good, good, good, good, None, good, 1, 3, 32, 32, 64, 0, None) == ERR_UNSUPPORTED   # too small
     lib.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
     assert lib.gpusq_patch_embed16_fp16(good, good, None, good, 4, 3, 224, 224, 768, 1, None) == ERR_NULL                  # bias flag
+    lib.gpusq_prune_n_of_m.argtypes = [vp, vp, ci, ci, i64, i64, vp]
+    assert lib.gpusq_prune_n_of_m(good, None, 1, 4, 4, 16, None) == ERR_NULL
+    assert lib.gpusq_prune_n_of_m(good, good, 1, 5, 4, 20, None) == ERR_UNSUPPORTED   # m
+    assert lib.gpusq_prune_n_of_m(good, good, 4, 4, 4, 16, None) == ERR_SHAPE         # n < m
+    assert lib.gpusq_prune_n_of_m(good, good, 2, 16, 4, 24, None) == ERR_SHAPE        # K % m
     lib.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, ci, i64, i64, vp]
     assert lib.gpusq_prune_4to8_pairs(good, None, None, 0, 4, 8, None) == ERR_NULL
     assert lib.gpusq_prune_4to8_pairs(good, good, None, 1, 4, 12, None) == ERR_SHAPE   # K % 8

@@ -780,3 +780,21 @@ def test_int4_storage_on_the_sparse_int8_path(g, N, K, grid):
         assert np.array_equal(host(g.spgemm_int8(Xq_g, packed, N, out_dtype=torch.int32)), acc_o)
         y = host(g.spgemm_int8(Xq_g, packed, N, act_scale=s_a_g, w_scale=s_g, bias=dev(bias)))
         assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(acc_o, s_a, s_o, bias)["y16"].view(np.uint16))
+
+
+@pytest.mark.parametrize("n,m", [(1, 4), (2, 16), (2, 4), (3, 8), (15, 16)])
+def test_n_of_m_pruning_bit_exact(g, n, m):
+    """the n:m patterns of the limitation paragraph (1:4, 2:16) and others, incl. a tie-heavy grid; 1:4 and 2:16 tensors
+    run through the 2:4 compressor and the sparse GEMM unchanged"""
+    N, K = 260, 1264 if m != 16 else 1280
+    for W in (synth.weights(N, K, seed=n * 100 + m, ids=(80,)), synth.small_integers((N, K), -2, 2, seed=m, ids=(81,)).astype(np.float32)):
+        P_o = oracle.prune_n_of_m(W, n, m)
+        P_g = g.prune_n_of_m(dev(W), n, m)
+        assert np.array_equal(host(P_g).view(np.uint32), P_o.view(np.uint32))
+    if (n, m) in ((1, 4), (2, 16)):
+        Wq, s_w = g.quantize_int8(P_g, g.PER_ROW)
+        vals, meta, viol = g.compress(Wq, want_violations=True)
+        assert int(host(viol)[0]) == 0
+        X = synth.small_integers((100, K), -100, 100, seed=5, ids=(82,)).astype(np.int8)
+        acc = host(g.spgemm_int8(dev(X), g.pack(vals, meta, K), N, out_dtype=torch.int32))
+        assert np.array_equal(acc, oracle.gemm_int8_dense(X, oracle.quantize_rows_int8(P_o)[0]))
