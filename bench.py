@@ -75,15 +75,19 @@ def main():
     eff_ops = 2.0 * M * N * K
 
     # ---- the timed region: W warm-up steps, then exactly K steps of the whole path --------------------------------
+    lin.prepare_weights(W)  # once with every optional output: the dense twin below reads the masked INT8 weights
     for _ in range(args.warmup):
-        lin.full_path(W, Xh, bias)
+        lin.prepare_weights(W, intermediates=False)
+        lin.forward(Xh, bias)
     gemm_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
     for i in range(args.steps):
-        lin.prepare_weights(W)
+        # prune -> quantise -> compress -> pack in one launch; it writes the packed operand and the scales, the
+        # intermediate tensors of the unfused chain are not materialised
+        lin.prepare_weights(W, intermediates=False)
         lin.quantize_activations(Xh)
         gemm_ev[i][0].record()
         lin.gemm(Xh, bias)
@@ -108,7 +112,8 @@ def main():
     t_gemm = time_kernel(lambda: lin.gemm(Xh, bias), it, torch)
     t_dense = time_kernel(lambda: lin.gemm_dense(Xh, bias), it, torch)
     t_qact = time_kernel(lambda: lin.quantize_activations(Xh), it, torch)
-    t_wprep = time_kernel(lambda: lin.prepare_weights(W), it, torch)
+    t_wprep = time_kernel(lambda: lin.prepare_weights(W, intermediates=False), it, torch)
+    t_wprep_all = time_kernel(lambda: lin.prepare_weights(W), it, torch)
     lin16 = SparseLinear(M, K, N, "fp16", gelu=gelu, bias=True)
     lin16.prepare_weights(W)
     t_gemm16 = time_kernel(lambda: lin16.gemm(Xh, bias), it, torch)
@@ -136,7 +141,7 @@ def main():
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "c1: ViT-Base MLP fc1, batch 64 (M=12608, K=768, N=3072), 2:4 INT8 per-channel weights, "
                                "per-tensor INT8 activations from fp16, fused bias+GELU, fp16 output",
-                   "M": M, "K": K, "N": N, "step": "prune+quantize_w+compress+pack+quantize_act+spgemm_int8"},
+                   "M": M, "K": K, "N": N, "step": "prune+quantize_w+compress+pack (one fused launch, intermediates not written)+quantize_act+spgemm_int8"},
         "wall_ms_per_step": wall_ms / args.steps,
         "roofline": roofline,
         "kernels": {
@@ -149,7 +154,7 @@ def main():
             "spgemm_fp16_frac_of_sparse_peak_5030": eff_ops / (t_gemm16 * 1e-3) / 1e12 / 5030.0,
             "gemm_fp16_dense_ms": t_dense16, "gemm_fp16_dense_tflops": eff_ops / (t_dense16 * 1e-3) / 1e12,
             "fp16_speedup_vs_dense": t_dense16 / t_gemm16,
-            "quantize_act_ms": t_qact, "weight_prep_ms": t_wprep,
+            "quantize_act_ms": t_qact, "weight_prep_ms": t_wprep, "weight_prep_with_intermediate_outputs_ms": t_wprep_all,
         },
         "paper_context": "A100 INT8 2:4 vs FP32 dense end-to-end: 1.26-1.47x latency, 2.40-2.60x throughput (Table 2); "
                          "no GEMM-level figure is published",

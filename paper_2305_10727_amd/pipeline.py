@@ -42,14 +42,17 @@ class SparseLinear:
         self.x_dtype = x_dtype
 
     # ---- weight side (a1, a2, a3 + packing) -------------------------------------------------------------------
-    def prepare_weights(self, W, fused=True):
-        """fused=True: one launch (gpusq_prepare_weights); fused=False: the four separate calls"""
+    def prepare_weights(self, W, fused=True, intermediates=True):
+        """fused=True: one launch (gpusq_prepare_weights); fused=False: the four separate calls.
+        intermediates=False (fused only): the pruned fp32 weights, the masked low-precision weights, the canonical values
+        and metadata stay in the kernel's registers; only what the sparse GEMM reads (packed operand, scales) is written."""
         L, s = G.lib(), G._stream()
         N, K = self.N, self.K
         if fused and K * 4 <= 64 * 1024:
-            G._check(L.gpusq_prepare_weights(_p(W), G.I8 if self.precision == "int8" else G.F16, _p(self.W_pruned),
-                                             _p(self.W_low), _p(self.w_scale) if self.precision == "int8" else None,
-                                             _p(self.values), _p(self.meta), _p(self.packed), N, K, s), "gpusq_prepare_weights")
+            keep = (lambda t: _p(t)) if intermediates else (lambda t: None)
+            G._check(L.gpusq_prepare_weights(_p(W), G.I8 if self.precision == "int8" else G.F16, keep(self.W_pruned),
+                                             keep(self.W_low), _p(self.w_scale) if self.precision == "int8" else None,
+                                             keep(self.values), keep(self.meta), _p(self.packed), N, K, s), "gpusq_prepare_weights")
             return
         G._check(L.gpusq_prune_2to4(_p(W), _p(self.W_pruned), None, G.F32, N, K, s), "gpusq_prune_2to4")
         if self.precision == "int8":

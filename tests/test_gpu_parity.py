@@ -109,7 +109,11 @@ def test_quantize_rows_bit_exact(g, dtype):
 def test_quantize_tensor_bit_exact(g, dtype):
     cases = [synth.activations(197, 192, "normal_clip4", seed=0), synth.activations(1, 5, seed=1),
              synth.activations(513, 770, "gelu_normal", seed=2), np.zeros((4, 8), np.float32),
-             np.array([[0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, 127.0]], np.float32)]
+             np.array([[0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, 127.0]], np.float32),
+             # larger tensors with ragged ends (more partial maxima than one workgroup folds in one pass) and the
+             # benchmark's activation tensor
+             synth.activations(3000, 1001, "normal", seed=3), synth.activations(64 * 197, 768, "normal", seed=4),
+             synth.activations(9001, 4099, "normal_clip4", seed=5)]
     for X in cases:
         X = X.astype(dtype)
         eq, es = oracle.quantize_tensor_int8(X.astype(np.float32))
