@@ -138,7 +138,20 @@ struct TilePlan {
   int full_tiles;   // = full_chunks * tiles_n
   int tail_tm;      // 1..4
   int total;        // full + tail tiles
+  // ceil(2^32 / tiles_n), or 0 when the shortcut below does not apply (tiles_n = 1 or > 4096, or 2^20 tiles or more)
+  uint32_t inv_tiles_n;
 };
+
+// idx / tiles_n without a division (a tile is decoded three times per tile, between K steps, by every wavefront, and an
+// integer division is some thirty scalar instructions): for d <= 4096 and idx < 2^20, mulhi(idx, ceil(2^32 / d)) is the
+// exact quotient (the error idx * e / (d * 2^32), e < d, stays below 1 / d).
+__host__ __device__ __forceinline__ int div_tiles_n(const TilePlan& p, int idx) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return p.inv_tiles_n ? (int)__umulhi((unsigned)idx, p.inv_tiles_n) : idx / p.tiles_n;
+#else
+  return p.inv_tiles_n ? (int)(((uint64_t)(unsigned)idx * p.inv_tiles_n) >> 32) : idx / p.tiles_n;
+#endif
+}
 
 struct Tile {
   int n_blk;
@@ -159,13 +172,15 @@ __host__ __device__ __forceinline__ int xcd_items(const TilePlan& p, int x, int&
 __device__ __forceinline__ Tile decode_tile(const TilePlan& p, int idx) {
   Tile t;
   if (idx < p.full_tiles) {
-    t.n_blk = idx % p.tiles_n;
-    t.m0 = (int64_t)(idx / p.tiles_n) * (16 * kTileWM) * p.full_tm;
+    const int chunk = div_tiles_n(p, idx);
+    t.n_blk = idx - chunk * p.tiles_n;
+    t.m0 = (int64_t)chunk * (16 * kTileWM) * p.full_tm;
     t.tm = p.full_tm;
   } else {
     const int j = idx - p.full_tiles;
-    t.n_blk = j % p.tiles_n;
-    t.m0 = ((int64_t)p.full_chunks * p.full_tm + (int64_t)(j / p.tiles_n) * p.tail_tm) * (16 * kTileWM);
+    const int chunk = div_tiles_n(p, j);
+    t.n_blk = j - chunk * p.tiles_n;
+    t.m0 = ((int64_t)p.full_chunks * p.full_tm + (int64_t)chunk * p.tail_tm) * (16 * kTileWM);
     t.tm = p.tail_tm;
   }
   return t;
@@ -994,6 +1009,7 @@ static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
     p.tail_tm = ttm;
     const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * 64 * ftm;
     p.total = p.full_tiles + (rows_left > 0 ? (int)ceil_div(rows_left, 64 * ttm) * tiles_n : 0);
+    p.inv_tiles_n = (tiles_n > 1 && tiles_n <= 4096 && p.total < (1 << 20)) ? (uint32_t)((((uint64_t)1 << 32) + tiles_n - 1) / tiles_n) : 0u;
     const double c = plan_makespan(p, grid_for(p, resident), ksteps, gelu);
     if (best_cost < 0 || c < best_cost) {
       best_cost = c;
