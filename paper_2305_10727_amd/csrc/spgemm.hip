@@ -194,6 +194,12 @@ __device__ __forceinline__ Tile decode_tile(const TilePlan& p, int idx) {
 __device__ __forceinline__ void copy16_to_lds(const void* gbase, uint32_t voff, uint32_t lds) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory", "m0");
 }
+// The same with the LDS address given as a scalar base plus a compile-time constant: one scalar instruction forms M0.
+template <int IMM>
+__device__ __forceinline__ void copy16_to_lds_at(const void* gbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase), "n"(IMM)
+               : "memory", "m0", "scc");
+}
 __device__ __forceinline__ void copy4_to_lds(const void* gbase, uint32_t voff, uint32_t lds) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory", "m0");
 }
@@ -201,25 +207,28 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const uint8_t*)p;
 }
 
-// Copy i (0..6) of one wavefront's share (an eighth) of the copies that bring one K step of a tile into the LDS stage
-// at `stage_lds`: i = 0..3 are 1 KB blocks of the X slab (block j = wave + 8i holds rows 8j..8j+7), i = 4, 5 fragments
-// of kept values, i = 6 1 KB of index words.  Each copy moves 64 lanes x 16 bytes from a wavefront-uniform 64-bit base
-// (scalar registers, advanced per K step by scalar adds) plus a 32-bit per-lane offset to 1 KB of consecutive LDS, so
-// a K step costs no vector ALU work for addressing.  Always exactly kCopies instructions per step, whatever the tile
-// (a short tile copies rows it does not use; there are only 4 KB / 2 KB of index words, so some wavefronts repeat a
-// block), so that the waits can count instructions.
-template <bool IS_I8>
-__device__ __forceinline__ void issue_step_copy(int i, uint32_t stage_lds, const uint8_t* Xks, const uint8_t* Wks,
-                                                const uint32_t (&xoff)[4], int wave, uint32_t loff) {
-  if (i < 4) {
-    copy16_to_lds(Xks, xoff[i], stage_lds + (uint32_t)(wave + 8 * i) * 1024u);
-  } else if (i < 6) {
-    const int f = wave + 8 * (i - 4);
-    copy16_to_lds(Wks + f * kFragValueBytes, loff, stage_lds + kXSlabBytes + (uint32_t)f * kFragValueBytes);
-  } else {
-    const int iw = IS_I8 ? (wave & 3) : (wave & 1);
-    copy16_to_lds(Wks + kTileValueBytes + iw * 1024, loff, stage_lds + kXSlabBytes + kTileValueBytes + (uint32_t)iw * 1024u);
-  }
+// Copy I (0..6) of one wavefront's share (an eighth) of the copies that bring one K step of a tile into an LDS stage:
+// I = 0..3 are 1 KB blocks of the X slab (block j = wave + 8I holds rows 8j..8j+7), I = 4, 5 fragments of kept values,
+// I = 6 1 KB of index words.  Each copy moves 64 lanes x 16 bytes from a wavefront-uniform 64-bit base in scalar
+// registers plus a 32-bit per-lane offset that is fixed for the whole tile, to 1 KB of consecutive LDS at a scalar
+// base plus a constant: per copy the K loop spends one scalar instruction and one wait state besides the copy itself
+// (the K loop is bound by instruction issue, scalar instructions and branches first of all).
+//   lds_wave = LDS address of the stage + wave * 1024, lds_idx = that of the index block this wavefront copies;
+//   Xks = the X rows of the tile at this K step, Wwave = the packed tile of this K step + wave * 1024;
+//   loff = lane * 16, loff8k = loff + 8192, ioff = loff + the index block's offset relative to Wwave.
+// Always exactly kCopies instructions per step, whatever the tile (a short tile copies rows it does not use; there are
+// only 4 KB / 2 KB of index words, so some wavefronts repeat a block), so that the waits can count instructions.
+template <int I>
+__device__ __forceinline__ void issue_step_copy(uint32_t lds_wave, uint32_t lds_idx, const uint8_t* Xks, const uint8_t* Wwave,
+                                                const uint32_t (&xoff)[4], uint32_t loff, uint32_t loff8k, uint32_t ioff) {
+  if constexpr (I < 4)
+    copy16_to_lds_at<8192 * I>(Xks, xoff[I < 4 ? I : 0], lds_wave);
+  else if constexpr (I == 4)
+    copy16_to_lds_at<kXSlabBytes>(Wwave, loff, lds_wave);
+  else if constexpr (I == 5)
+    copy16_to_lds_at<kXSlabBytes + 8192>(Wwave, loff8k, lds_wave);
+  else
+    copy16_to_lds_at<0>(Wwave, ioff, lds_idx);
 }
 
 // Per-lane byte offsets, relative to the tile's first row, of the four X blocks a wavefront copies per K step: lane l
@@ -319,17 +328,21 @@ __device__ __forceinline__ void load_step_head(v8i (&b)[kTileTM], v4i (&av)[4], 
 // fragment kBarrierFrag the wait and the barrier (see the kernel); behind it, one per matrix instruction, the reads
 // of the next step's head from `next` into `bn`, `av`, `ai` and the wavefront's kCopies copy requests.  So every other
 // instruction is issued in the shadow of a matrix instruction.
-// wait_mode (wavefront-uniform): what may stay outstanding at the barrier: 0 = nothing, 1 = one step of copies,
-// 2 = one step of copies and 16 output stores, 3 = one step of copies and 8 output stores.
-// last (wavefront-uniform): the last step of a tile reads nothing ahead (the head of the next tile's first step is read
-// after the epilogue, which keeps those registers free for the epilogue's arithmetic).
+// The step has no conditional parts: what the K loop can sustain is set by the instructions a wavefront must issue per
+// step (measured: a compare-and-branch pair between two matrix instructions costs more than the matrix instruction), so
+// the last step of a tile reads ahead like any other (the next tile reloads those registers) and the steps at the end of
+// a workgroup's sequence request copies like any other (the cursor then stays on the last step: they land in a free
+// stage and are never read).
+// wait_mode (wavefront-uniform): what may stay outstanding at the barrier besides one step of copies: 1 = nothing,
+// 2 = 16 output stores, 3 = 8 output stores; 0 = nothing at all may stay outstanding.
 // behind_barrier(): called once, right behind the barrier and before the step's copy requests.
 template <bool IS_I8, class Hook>
-__device__ __forceinline__ void tile_step(bool last, int wait_mode, const uint8_t* stage, const uint8_t* next, const BOffsets& bo,
+__device__ __forceinline__ void tile_step(int wait_mode, const uint8_t* stage, const uint8_t* next, const BOffsets& bo,
                                           typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM], const v8i (&b)[kTileTM],
                                           v8i (&bn)[kTileTM], v4i (&av)[4], int (&ai)[kTileTN], uint32_t a_off, uint32_t i_off,
-                                          bool requested, uint32_t req_lds, const uint8_t* req_x, const uint8_t* req_w,
-                                          const uint32_t (&xoff)[4], int wave, uint32_t loff, Hook&& behind_barrier) {
+                                          uint32_t req_lds_wave, uint32_t req_lds_idx, const uint8_t* req_x, const uint8_t* req_w,
+                                          const uint32_t (&xoff)[4], uint32_t loff, uint32_t loff8k, uint32_t ioff,
+                                          Hook&& behind_barrier) {
   const uint8_t* abase = stage + kXSlabBytes + a_off;
   const uint8_t* ibase = stage + kXSlabBytes + i_off;
   const uint8_t* abase_n = next + kXSlabBytes + a_off;
@@ -340,14 +353,14 @@ __device__ __forceinline__ void tile_step(bool last, int wait_mode, const uint8_
     for (int mt = 0; mt < kTileTM; ++mt) {
       if (tn == kBarrierFrag && mt == 0) {
         __builtin_amdgcn_sched_barrier(0);  // the compiler must not move the wait above the matrix instructions before it
-        if (wait_mode == 0)
-          __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        else if (wait_mode == 1)
+        if (wait_mode == 1)
           __builtin_amdgcn_s_waitcnt(kWaitVm7);
+        else if (wait_mode == 2)
+          __builtin_amdgcn_s_waitcnt(kWaitVm23);
         else if (wait_mode == 3)
           __builtin_amdgcn_s_waitcnt(kWaitVm15);
         else
-          __builtin_amdgcn_s_waitcnt(kWaitVm23);
+          __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");  // no LDS read moves above the barrier
         behind_barrier();
@@ -356,19 +369,25 @@ __device__ __forceinline__ void tile_step(bool last, int wait_mode, const uint8_
         const int f = tn + 3;  // f >= kTileTN exactly when tn >= kBarrierFrag: the next stage, behind the barrier
         if (f < kTileTN)
           av[f & 3] = *(const v4i*)(abase + f * kFragValueBytes);
-        else if (!last)
+        else
           av[f & 3] = *(const v4i*)(abase_n + (f - kTileTN) * kFragValueBytes);
       }
       if (tn == 0 && mt == 2) load_index_half<IS_I8>(ai, 1, ibase);
       if (tn >= kBarrierFrag) {
         const int slot = (tn - kBarrierFrag) * kTileTM + mt;  // 0..11
-        if (!last && slot < 2 * kTileTM) {
+        if (slot < 2 * kTileTM) {
           const v4i piece = *(const v4i*)(next + ((slot & 1) ? bo.hi : bo.lo) + (slot >> 1) * 16 * kStepBytes);
 #pragma unroll
           for (int j = 0; j < 4; ++j) bn[slot >> 1][4 * (slot & 1) + j] = piece[j];
         }
-        if (!last && slot == 2 * kTileTM) load_index_half<IS_I8>(ai, 0, ibase_n);
-        if (requested && slot < kCopies) issue_step_copy<IS_I8>(slot, req_lds, req_x, req_w, xoff, wave, loff);
+        if (slot == 2 * kTileTM) load_index_half<IS_I8>(ai, 0, ibase_n);
+        if (slot == 0) issue_step_copy<0>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 1) issue_step_copy<1>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 2) issue_step_copy<2>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 3) issue_step_copy<3>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 4) issue_step_copy<4>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 5) issue_step_copy<5>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 6) issue_step_copy<6>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
       }
       __builtin_amdgcn_sched_barrier(0);
       acc[tn][mt] = smfmac<IS_I8>(av[tn & 3], b[mt], acc[tn][mt], ai[tn]);
@@ -386,6 +405,7 @@ __device__ __forceinline__ void batch_epilogue(const GemmArgs& a, const typename
                                              const float* p, float s_a, int n_wave, int64_t m_wave, int lane, int tm_active) {
   constexpr bool RAW = IS_I8 && OUT == GPUSQ_I32;
   constexpr int OB = dtype_bytes(OUT);
+  asm volatile("" : "+v"(lane));  // see line_epilogue
   uint8_t* yrow[kTileTM];
   bool row_ok[kTileTM];
 #pragma unroll
@@ -491,6 +511,9 @@ __device__ __forceinline__ void line_epilogue(const GemmArgs& a, const typename 
                                               const float* p, float s_a, float so, float rso, int n_wave, int64_t m_wave, int lane,
                                               int tm_active) {
   constexpr int OB = dtype_bytes(OUT);
+  // (the lane number is laundered through an empty asm: everything derived from it below is then computed here, per
+  // tile, instead of once per kernel with the results held in registers, or spilled, across the K loops)
+  asm volatile("" : "+v"(lane));
   const int c = lane & 15, q = lane >> 4, up = c >> 3;
   const int64_t slab_bytes = (int64_t)16 * a.N * OB, half_bytes = (int64_t)8 * a.N * OB;
   global_u8* ywave = uniform_ptr((uint8_t*)a.Y + (m_wave * a.N + n_wave) * OB);  // the wavefront's first row and channel
@@ -637,7 +660,6 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
   const int items = xcd_items(plan, xcd, f0, nf, t0);
   const int my_items = wl < items ? (items - wl + wgs_per_xcd - 1) / wgs_per_xcd : 0;
   if (my_items == 0) return;  // the whole workgroup leaves before any barrier
-  const int total_steps = my_items * ksteps;
   auto tile_of = [&](int i) {
     const int it = wl + i * wgs_per_xcd;
     return decode_tile(plan, it < nf ? f0 + it : t0 + it - nf);
@@ -673,33 +695,51 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
   const uint32_t a_off = (uint32_t)(wn * kTileTN * kFragValueBytes + lane * 16);
   const uint32_t i_off = (uint32_t)index_offset(IS_I8, wn * kTileTN, lane);
 
-  // cursor of the copy requests: the next K step to request, as (tile, step), with its source addresses
+  // lane offsets of the copies of kept values and index words, relative to the packed tile of a K step + wave * 1024
+  const uint32_t loff8k = loff + 8192u;
+  const int idx_block = IS_I8 ? (wave & 3) : (wave & 1);  // the 1 KB of index words this wavefront copies
+  const uint32_t ioff = loff + (uint32_t)(kTileValueBytes + idx_block * 1024 - wave * 1024);
+  const uint32_t wave_lds = (uint32_t)wave * 1024u, idx_lds = (uint32_t)(kXSlabBytes + kTileValueBytes + idx_block * 1024);
+
+  // Cursor of the copy requests: the next K step to request, as (tile, step), with its source addresses (pf_w includes
+  // wave * 1024).  At the end of the workgroup's sequence it stays on the last step: the requests go on (the waits
+  // count a fixed number of copies per step) and re-fetch that step into a stage that nothing reads any more.
   int pf_item = 0, pf_ks = 0;
   const uint8_t *pf_x = Xg, *pf_w = Wg;
   uint32_t pf_xoff[4] = {0, 0, 0, 0};
   auto seek = [&](int item) {
     pf_item = item;
     pf_ks = 0;
-    if (item < my_items) {
-      const Tile t = tile_of(item);
-      if constexpr (PATCH) {
-        patch_x_offsets<IS_I8>(pf_xoff, t.m0, a, wave, lane);
-        pf_x = Xg;
-      } else {
-        tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane);
-        pf_x = Xg + t.m0 * k_bytes;
-      }
-      pf_w = Wg + t.n_blk * w_col_bytes;
+    const Tile t = tile_of(item);
+    if constexpr (PATCH) {
+      patch_x_offsets<IS_I8>(pf_xoff, t.m0, a, wave, lane);
+      pf_x = Xg;
+    } else {
+      tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane);
+      pf_x = Xg + t.m0 * k_bytes;
     }
+    pf_w = Wg + t.n_blk * w_col_bytes + wave_lds;
   };
   auto advance = [&]() {
-    ++pf_ks;
-    if constexpr (PATCH)
-      pf_x = Xg + patch_step_offset<IS_I8>(a, pf_ks);
-    else
-      pf_x += kStepBytes;
-    pf_w += tile_bytes(IS_I8);
-    if (pf_ks == ksteps) seek(pf_item + 1);
+    if (pf_ks + 1 < ksteps) {
+      ++pf_ks;
+      if constexpr (PATCH)
+        pf_x = Xg + patch_step_offset<IS_I8>(a, pf_ks);
+      else
+        pf_x += kStepBytes;
+      pf_w += tile_bytes(IS_I8);
+    } else if (pf_item + 1 < my_items) {
+      seek(pf_item + 1);
+    }
+  };
+  auto request_step = [&](uint32_t stage_lds) {
+    issue_step_copy<0>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
+    issue_step_copy<1>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
+    issue_step_copy<2>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
+    issue_step_copy<3>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
+    issue_step_copy<4>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
+    issue_step_copy<5>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
+    issue_step_copy<6>(stage_lds + wave_lds, stage_lds + idx_lds, pf_x, pf_w, pf_xoff, loff, loff8k, ioff);
   };
 
   acc_t acc[kTileTN][kTileTM];
@@ -710,59 +750,49 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
   // the constants of the first tile, then the first three K steps of the sequence
   request_constants(tile_of(0).n_blk * kTileBN + wn * (kTileTN * 16), 0);
   seek(0);
-  {
-    int n_req = 0;
-    for (int g = 0; g < kRing; ++g) {
-      if (pf_item < my_items) {
-#pragma unroll
-        for (int i = 0; i < kCopies; ++i)
-          issue_step_copy<IS_I8>(i, ring_lds + (uint32_t)g * STAGE, pf_x, pf_w, pf_xoff, wave, loff);
-        advance();
-        ++n_req;
-      }
-    }
-    if (n_req == kRing)
-      __builtin_amdgcn_s_waitcnt(kWaitVm14);  // the constants and step 0 have landed
-    else
-      __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  for (int g = 0; g < kRing; ++g) {
+    request_step(ring_lds + (uint32_t)g * STAGE);
+    advance();
   }
+  __builtin_amdgcn_s_waitcnt(kWaitVm14);  // the constants and step 0 have landed
   __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  int g = 0, slot = 0;     // global K step and its ring stage
-  int stores_pending = 0;  // output stores of the previous tile's epilogue (-1: unknown)
+  int slot_off = 0;        // byte offset of the current K step's ring stage
+  int first2_mode = 1;     // wait mode of a tile's first two steps (output stores of the previous tile still in the queue)
   for (int item = 0; item < my_items; ++item) {
     const Tile t = tile_of(item);
-    const BOffsets bo = b_offsets(wm, t.tm, lane);
+    int lane_now = lane;
+    asm volatile("" : "+v"(lane_now));  // the offsets are computed here, per tile, not once per kernel and kept (or spilled)
+    const BOffsets bo = b_offsets(wm, t.tm, lane_now);
     const int next_n0 = item + 1 < my_items ? tile_of(item + 1).n_blk * kTileBN + wn * (kTileTN * 16) : -1;
 #pragma unroll
     for (int i = 0; i < kTileTN; ++i)
 #pragma unroll
       for (int j = 0; j < kTileTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
     // the stage of the tile's first step has landed: start-up barrier, or the barrier in the previous tile's last step
-    load_step_head<IS_I8>(b0, av, ai, ring + (size_t)slot * STAGE, ring + (size_t)slot * STAGE + kXSlabBytes, bo, a_off, i_off);
+    load_step_head<IS_I8>(b0, av, ai, ring + slot_off, ring + slot_off + kXSlabBytes, bo, a_off, i_off);
     auto step = [&](int ks, const v8i (&b)[kTileTM], v8i (&bn)[kTileTM]) {
-      const bool requested = pf_item < my_items;
-      const int nslot = slot + 1 == kRing ? 0 : slot + 1;
-      // Outstanding at the barrier of step g, oldest first: the copies of step g+1, then those of step g+2 (if the
-      // sequence has one), which may stay in flight.  In the first two steps of a tile the output stores of the previous
-      // tile's epilogue sit in the queue behind the copies waited for, so they may stay in flight too: the stores drain
-      // to memory while the K loop goes on.  The third barrier of a tile then waits for copies that were requested after
-      // those stores.  (Only the common count, the 16 stores of a wavefront whose 128 x 64 outputs all lie inside Y, is
-      // exploited; any other count waits for the stores as well, which is only stricter.)
-      const int wait_mode = g + 2 >= total_steps ? 0 : (ks < 2 ? (stores_pending < 0 ? 0 : (stores_pending >= 16 ? 2 : (stores_pending >= 8 ? 3 : 1))) : 1);
-      tile_step<IS_I8>(ks + 1 == ksteps, wait_mode, ring + (size_t)slot * STAGE, ring + (size_t)nslot * STAGE, bo, acc, b, bn, av, ai,
-                       a_off, i_off, requested, ring_lds + (uint32_t)slot * STAGE, pf_x, pf_w, pf_xoff, wave, loff, [&]() {
+      const int next_off = slot_off + STAGE == kRing * STAGE ? 0 : slot_off + STAGE;
+      // Outstanding at the barrier of step g, oldest first: the copies of step g+1, then those of step g+2, which may
+      // stay in flight.  In the first two steps of a tile the output stores of the previous tile's epilogue sit in the
+      // queue behind the copies waited for, so they may stay in flight too: the stores drain to memory while the K loop
+      // goes on.  The third barrier of a tile then waits for copies that were requested after those stores.  (Only two
+      // counts are exploited, the 16 and 8 stores of a wavefront whose 128 x 64 outputs all lie inside Y; any other
+      // count waits for the stores as well, which is only stricter.)
+      const int wait_mode = ks < 2 ? first2_mode : 1;
+      tile_step<IS_I8>(wait_mode, ring + slot_off, ring + next_off, bo, acc, b, bn, av, ai, a_off, i_off,
+                       ring_lds + (uint32_t)slot_off + wave_lds, ring_lds + (uint32_t)slot_off + idx_lds, pf_x, pf_w, pf_xoff, loff,
+                       loff8k, ioff, [&]() {
                          // The next tile's constants go into the other constants array, which was last read in the
                          // previous tile's epilogue (every wavefront has left it: it passed this tile's barriers).  They
                          // are older than this step's copy requests and than this tile's output stores, so the wait in
                          // front of the next tile's first barrier covers them and that barrier publishes them.
                          if (ks + 1 == ksteps) request_constants(next_n0, (item + 1) & 1);
                        });
-      if (requested) advance();
-      ++g;
-      slot = nslot;
+      advance();
+      slot_off = next_off;
     };
     for (int ks = 0; ks < ksteps; ks += 2) {
       step(ks, b0, b1);
@@ -772,9 +802,9 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
     const int64_t m_wave = t.m0 + wm * t.tm * 16;
     const int64_t rows = (int64_t)a.M - m_wave;
     const int chans = a.N - n_wave;
-    // The epilogue, and the number of store instructions this wavefront issues in it (with N % 8 != 0 that number
-    // depends on the lanes: then the next tile waits for everything, because a count that is too high would let its
-    // copies go unwaited).
+    // The epilogue, and the number of store instructions this wavefront issues in it (a count that is too high would let
+    // the next tile's copies go unwaited, one that is too low only waits for stores as well).
+    int stores_pending;
     const bool lines = OUT == GPUSQ_F16 ? (a.N & 7) == 0 : (OUT == GPUSQ_I8 ? (a.N & 15) == 0 : true);
     if (lines) {
       if (t.tm == kTileTM && rows >= kTileTM * 16 && chans >= kTileTN * 16)
@@ -789,12 +819,15 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
       stores_pending = n * (chans <= 0 ? 0 : (chans >= 128 ? 128 / per_line : (chans + per_line - 1) / per_line));
     } else {
       batch_epilogue<IS_I8, GELU, OUT>(a, acc, prm[item & 1][wn], s_a, n_wave, m_wave, lane, t.tm);
-      // one (two for 2 x 16 bytes of int32) per batch of 32 channels x 16 rows with a row inside M and a channel inside N
+      // one (two for 2 x 16 bytes of int32) per batch of 32 channels x 16 rows with a row inside M and a channel inside N;
+      // with N % 8 != 0 the number depends on the lanes and is not used
       const int mts = rows <= 0 ? 0 : (rows >= t.tm * 16 ? t.tm : (int)((rows + 15) >> 4));
       const int gs = chans <= 0 ? 0 : (chans >= 128 ? 4 : (chans + 31) >> 5);
-      stores_pending = (a.N & 7) ? -1 : mts * gs * (OUT == GPUSQ_I32 ? 2 : 1);
+      stores_pending = (a.N & 7) ? 0 : mts * gs * (OUT == GPUSQ_I32 ? 2 : 1);
     }
+    first2_mode = stores_pending >= 16 ? 2 : (stores_pending >= 8 ? 3 : 1);
   }
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);  // the copies requested past the end of the sequence land before the LDS is given up
 }
 
 // ------------------------------------------------------------------------------------------------ small / generic kernel
