@@ -854,7 +854,7 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn = wave % WN, wm = wave / WN;
-  const int M = a.M, N = a.N;
+  const int M = a.M;
   if (tid < BN) {
     ChannelParams prm;
     prm.fetch<IS_I8>(a, n_blk * BN + tid);
@@ -862,7 +862,6 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   }
   const int64_t k_bytes = (int64_t)a.K * ES;
   const int ksteps = (int)((k_bytes + kStepBytes - 1) / kStepBytes);
-  const int row_blocks = ((N + kTileRows - 1) / kTileRows) * 4;  // the packed buffer is padded to whole 256-row tiles
   const int rb0 = (n_blk * BN + wn * TN * 16) / kRowBlock;
   const uint8_t* Xg = (const uint8_t*)a.X;
   const uint8_t* Wg = (const uint8_t*)a.W;
@@ -885,28 +884,35 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   // per SIMD (a lone wavefront issues a vector instruction only every 6-8 clocks) address arithmetic per load is what a
   // step would otherwise cost.
   const global_u8* Xtile = uniform_ptr(Xg + (int64_t)m_blk * BM * k_bytes);
+  // Rows past the end of X re-read the last row (their results are never stored), so only a K that is not a whole
+  // number of steps needs a predicate, and only in the last step: a plain step is 7 loads and nothing else.
   uint32_t xoff[XCH];
-  int xcol[XCH];  // first K byte (inside a step) of the lane's chunk, or past any K for rows beyond M
+  const int64_t last_row = (int64_t)M - 1 - (int64_t)m_blk * BM;  // >= 0: a tile starts inside X
 #pragma unroll
   for (int j = 0; j < XCH; ++j) {
     const int c = tid + 256 * j;
-    const int row = c >> 3, cc = c & 7;
-    xoff[j] = (uint32_t)row * (uint32_t)k_bytes + cc * 16;  // the host keeps 128 rows of X below 4 GiB
-    xcol[j] = ((int64_t)m_blk * BM + row < M) ? cc * 16 : 0x7FFFFFFF;
+    const int row = (c >> 3) < last_row ? (c >> 3) : (int)last_row;
+    xoff[j] = (uint32_t)row * (uint32_t)k_bytes + (c & 7) * 16;  // the host keeps 128 rows of X below 4 GiB
   }
+  const int tail_bytes = (int)(k_bytes % kStepBytes);  // 0: K is a whole number of steps
   static_assert(TN == 4, "a wavefront's fragments are the four of one 64-channel row block");
+  // (the packed buffer is padded to whole 256-channel tiles, so the wavefront's row block always exists: rb < row_blocks)
   const int rb = rb0;
-  const bool rb_ok = rb < row_blocks;  // wavefront-uniform
   const int f0 = (rb & 3) * 4;
   const global_u8* Wrow = uniform_ptr(Wg + (int64_t)(rb >> 2) * ksteps * tile_bytes(IS_I8));
   const uint32_t a_lane = (uint32_t)(f0 * kFragValueBytes + lane * 16);
   const uint32_t i_lane = (uint32_t)index_offset(IS_I8, f0, lane);  // the index words of fragments f0 .. f0+3 are adjacent
   auto load_x = [&](int ks, int slot) {
     const global_u8* base = Xtile + (int64_t)ks * kStepBytes;
-    const int k_left = (int)(k_bytes - (int64_t)ks * kStepBytes < kStepBytes ? k_bytes - (int64_t)ks * kStepBytes : kStepBytes);
+    if (tail_bytes != 0 && ks + 1 == ksteps) {  // workgroup-uniform: the ragged last step zero-fills past the row end
 #pragma unroll
-    for (int j = 0; j < XCH; ++j)
-      xr[slot][j] = xcol[j] < k_left ? *(const __attribute__((address_space(1))) v4i*)(base + xoff[j]) : v4i{0, 0, 0, 0};
+      for (int j = 0; j < XCH; ++j)
+        xr[slot][j] = (int)(((tid + 256 * j) & 7) * 16) < tail_bytes ? *(const __attribute__((address_space(1))) v4i*)(base + xoff[j])
+                                                                      : v4i{0, 0, 0, 0};
+    } else {
+#pragma unroll
+      for (int j = 0; j < XCH; ++j) xr[slot][j] = *(const __attribute__((address_space(1))) v4i*)(base + xoff[j]);
+    }
   };
   auto store_x = [&](int buf, int slot) {
 #pragma unroll
@@ -916,65 +922,63 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
     }
   };
   auto load_a = [&](int ks, int slot) {
-    if (rb_ok) {
-      const global_u8* t = Wrow + (int64_t)ks * tile_bytes(IS_I8);
+    const global_u8* t = Wrow + (int64_t)ks * tile_bytes(IS_I8);
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-        av[slot][tn] = *(const __attribute__((address_space(1))) v4i*)(t + a_lane + tn * kFragValueBytes);
-      if constexpr (IS_I8) {
-        const v4i w = *(const __attribute__((address_space(1))) v4i*)(t + i_lane);
+    for (int tn = 0; tn < TN; ++tn)
+      av[slot][tn] = *(const __attribute__((address_space(1))) v4i*)(t + a_lane + tn * kFragValueBytes);
+    if constexpr (IS_I8) {
+      const v4i w = *(const __attribute__((address_space(1))) v4i*)(t + i_lane);
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) ai[slot][tn] = w[tn];
-      } else {
-        const ep_v2u w = *(const __attribute__((address_space(1))) ep_v2u*)(t + i_lane);
-        ai[slot][0] = (int)(w[0] & 0xFFFFu);
-        ai[slot][1] = (int)(w[0] >> 16);
-        ai[slot][2] = (int)(w[1] & 0xFFFFu);
-        ai[slot][3] = (int)(w[1] >> 16);
-      }
+      for (int tn = 0; tn < TN; ++tn) ai[slot][tn] = w[tn];
     } else {
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) {
-        av[slot][tn] = v4i{0, 0, 0, 0};
-        ai[slot][tn] = 0;
-      }
+      const ep_v2u w = *(const __attribute__((address_space(1))) ep_v2u*)(t + i_lane);
+      ai[slot][0] = (int)(w[0] & 0xFFFFu);
+      ai[slot][1] = (int)(w[0] >> 16);
+      ai[slot][2] = (int)(w[1] & 0xFFFFu);
+      ai[slot][3] = (int)(w[1] >> 16);
     }
   };
 
+  // K steps q * D + r: q passes of D steps without any condition in them (the request D - 1 steps ahead is clamped to
+  // the last step, whose data is then fetched again and not used), then the r < D remaining steps, whose operands the
+  // last pass (or the preamble) has already requested, as straight-line code behind uniform forward branches.
+  auto clamp_step = [&](int ks) { return ks < ksteps ? ks : ksteps - 1; };
 #pragma unroll
-  for (int d = 0; d < D - 1; ++d)
-    if (d < ksteps) {
-      load_x(d, d);
-      load_a(d, d);
-    }
-
+  for (int d = 0; d < D - 1; ++d) {
+    load_x(clamp_step(d), d);
+    load_a(clamp_step(d), d);
+  }
   const int b_row = wm * TM * 16 + (lane & 15);
   const int b_col = (lane >> 4) * 16;
-  for (int ks0 = 0; ks0 < ksteps; ks0 += D) {
+  auto compute_step = [&](int ks, int slot) {
+    // The X slab alternates between two LDS buffers; the barrier of step ks - 1 lies behind every wavefront's reads of
+    // step ks - 2, which used this buffer last.
+    const int cur = ks & 1;
+    store_x(cur, slot);
+    __syncthreads();
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+      const uint8_t* p = &Xs[cur][(b_row + mt * 16) * kLdsRow + b_col];
+      const v4i lo = *(const v4i*)p, hi = *(const v4i*)(p + 64);
+      const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[slot][tn], b, acc[tn][mt], ai[slot][tn]);
+    }
+  };
+  const int passes = ksteps / D, rest = ksteps - passes * D;
+  int ks = 0;
+  for (int pass = 0; pass < passes; ++pass) {
 #pragma unroll
     for (int j = 0; j < D; ++j) {
-      const int ks = ks0 + j;
-      if (ks < ksteps) {  // workgroup-uniform
-        if (ks + D - 1 < ksteps) {
-          load_x(ks + D - 1, (j + D - 1) % D);
-          load_a(ks + D - 1, (j + D - 1) % D);
-        }
-        // The X slab alternates between two LDS buffers; the barrier of step ks - 1 lies behind every wavefront's
-        // reads of step ks - 2, which used this buffer last.
-        const int cur = ks & 1;
-        store_x(cur, j);
-        __syncthreads();
-#pragma unroll
-        for (int mt = 0; mt < TM; ++mt) {
-          const uint8_t* p = &Xs[cur][(b_row + mt * 16) * kLdsRow + b_col];
-          const v4i lo = *(const v4i*)p, hi = *(const v4i*)(p + 64);
-          const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-#pragma unroll
-          for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[j][tn], b, acc[tn][mt], ai[j][tn]);
-        }
-      }
+      load_x(clamp_step(ks + D - 1), (j + D - 1) % D);
+      load_a(clamp_step(ks + D - 1), (j + D - 1) % D);
+      compute_step(ks, j);
+      ++ks;
     }
   }
+#pragma unroll
+  for (int d = 0; d < D - 1; ++d)
+    if (d < rest) compute_step(ks + d, d);  // workgroup-uniform
   __syncthreads();  // the per-channel constants written at the top are read below (also when K has no step at all)
   wave_epilogue<IS_I8, TN, TM>(a, acc, cs, bs, n_blk * BN, n_blk * BN + wn * TN * 16, (int64_t)m_blk * BM + wm * TM * 16, lane);
 }
@@ -1084,7 +1088,7 @@ static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu,
   if (k_bytes % kStepBytes != 0) return wgs64 <= 2 * resident ? 0 : 1;
   if (fused_patches) return 2;
   if (wgs64 > 16 * resident) return 2;  // far beyond the crossover: skip the planning
-  const double per_round = 0.8 * ksteps, chain = 2.2 + 0.6 * ksteps;
+  const double per_round = 0.8 * ksteps, chain = 3.6 + 0.25 * ksteps;
   const double throughput = 3.3 + per_round * (double)wgs64 / (2.0 * resident);
   const double est_small = chain > throughput ? chain : throughput;
   const TilePlan p = make_plan((int)M, (int)N, resident, (int)ksteps, gelu);
