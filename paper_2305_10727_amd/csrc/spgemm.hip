@@ -681,9 +681,11 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
     if constexpr (!RAW) {
       if (wm == 0 && n0 >= 0) {
         const uint32_t dst = prm_lds + (uint32_t)parity * (uint32_t)sizeof(prm[0]);
+        int lane_now = lane;
+        asm volatile("" : "+v"(lane_now));  // computed here, per tile: nothing lane-dependent is carried (or spilled) across the K loop
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          int n = n0 + i * 64 + lane;
+          int n = n0 + i * 64 + lane_now;
           n = n < a.N ? n : a.N - 1;  // channels past the end are never stored
           if constexpr (IS_I8) copy4_to_lds(a.w_scale, (uint32_t)n * 4u, dst + (uint32_t)i * 256u);
           if (has_bias) copy4_to_lds(a.bias, (uint32_t)n * 4u, dst + 512u + (uint32_t)i * 256u);
@@ -711,11 +713,13 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
     pf_item = item;
     pf_ks = 0;
     const Tile t = tile_of(item);
+    int lane_now = lane;
+    asm volatile("" : "+v"(lane_now));  // (computed here, per tile)
     if constexpr (PATCH) {
-      patch_x_offsets<IS_I8>(pf_xoff, t.m0, a, wave, lane);
+      patch_x_offsets<IS_I8>(pf_xoff, t.m0, a, wave, lane_now);
       pf_x = Xg;
     } else {
-      tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane);
+      tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane_now);
       pf_x = Xg + t.m0 * k_bytes;
     }
     pf_w = Wg + t.n_blk * w_col_bytes + wave_lds;
