@@ -20,6 +20,7 @@
 //                       Needs K*elemsize % 128 == 0.
 //   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 #include "epilogue.h"
@@ -125,8 +126,7 @@ constexpr int kWaitVm14 = 0x007E;   // vmcnt(2 * kCopies)
 constexpr int kWaitVm15 = 0x007F;   // vmcnt(kCopies + 8)
 constexpr int kWaitVm23 = 0x4077;   // vmcnt(kCopies + 16)
 static_assert(kCopies == 7, "the wait immediates encode 7, 14, 7 + 8 and 7 + 16");
-static_assert(kBarrierFrag + 3 == kTileTN && (kTileTN - kBarrierFrag) * kTileTM >= 2 * kTileTM + 1 &&
-                  (kTileTN - kBarrierFrag) * kTileTM >= kCopies, "slot plan of tile_step");
+static_assert(kBarrierFrag + 3 == kTileTN, "slot plan of tile_step");
 
 // The list of tiles of one launch.  The first `full_tiles` tiles have 64*full_tm rows (n fastest); the rows behind the
 // last of them are cut into tail tiles of 64*tail_tm rows.  The host picks the three numbers so that the workgroup
@@ -336,7 +336,7 @@ __device__ __forceinline__ void load_step_head(v8i (&b)[kTileTM], v4i (&av)[4], 
 // wait_mode (wavefront-uniform): what may stay outstanding at the barrier besides one step of copies: 1 = nothing,
 // 2 = 16 output stores, 3 = 8 output stores; 0 = nothing at all may stay outstanding.
 // behind_barrier(): called once, right behind the barrier and before the step's copy requests.
-template <bool IS_I8, class Hook>
+template <bool IS_I8, int TMA, class Hook>
 __device__ __forceinline__ void tile_step(int wait_mode, const uint8_t* stage, const uint8_t* next, const BOffsets& bo,
                                           typename AccT<IS_I8>::type (&acc)[kTileTN][kTileTM], const v8i (&b)[kTileTM],
                                           v8i (&bn)[kTileTM], v4i (&av)[4], int (&ai)[kTileTN], uint32_t a_off, uint32_t i_off,
@@ -347,10 +347,12 @@ __device__ __forceinline__ void tile_step(int wait_mode, const uint8_t* stage, c
   const uint8_t* ibase = stage + kXSlabBytes + i_off;
   const uint8_t* abase_n = next + kXSlabBytes + a_off;
   const uint8_t* ibase_n = next + kXSlabBytes + i_off;
+  constexpr int kSlots = (kTileTN - kBarrierFrag) * TMA;  // matrix instructions behind the barrier
+  static_assert(kSlots >= 2 * TMA + 1, "slot plan of tile_step");
 #pragma unroll
   for (int tn = 0; tn < kTileTN; ++tn) {
 #pragma unroll
-    for (int mt = 0; mt < kTileTM; ++mt) {
+    for (int mt = 0; mt < TMA; ++mt) {
       if (tn == kBarrierFrag && mt == 0) {
         __builtin_amdgcn_sched_barrier(0);  // the compiler must not move the wait above the matrix instructions before it
         if (wait_mode == 1)
@@ -372,22 +374,24 @@ __device__ __forceinline__ void tile_step(int wait_mode, const uint8_t* stage, c
         else
           av[f & 3] = *(const v4i*)(abase_n + (f - kTileTN) * kFragValueBytes);
       }
-      if (tn == 0 && mt == 2) load_index_half<IS_I8>(ai, 1, ibase);
+      if (tn == 0 && mt == (TMA > 2 ? 2 : TMA - 1)) load_index_half<IS_I8>(ai, 1, ibase);
       if (tn >= kBarrierFrag) {
-        const int slot = (tn - kBarrierFrag) * kTileTM + mt;  // 0..11
-        if (slot < 2 * kTileTM) {
+        const int slot = (tn - kBarrierFrag) * TMA + mt;  // 0..kSlots-1
+        if (slot < 2 * TMA) {
           const v4i piece = *(const v4i*)(next + ((slot & 1) ? bo.hi : bo.lo) + (slot >> 1) * 16 * kStepBytes);
 #pragma unroll
           for (int j = 0; j < 4; ++j) bn[slot >> 1][4 * (slot & 1) + j] = piece[j];
         }
-        if (slot == 2 * kTileTM) load_index_half<IS_I8>(ai, 0, ibase_n);
-        if (slot == 0) issue_step_copy<0>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
-        if (slot == 1) issue_step_copy<1>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
-        if (slot == 2) issue_step_copy<2>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
-        if (slot == 3) issue_step_copy<3>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
-        if (slot == 4) issue_step_copy<4>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
-        if (slot == 5) issue_step_copy<5>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
-        if (slot == 6) issue_step_copy<6>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (slot == 2 * TMA) load_index_half<IS_I8>(ai, 0, ibase_n);
+        // copy c goes out in slot c (12 slots) or is spread evenly over fewer slots
+        auto at = [&](int c) { return slot == (kSlots >= kCopies ? c : c * kSlots / kCopies); };
+        if (at(0)) issue_step_copy<0>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (at(1)) issue_step_copy<1>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (at(2)) issue_step_copy<2>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (at(3)) issue_step_copy<3>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (at(4)) issue_step_copy<4>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (at(5)) issue_step_copy<5>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
+        if (at(6)) issue_step_copy<6>(req_lds_wave, req_lds_idx, req_x, req_w, xoff, loff, loff8k, ioff);
       }
       __builtin_amdgcn_sched_barrier(0);
       acc[tn][mt] = smfmac<IS_I8>(av[tn & 3], b[mt], acc[tn][mt], ai[tn]);
@@ -777,7 +781,7 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
       for (int j = 0; j < kTileTM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
     // the stage of the tile's first step has landed: start-up barrier, or the barrier in the previous tile's last step
     load_step_head<IS_I8>(b0, av, ai, ring + slot_off, ring + slot_off + kXSlabBytes, bo, a_off, i_off);
-    auto step = [&](int ks, const v8i (&b)[kTileTM], v8i (&bn)[kTileTM]) {
+    auto step = [&](auto tma, int ks, const v8i (&b)[kTileTM], v8i (&bn)[kTileTM]) {
       const int next_off = slot_off + STAGE == kRing * STAGE ? 0 : slot_off + STAGE;
       // Outstanding at the barrier of step g, oldest first: the copies of step g+1, then those of step g+2, which may
       // stay in flight.  In the first two steps of a tile the output stores of the previous tile's epilogue sit in the
@@ -786,7 +790,7 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
       // counts are exploited, the 16 and 8 stores of a wavefront whose 128 x 64 outputs all lie inside Y; any other
       // count waits for the stores as well, which is only stricter.)
       const int wait_mode = ks < 2 ? first2_mode : 1;
-      tile_step<IS_I8>(wait_mode, ring + slot_off, ring + next_off, bo, acc, b, bn, av, ai, a_off, i_off,
+      tile_step<IS_I8, decltype(tma)::value>(wait_mode, ring + slot_off, ring + next_off, bo, acc, b, bn, av, ai, a_off, i_off,
                        ring_lds + (uint32_t)slot_off + wave_lds, ring_lds + (uint32_t)slot_off + idx_lds, pf_x, pf_w, pf_xoff, loff,
                        loff8k, ioff, [&]() {
                          // The next tile's constants go into the other constants array, which was last read in the
@@ -798,10 +802,23 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
       advance();
       slot_off = next_off;
     };
-    for (int ks = 0; ks < ksteps; ks += 2) {
-      step(ks, b0, b1);
-      if (ks + 1 < ksteps) step(ks + 1, b1, b0);
-    }
+    // A tile of fewer than 4 slabs per wavefront runs a K loop with the matrix instructions of its own slabs only (the
+    // other accumulators stay zero and are never stored); the copies stay the same, so that the waits count the same
+    // in every tile.
+    auto k_loop = [&](auto tma) {
+      for (int ks = 0; ks < ksteps; ks += 2) {
+        step(tma, ks, b0, b1);
+        if (ks + 1 < ksteps) step(tma, ks + 1, b1, b0);
+      }
+    };
+    if (PATCH || t.tm == 4)  // (the patch gather keeps the one full-height loop: its address registers leave no room)
+      k_loop(std::integral_constant<int, 4>{});
+    else if (t.tm == 3)
+      k_loop(std::integral_constant<int, 3>{});
+    else if (t.tm == 2)
+      k_loop(std::integral_constant<int, 2>{});
+    else
+      k_loop(std::integral_constant<int, 1>{});
     const int n_wave = t.n_blk * kTileBN + wn * (kTileTN * 16);
     const int64_t m_wave = t.m0 + wm * t.tm * 16;
     const int64_t rows = (int64_t)a.M - m_wave;
@@ -1008,10 +1025,11 @@ static int num_cus() {
   return cus;
 }
 
-// Estimated run time (microseconds, fitted to traces of the kernel on MI355X) of one tile of 64*tm rows: a K step costs
-// the same whatever tm (a short tile still runs every wavefront through whole operands: measured 1.1-1.2 us for
-// tm = 1..4), the epilogue scales with the rows stored and is larger with GELU.
-static double tile_cost(int tm, int ksteps, bool gelu) { return ksteps * 1.1 + (gelu ? 1.6 : 1.1) * tm + 0.3; }
+// Estimated run time (microseconds, fitted to traces and timings of the kernel on MI355X) of one tile of 64*tm rows: a
+// K step costs nearly the same whatever tm (a short tile copies and reads whole operands and only leaves out the matrix
+// instructions of the slabs it does not have: 1.1 us for tm = 4, about 0.075 us less per slab left out), the epilogue
+// scales with the rows stored and is larger with GELU.
+static double tile_cost(int tm, int ksteps, bool gelu) { return ksteps * (0.8 + 0.075 * tm) + (gelu ? 1.6 : 1.1) * tm + 0.3; }
 
 // The workgroup with the most work under the kernel's assignment (XCD x takes its share of the list, its workgroup wl
 // the items wl, wl + W, ...).
