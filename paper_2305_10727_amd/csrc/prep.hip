@@ -325,14 +325,9 @@ __global__ void __launch_bounds__(256) quantize_tensor_kernel(const T* __restric
     if (i + 8 <= n) {
       float v[8];
       load8(X + i, v);
-      int qc[8];
-      quantize_codes<8>(v, s, rs, qc);
-      uint32_t w[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        w[h] = (uint32_t)(qc[4 * h] & 0xFF) | ((uint32_t)(qc[4 * h + 1] & 0xFF) << 8) | ((uint32_t)(qc[4 * h + 2] & 0xFF) << 16) |
-               ((uint32_t)(qc[4 * h + 3] & 0xFF) << 24);
-      *(uint2*)(Q + i) = uint2{w[0], w[1]};
+      unsigned lo, hi;
+      quantize_bytes8(v, s, rs, lo, hi);  // the same codes as quantize_codes with about half the arithmetic
+      *(uint2*)(Q + i) = uint2{lo, hi};
     } else {
       for (int64_t j = i; j < n; ++j) Q[j] = (int8_t)quantize_code(load_as_f32(X, j), s, rs);
     }
