@@ -443,6 +443,38 @@ def test_tile_kernel_corner_shapes(g, force_kernel, M, K, N, seed, kernel):
     assert np.array_equal(yh.view(np.uint16), oracle.epilogue_fp16_f64(a64)["y16"].view(np.uint16))
 
 
+# One shape per tile height of the tile kernel (its K loop exists once per height: 64, 128, 192 and 256 rows), and one
+# whose plan mixes full-height tiles with 64-row tail tiles; the heights are what the planner picks on 256 CUs.
+HEIGHT_SHAPES = [(11229, 512, 256, 21, {1}), (8208, 512, 512, 22, {2}), (10911, 512, 768, 23, {3}), (12289, 512, 1024, 24, {4}),
+                 (13084, 512, 1280, 25, {4, 1})]
+
+
+@pytest.mark.parametrize("M,K,N,seed,heights", HEIGHT_SHAPES)
+def test_tile_kernel_every_tile_height(g, force_kernel, M, K, N, seed, heights):
+    force_kernel(2)
+    for dt in (torch.int8, torch.float16):
+        plan = g.spgemm_plan(dt, M, N, K)
+        assert plan["kernel"] == 2
+        got = {plan["full_tm"]} if plan["full_chunks"] else set()
+        if plan["tiles"] > plan["full_chunks"] * plan["tiles_n"]:
+            got.add(plan["tail_tm"])
+        if torch.cuda.get_device_properties(0).multi_processor_count == 256:  # (the heights were planned for 256 CUs)
+            assert got == heights
+    p = Int8Problem(M, K, N, seed)
+    d = gpu_prepare_int8(g, p.W32, p.X32)
+    exp = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
+    acc = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+    assert np.array_equal(host(acc), exp)
+    yg = host(g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(p.bias), gelu=True))
+    assert ulp_diff_f16(yg, oracle.epilogue_int8_f64(exp, p.s_a, p.s_w, p.bias, gelu=True)["y16"]).max() <= 1
+    X, W, Wh, vals, meta, _ = fp16_problem(M, K, N, seed, integers=True)
+    v, m = g.compress(dev(Wh))
+    packed = g.pack(v, m, K)
+    _, a64 = oracle.spgemm_fp16(X, vals, meta)
+    yh = host(g.spgemm_fp16(dev(X), packed, N))
+    assert np.array_equal(yh.view(np.uint16), oracle.epilogue_fp16_f64(a64)["y16"].view(np.uint16))
+
+
 def _sampled_rows(M, n_random=192, seed=0):
     return np.unique(np.concatenate([np.arange(64), np.arange(M - 160, M), np.random.default_rng(seed).integers(0, M, n_random)]))
 
