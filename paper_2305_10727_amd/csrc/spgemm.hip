@@ -260,11 +260,13 @@ __device__ __forceinline__ void patch_x_offsets(uint32_t (&xoff)[4], int64_t m0,
   for (int i = 0; i < 4; ++i) {
     const int r = 8 * (wave + i * 8) + (lane >> 3);
     const int ch = (lane & 7) ^ ((r >> 1) & 7);  // logical chunk of the step this lane fetches (see tile_x_offsets)
-    int64_t m = m0 + r;
-    m = m < a.M ? m : (int64_t)a.M - 1;          // rows past the end re-read the last row
-    const int px = (int)(m % px_n), py = (int)((m / px_n) % py_n);
-    const int64_t b = m / ((int64_t)px_n * py_n);
-    const int64_t pixel = ((b * a.patch_C) * a.patch_H + py * 16) * a.patch_W + px * 16;  // first pixel of the patch, channel 0
+    // (32-bit unsigned arithmetic: M < 2^31, and 64-bit divisions here cost the K loop, into which the tile change is
+    // inlined, scores of registers)
+    uint32_t m = (uint32_t)m0 + (uint32_t)r;
+    m = m < (uint32_t)a.M ? m : (uint32_t)a.M - 1u;  // rows past the end re-read the last row
+    const uint32_t prow = m / (uint32_t)px_n, px = m - prow * (uint32_t)px_n;
+    const uint32_t b = prow / (uint32_t)py_n, py = prow - b * (uint32_t)py_n;
+    const int64_t pixel = (((int64_t)b * a.patch_C) * a.patch_H + py * 16) * a.patch_W + px * 16;  // first pixel of the patch, channel 0
     const int row_in_step = IS_I8 ? ch : (ch >> 1), half = IS_I8 ? 0 : (ch & 1);
     xoff[i] = (uint32_t)((pixel + (int64_t)row_in_step * a.patch_W) * ES + half * 16);
   }
@@ -811,7 +813,7 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
         if (ks + 1 < ksteps) step(tma, ks + 1, b1, b0);
       }
     };
-    if (PATCH || t.tm == 4)  // (the patch gather keeps the one full-height loop: its address registers leave no room)
+    if (t.tm == 4)
       k_loop(std::integral_constant<int, 4>{});
     else if (t.tm == 3)
       k_loop(std::integral_constant<int, 3>{});

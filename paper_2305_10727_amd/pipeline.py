@@ -113,14 +113,14 @@ class SparsePatchEmbed:
     [B*(H/P)*(W/P), D].  The weight [D,C,P,P] is flattened to [D, C*P*P] (zero-padded to whole 128-byte K steps) and
     prepared like a linear layer's; an image is (quantised per tensor and) cut into flattened patches by
     gpusq_im2col_patches, then multiplied by gpusq_spgemm_*; with P = 16 (and a problem large enough for the tile kernel)
-    gpusq_patch_embed16_* lets the GEMM gather the patches itself (fused=True; the default for fp16, where it is measurably
-    faster: a 16-byte piece of an int8 patch row touches a cache line of its own, which costs the int8 GEMM as much as the
-    separate im2col pass saves)."""
+    gpusq_patch_embed16_* lets the GEMM gather the patches itself (fused=True, the default where it applies: it saves
+    the im2col pass, most on the fp16 path, where a patch row is 32 contiguous bytes; a 16-byte piece of an int8 patch
+    row touches a cache line of its own, which gives part of the saving back)."""
 
     def __init__(self, B, C, H, W, P, D, precision="int8", bias=True, device="cuda", fused=None):
         self.shape = (B, C, H, W)
         can_fuse = P == 16 and B * (H // P) * (W // P) * D > 256 * 1024
-        self.fused = (can_fuse and precision == "fp16") if fused is None else (fused and can_fuse)
+        self.fused = can_fuse if fused is None else (fused and can_fuse)
         self.P, self.D, self.precision = P, D, precision
         self.K = C * P * P
         step = 128 if precision == "int8" else 64  # whole 128-byte K steps: the tile kernel's requirement
