@@ -1031,13 +1031,19 @@ static int num_cus() {
 // K step costs nearly the same whatever tm (a short tile copies and reads whole operands and only leaves out the matrix
 // instructions of the slabs it does not have: 1.1 us for tm = 4, about 0.075 us less per slab left out), the epilogue
 // scales with the rows stored and is larger with GELU.
-static double tile_cost(int tm, int ksteps, bool gelu) { return ksteps * (0.8 + 0.075 * tm) + (gelu ? 1.6 : 1.1) * tm + 0.3; }
+// `busy` is the fraction of the CUs that have a workgroup: the fewer run, the faster each one's K steps (the chip runs
+// at its power limit when all of them multiply: 1.1 us per step on 256 CUs, 0.63 on 150, 0.46 on 100).
+static double tile_cost(int tm, int ksteps, bool gelu, double busy) {
+  double step = (0.8 + 0.075 * tm) * (0.1 + 0.9 * busy);
+  if (step < 0.6) step = 0.6;  // (what a K step costs a lone workgroup: latency, not throughput)
+  return ksteps * step + (gelu ? 1.6 : 1.1) * tm + 0.3;
+}
 
 // The workgroup with the most work under the kernel's assignment (XCD x takes its share of the list, its workgroup wl
 // the items wl, wl + W, ...).
-static double plan_makespan(const TilePlan& p, int grid, int ksteps, bool gelu) {
+static double plan_makespan(const TilePlan& p, int grid, int ksteps, bool gelu, double busy) {
   const int W = grid / 8;
-  const double cf = tile_cost(p.full_tm, ksteps, gelu), ct = tile_cost(p.tail_tm, ksteps, gelu);
+  const double cf = tile_cost(p.full_tm, ksteps, gelu, busy), ct = tile_cost(p.tail_tm, ksteps, gelu, busy);
   double worst = 0;
   for (int x = 0; x < 8; ++x) {
     int f0, nf, t0;
@@ -1071,7 +1077,7 @@ static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
     const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * 64 * ftm;
     p.total = p.full_tiles + (rows_left > 0 ? (int)ceil_div(rows_left, 64 * ttm) * tiles_n : 0);
     p.inv_tiles_n = (tiles_n > 1 && tiles_n <= 4096 && p.total < (1 << 20)) ? (uint32_t)((((uint64_t)1 << 32) + tiles_n - 1) / tiles_n) : 0u;
-    const double c = plan_makespan(p, grid_for(p, resident), ksteps, gelu);
+    const double c = plan_makespan(p, grid_for(p, resident), ksteps, gelu, 1.0);  // (plans are compared at the full-chip step cost)
     if (best_cost < 0 || c < best_cost) {
       best_cost = c;
       best = p;
@@ -1113,10 +1119,11 @@ static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu,
   if (fused_patches) return 2;
   if (wgs64 > 16 * resident) return 2;  // far beyond the crossover: skip the planning
   const double per_round = 0.8 * ksteps, chain = 3.6 + 0.25 * ksteps;
-  const double throughput = 3.3 + per_round * (double)wgs64 / (2.0 * resident);
+  const double throughput = 4.5 + per_round * (double)wgs64 / (2.0 * resident);
   const double est_small = chain > throughput ? chain : throughput;
   const TilePlan p = make_plan((int)M, (int)N, resident, (int)ksteps, gelu);
-  const double est_tile = plan_makespan(p, grid_for(p, resident), (int)ksteps, gelu) + 2.8;
+  const int grid = grid_for(p, resident);
+  const double est_tile = plan_makespan(p, grid, (int)ksteps, gelu, (double)(p.total < grid ? p.total : grid) / resident) + 2.8;
   return est_small < est_tile ? 0 : 2;
 }
 
@@ -1138,19 +1145,51 @@ gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilog
   return GPUSQ_OK;
 }
 
+// The kernel choice and tile plan of a problem, remembered per thread for the last few distinct problems: a layer is
+// launched over and over with the same sizes, and planning (a dozen candidate plans, each walked over every workgroup)
+// takes the host several microseconds, which is what a launch of a 10 us GEMM is bound by when it is repeated.
+struct Decision {
+  bool is_i8, gelu, patches;
+  char forced;  // first character of GPUSQ_FORCE_KERNEL, 0 when unset
+  int64_t M, N, K;
+  int resident, choice;
+  TilePlan plan;  // valid when choice == 2
+};
+static const Decision& decide(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu, int resident, bool patches) {
+  constexpr int kSlots = 16;
+  thread_local Decision cache[kSlots];
+  thread_local int used = 0, next = 0;
+  const char* f = getenv("GPUSQ_FORCE_KERNEL");
+  const char forced = (f && f[0] && f[1] == 0) ? f[0] : (char)0;
+  for (int i = 0; i < used; ++i) {
+    const Decision& d = cache[i];
+    if (d.M == M && d.N == N && d.K == K && d.is_i8 == is_i8 && d.gelu == gelu && d.patches == patches && d.forced == forced &&
+        d.resident == resident)
+      return d;
+  }
+  Decision& d = cache[next];
+  next = (next + 1) % kSlots;
+  if (used < kSlots) ++used;
+  d = Decision{is_i8, gelu, patches, forced, M, N, K, resident, kernel_choice(is_i8, M, N, K, gelu, resident, patches), TilePlan{}};
+  const int64_t k_bytes = K * (is_i8 ? 1 : 2);
+  if (d.choice == 2) d.plan = make_plan((int)M, (int)N, resident, (int)(k_bytes / kStepBytes), gelu);
+  return d;
+}
+
 template <bool IS_I8>
 static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int64_t k_bytes = (int64_t)a.K * (IS_I8 ? 1 : 2);
   const bool gelu = (a.epilogue & GPUSQ_EPI_GELU) != 0;
   const int resident = num_cus();
-  const int choice = kernel_choice(IS_I8, a.M, a.N, a.K, gelu, resident, a.patch_P != 0);
+  const Decision& dec = decide(IS_I8, a.M, a.N, a.K, gelu, resident, a.patch_P != 0);
+  const int choice = dec.choice;
   // the fused patch gather exists in the tile kernel only, for 16 x 16 patches, fp16 output, no GELU
   if (a.patch_P != 0 && (choice != 2 || a.patch_P != 16 || a.out_dt != GPUSQ_F16 || gelu)) return GPUSQ_ERR_UNSUPPORTED;
   if (choice == 0) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);
   if (choice == 1) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);
   // persistent grid: one workgroup per CU, never more workgroups than tiles
   const int ksteps = (int)(k_bytes / kStepBytes);
-  const TilePlan plan = make_plan(a.M, a.N, resident, ksteps, gelu);
+  const TilePlan plan = dec.plan;
   const dim3 grid((unsigned)grid_for(plan, resident));
   if ((ceil_div(plan.total, grid.x) + 2) * ksteps >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
   if ((int64_t)a.N * 16 * 4 >= ((int64_t)1 << 31)) return GPUSQ_ERR_UNSUPPORTED;  // 32-bit lane offsets inside 16 rows of Y
