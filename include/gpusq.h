@@ -22,7 +22,8 @@
  *     points additionally need K % 16 == 0 and N % 4 == 0 (GPUSQ_ERR_UNSUPPORTED otherwise); M is arbitrary.
  *     Sizes must be positive, each dimension below 2^31 and each tensor below 2^40 elements (GPUSQ_ERR_SHAPE).
  *   - Thread safety: calls on distinct streams may run concurrently; the library holds no mutable global state
- *     besides the last HIP error code.
+ *     besides the last HIP error code, the device's CU count (read once) and, per host thread, the kernel choices
+ *     and tile plans of the last few distinct GEMM problems.
  */
 #ifndef GPUSQ_H
 #define GPUSQ_H
