@@ -172,6 +172,19 @@ gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const floa
                                const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale,
                                int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
 
+/* The same product with the quantise node of the activations [Sec. 2.2: activations are quantised at run time with a
+ * calibrated scale before every quantised layer] folded into the GEMM: X [M][K] fp16 is turned into the codes
+ * Xq = clamp(rint(X / act_scale[0]), -127, 127) on its way to the matrix instructions (the code rule of
+ * gpusq_quantize_int8 with scale_is_input != 0; bit-identical to calling that first), so a layer with a static scale is
+ * one launch instead of two.  Only the latency kernel, through whose registers X passes, can do this: a problem that
+ * gpusq_spgemm_plan assigns to the tile kernel (kernel == 2) returns GPUSQ_ERR_UNSUPPORTED and is served by
+ * gpusq_quantize_int8 + gpusq_spgemm_int8.  Every workgroup quantises the rows of its own tile, so the saving is that
+ * of a launch (a few microseconds) against extra work per K step: it pays for short K (up to about 384).
+ * All other arguments as for gpusq_spgemm_int8. */
+gpusq_status gpusq_spgemm_int8_xf16(const void* X, const void* Wpacked, const float* act_scale, const float* w_scale,
+                                    const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale,
+                                    int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
+
 /* ---- patch embedding [Sec. 3.3: the patch-embedding layer is a convolution with C input channels, D_embed output
  * channels and kernel size = stride = P on images N x C x H x W, each P x P patch becoming one token; 2:4 sparsity is
  * applied to it like to the linear layers].  With kernel = stride the convolution is the product of the flattened patches

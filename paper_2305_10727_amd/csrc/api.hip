@@ -278,6 +278,18 @@ gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const floa
   return launch_spgemm(true, a, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_spgemm_int8_xf16(const void* X, const void* Wpacked, const float* act_scale, const float* w_scale,
+                                    const float* bias, void* Y, gpusq_dtype out_dt, const float* out_scale, int64_t M,
+                                    int64_t N, int64_t K, int epilogue, void* stream) {
+  gpusq_status st = check_gemm(X, Wpacked, bias, Y, M, N, K, epilogue);
+  if (st != GPUSQ_OK) return st;
+  st = check_int8_extras(act_scale, w_scale, out_dt, out_scale);
+  if (st != GPUSQ_OK) return st;
+  GemmArgs a{X, Wpacked, act_scale, w_scale, bias, out_scale, Y, (int)M, (int)N, (int)K, epilogue, (int)out_dt};
+  a.x_f16 = 1;
+  return launch_spgemm(true, a, (hipStream_t)stream);
+}
+
 gpusq_status gpusq_gemm_fp16_dense(const void* X, const void* W, const float* bias, void* Y, int64_t M, int64_t N,
                                    int64_t K, int epilogue, void* stream) {
   gpusq_status st = check_gemm(X, W, bias, Y, M, N, K, epilogue);

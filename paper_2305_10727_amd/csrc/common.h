@@ -153,6 +153,8 @@ struct GemmArgs {
   // patch (py, px) of image b, column (c*P + i)*P + j its pixel (py*P + i, px*P + j) of channel c; M = B*(H/P)*(W/P),
   // K = C*P*P.  The tile kernel then fetches its X slabs from the image directly (no flattened-patch buffer).
   int patch_P = 0, patch_C = 0, patch_H = 0, patch_W = 0;
+  // INT8 path, small kernel only: X holds fp16 activations, quantised inside the kernel with the static act_scale
+  int x_f16 = 0;
 };
 
 gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s);

@@ -859,13 +859,17 @@ constexpr int kLdsRow = kStepBytes + 16;  // 144-byte row pitch: 16 rows x 16-by
 // Workgroup = 4 wavefronts arranged WN (along n) x WM (along m); a wavefront owns TN x TM accumulator tiles.
 // Workgroup tile: BN = WN*TN*16 output channels x BM = WM*TM*16 activation rows.  X goes global -> registers -> LDS
 // (zero-filled past the row end and past M), the weight fragments go straight from global memory to registers.
-template <bool IS_I8, int TN, int TM, int WN, int WM>
+// XF16 (INT8 path only): X is given in fp16 and quantised on its way through the registers, with the caller's static
+// activation scale and the code rule of the activation quantiser; a chunk of 16 codes is then 32 bytes in memory.
+template <bool IS_I8, int TN, int TM, int WN, int WM, bool XF16 = false>
 __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, const int tiles_n, const int tiles_total) {
   static_assert(WN * WM == 4 && TN % 4 == 0, "4 wavefronts; a wavefront spans whole 64-row blocks");
+  static_assert(IS_I8 || !XF16, "the fp16 path takes fp16 X as it is");
   typedef typename AccT<IS_I8>::type acc_t;
   constexpr int BN = WN * TN * 16, BM = WM * TM * 16;
   constexpr int ES = IS_I8 ? 1 : 2;
-  constexpr int XCH = BM / 32;  // 16-byte chunks of the X slab each thread moves per K step
+  constexpr int XW = XF16 ? 2 : 1;  // bytes of X in memory per byte of the X operand
+  constexpr int XCH = BM / 32;      // 16-byte chunks of the X slab each thread moves per K step
 
   __shared__ __attribute__((aligned(16))) uint8_t Xs[2][BM * kLdsRow];
   __shared__ __attribute__((aligned(16))) float cs[BN];
@@ -897,8 +901,8 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
 
   // Operands are requested D - 1 K steps ahead, each step into its own set of registers: at these sizes a K step is a
   // few matrix instructions, and what a step costs is the memory latency divided by the number of steps in flight.
-  constexpr int D = TM == 1 ? 6 : 3;
-  v4i xr[D][XCH];
+  constexpr int D = TM == 1 ? (XF16 ? 4 : 6) : 3;  // (fp16 X in flight takes twice the registers per step)
+  v4i xr[D][XCH][XW];
   v4i av[D][TN];
   int ai[D][TN];
 
@@ -906,7 +910,12 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   // offset fixed for the whole tile, so a K step issues its loads with next to no vector arithmetic: with one wavefront
   // per SIMD (a lone wavefront issues a vector instruction only every 6-8 clocks) address arithmetic per load is what a
   // step would otherwise cost.
-  const global_u8* Xtile = uniform_ptr(Xg + (int64_t)m_blk * BM * k_bytes);
+  const global_u8* Xtile = uniform_ptr(Xg + (int64_t)m_blk * BM * k_bytes * XW);
+  float s_x = 1.0f, r_x = 1.0f;
+  if constexpr (XF16) {
+    s_x = a.act_scale[0];
+    r_x = scale_reciprocal(s_x);
+  }
   // Rows past the end of X re-read the last row (their results are never stored), so only a K that is not a whole
   // number of steps needs a predicate, and only in the last step: a plain step is 7 loads and nothing else.
   uint32_t xoff[XCH];
@@ -915,7 +924,7 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   for (int j = 0; j < XCH; ++j) {
     const int c = tid + 256 * j;
     const int row = (c >> 3) < last_row ? (c >> 3) : (int)last_row;
-    xoff[j] = (uint32_t)row * (uint32_t)k_bytes + (c & 7) * 16;  // the host keeps 128 rows of X below 4 GiB
+    xoff[j] = ((uint32_t)row * (uint32_t)k_bytes + (c & 7) * 16) * XW;  // the host keeps 128 rows of X below 4 GiB
   }
   const int tail_bytes = (int)(k_bytes % kStepBytes);  // 0: K is a whole number of steps
   static_assert(TN == 4, "a wavefront's fragments are the four of one 64-channel row block");
@@ -926,22 +935,44 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   const uint32_t a_lane = (uint32_t)(f0 * kFragValueBytes + lane * 16);
   const uint32_t i_lane = (uint32_t)index_offset(IS_I8, f0, lane);  // the index words of fragments f0 .. f0+3 are adjacent
   auto load_x = [&](int ks, int slot) {
-    const global_u8* base = Xtile + (int64_t)ks * kStepBytes;
+    const global_u8* base = Xtile + (int64_t)ks * (kStepBytes * XW);
     if (tail_bytes != 0 && ks + 1 == ksteps) {  // workgroup-uniform: the ragged last step zero-fills past the row end
 #pragma unroll
       for (int j = 0; j < XCH; ++j)
-        xr[slot][j] = (int)(((tid + 256 * j) & 7) * 16) < tail_bytes ? *(const __attribute__((address_space(1))) v4i*)(base + xoff[j])
-                                                                      : v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int h = 0; h < XW; ++h)
+          xr[slot][j][h] = (int)(((tid + 256 * j) & 7) * 16) < tail_bytes
+                               ? *(const __attribute__((address_space(1))) v4i*)(base + xoff[j] + 16 * h)
+                               : v4i{0, 0, 0, 0};
     } else {
 #pragma unroll
-      for (int j = 0; j < XCH; ++j) xr[slot][j] = *(const __attribute__((address_space(1))) v4i*)(base + xoff[j]);
+      for (int j = 0; j < XCH; ++j)
+#pragma unroll
+        for (int h = 0; h < XW; ++h) xr[slot][j][h] = *(const __attribute__((address_space(1))) v4i*)(base + xoff[j] + 16 * h);
     }
   };
   auto store_x = [&](int buf, int slot) {
 #pragma unroll
     for (int j = 0; j < XCH; ++j) {
       const int c = tid + 256 * j;
-      *(v4i*)(&Xs[buf][(c >> 3) * kLdsRow + (c & 7) * 16]) = xr[slot][j];
+      v4i codes;
+      if constexpr (XF16) {
+        // 16 fp16 values -> 16 int8 codes (zero-filled chunks give zero codes)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const ep_v8h x = __builtin_bit_cast(ep_v8h, xr[slot][j][h]);
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = (float)x[e];
+          unsigned lo, hi;
+          quantize_bytes8(v, s_x, r_x, lo, hi);
+          codes[2 * h] = (int)lo;
+          codes[2 * h + 1] = (int)hi;
+        }
+      } else {
+        codes = xr[slot][j][0];
+      }
+      *(v4i*)(&Xs[buf][(c >> 3) * kLdsRow + (c & 7) * 16]) = codes;
     }
   };
   auto load_a = [&](int ks, int slot) {
@@ -1012,7 +1043,14 @@ static gpusq_status launch_small(const GemmArgs& a, hipStream_t s) {
   const int tiles_n = (int)ceil_div(a.N, BN), tiles_m = (int)ceil_div(a.M, BM);
   const int total = tiles_n * tiles_m;
   const int grid = (int)ceil_div(total, 8) * 8;  // whole rounds over the 8 XCDs; surplus workgroups exit at once
-  if ((int64_t)a.K * (IS_I8 ? 1 : 2) * BM >= ((int64_t)1 << 32)) return GPUSQ_ERR_UNSUPPORTED;  // 32-bit lane offsets inside a tile's rows of X
+  const int x_elem_bytes = (IS_I8 && !a.x_f16) ? 1 : 2;
+  if ((int64_t)a.K * x_elem_bytes * BM >= ((int64_t)1 << 32)) return GPUSQ_ERR_UNSUPPORTED;  // 32-bit lane offsets inside a tile's rows of X
+  if constexpr (IS_I8) {
+    if (a.x_f16) {
+      spgemm_small_kernel<true, TN, TM, WN, WM, true><<<grid, 256, 0, s>>>(a, tiles_n, total);
+      return check_launch();
+    }
+  }
   spgemm_small_kernel<IS_I8, TN, TM, WN, WM><<<grid, 256, 0, s>>>(a, tiles_n, total);
   return check_launch();
 }
@@ -1185,6 +1223,8 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const int choice = dec.choice;
   // the fused patch gather exists in the tile kernel only, for 16 x 16 patches, fp16 output, no GELU
   if (a.patch_P != 0 && (choice != 2 || a.patch_P != 16 || a.out_dt != GPUSQ_F16 || gelu)) return GPUSQ_ERR_UNSUPPORTED;
+  // quantising fp16 activations on the way in exists in the small kernel only (X passes through its registers)
+  if (a.x_f16 && (!IS_I8 || choice == 2)) return GPUSQ_ERR_UNSUPPORTED;
   if (choice == 0) return launch_small<IS_I8, 4, 1, 1, 4>(a, s);
   if (choice == 1) return launch_small<IS_I8, 4, 4, 2, 2>(a, s);
   // persistent grid: one workgroup per CU, never more workgroups than tiles

@@ -23,7 +23,7 @@ EXPORTS = [
     "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
     "gpusq_quantize_workspace_bytes",
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
-    "gpusq_spgemm_int8", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
+    "gpusq_spgemm_int8", "gpusq_spgemm_int8_xf16", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
     "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
     "gpusq_int4_to_sparse_int8", "gpusq_prune_n_of_m",
 ]
@@ -67,6 +67,8 @@ def lib():
         L.gpusq_prepare_weights.restype = ci
         L.gpusq_spgemm_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_int8.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+        L.gpusq_spgemm_int8_xf16.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+        L.gpusq_spgemm_int8_xf16.restype = ci
         L.gpusq_gemm_fp16_dense.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.gpusq_gemm_int8_dense.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
         L.gpusq_im2col_patches.argtypes = [vp, vp, ci, i64, i64, i64, i64, i64, i64, vp]
@@ -316,6 +318,18 @@ def spgemm_int8(Xq, Wpacked, N, act_scale=None, w_scale=None, bias=None, gelu=Fa
     _check(lib().gpusq_spgemm_int8(_ptr(Xq), _ptr(Wpacked), _ptr(act_scale), _ptr(w_scale), _ptr(bias), _ptr(Y),
                                    _TORCH_DT[out_dtype], _ptr(out_scale), M, N, K, _epi(bias, gelu), _stream()),
            "gpusq_spgemm_int8")
+    return Y
+
+
+def spgemm_int8_xf16(X, Wpacked, N, act_scale, w_scale, bias=None, gelu=False, out_dtype=torch.float16, out_scale=None,
+                     out=None):
+    """X fp16 [M,K], quantised inside the GEMM with the static act_scale (latency kernel only: raises GpusqError with
+    ERR_UNSUPPORTED for problems that spgemm_plan assigns to the tile kernel)"""
+    M, K = X.shape
+    Y = torch.empty((M, N), dtype=out_dtype, device=X.device) if out is None else out
+    _check(lib().gpusq_spgemm_int8_xf16(_ptr(X), _ptr(Wpacked), _ptr(act_scale), _ptr(w_scale), _ptr(bias), _ptr(Y),
+                                        _TORCH_DT[out_dtype], _ptr(out_scale), M, N, K, _epi(bias, gelu), _stream()),
+           "gpusq_spgemm_int8_xf16")
     return Y
 
 

@@ -84,6 +84,21 @@ class SparseLinear:
                      "gpusq_spgemm_fp16")
         return self.Y
 
+    def takes_fp16_input(self):
+        """True when the INT8 GEMM of this layer should quantise fp16 activations itself (static scale): the problem
+        goes to the latency kernel, the only one that can, and K is short.  Every workgroup quantises the X rows of its
+        own tile, K step by K step, which costs it about 0.5 us per step; the launch this saves is worth 2.5-3 us
+        (measured per block at batch 1: K = 192 29 -> 25 us, K = 384 30 -> 29 us, K = 768 34 -> 43 us)."""
+        return (self.precision == "int8" and self.K <= 384 and
+                G.spgemm_plan(torch.int8, self.M, self.N, self.K, self.epilogue)["kernel"] != 2)
+
+    def gemm_from_f16(self, X, bias, out_scale=None):
+        """INT8 path with a static act_scale: quantise + GEMM in one launch (see takes_fp16_input)"""
+        G._check(G.lib().gpusq_spgemm_int8_xf16(_p(X), _p(self.packed), _p(self.act_scale), _p(self.w_scale), _p(bias), _p(self.Y),
+                                                G._TORCH_DT[self.out_dtype], _p(out_scale), self.M, self.N, self.K, self.epilogue,
+                                                G._stream()), "gpusq_spgemm_int8_xf16")
+        return self.Y
+
     def gemm_dense(self, X, bias, out_scale=None):
         """the dense twin on the same masked weights"""
         L, s = G.lib(), G._stream()
@@ -171,10 +186,11 @@ class EncoderBlockLinears:
     activation scales, the deployment form with quantise / dequantise nodes around every linear layer: the
     re-quantisation of a layer's output with the next layer's input scale is fused into its epilogue (qkv -> int8,
     fc1 -> GELU -> int8, which fc2 reads directly), so one block is six launches of the library:
-        quantise x, qkv, [attention], proj, [residual + norm], quantise h, fc1 (GELU), fc2.
+        quantise x, qkv, [attention], proj, [residual + norm], quantise h, fc1 (GELU), fc2;
+    with few rows (problems of the latency kernel) qkv and fc1 quantise their fp16 input on the way in: four launches.
     Attention and the normalisation are not part of the library: `attention(qkv_int8 [M,3D], out_int8 [M,D])` and
     `norm(proj_fp16 [M,D]) -> fp16 [M,D]` are the caller's (stubs in the tests and the report).  capture() records the
-    whole sequence into a HIP graph, which removes the launch gaps that dominate at batch 1.
+    whole sequence into a HIP graph, which takes the host out of the loop.
 
     scales: dict of 1-element fp32 device tensors: x (block input), qkv (qkv output), attn (attention output),
     h (fc1 input), g (GELU output = fc2 input)."""
@@ -191,6 +207,8 @@ class EncoderBlockLinears:
         self.fc1.act_scale = scales["h"]
         self.fc2.act_scale = scales["g"]
         self.fc2.Xq = self.fc1.Y  # fc2 reads the codes fc1's epilogue wrote: no pass in between
+        # few rows (the latency kernel): qkv and fc1 quantise their fp16 input themselves, four launches per block
+        self.fold_quantise = self.qkv.takes_fp16_input() and self.fc1.takes_fp16_input()
         self.graph = None
 
     def prepare_weights(self, Wqkv, Wproj, Wfc1, Wfc2):
@@ -199,14 +217,20 @@ class EncoderBlockLinears:
 
     def forward(self, x, biases, attention, norm=None):
         """x fp16 [M,D]; biases: (b_qkv, b_proj, b_fc1, b_fc2); returns fc2's fp16 output [M,D] (a buffer of this object)"""
-        self.qkv.quantize_activations(x, static=True)
-        self.qkv.gemm(None, biases[0], self.scales["qkv"])
+        if self.fold_quantise:
+            self.qkv.gemm_from_f16(x, biases[0], self.scales["qkv"])
+        else:
+            self.qkv.quantize_activations(x, static=True)
+            self.qkv.gemm(None, biases[0], self.scales["qkv"])
         attention(self.qkv.Y, self.proj.Xq)
         h = self.proj.gemm(None, biases[1])
         if norm is not None:
             h = norm(h)
-        self.fc1.quantize_activations(h, static=True)
-        self.fc1.gemm(None, biases[2], self.scales["g"])
+        if self.fold_quantise:
+            self.fc1.gemm_from_f16(h, biases[2], self.scales["g"])
+        else:
+            self.fc1.quantize_activations(h, static=True)
+            self.fc1.gemm(None, biases[2], self.scales["g"])
         return self.fc2.gemm(None, biases[3])
 
     def capture(self, x, biases, attention, norm=None):

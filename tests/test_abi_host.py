@@ -69,6 +69,12 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_spgemm_int8(good, good, good, good, None, good, 1, None, 8, 8, 32, 1, None) == ERR_NULL  # bias flag
     assert lib.gpusq_spgemm_int8(good, good, good, good, None, good, 2, None, 8, 8, 32, 0, None) == ERR_NULL  # out_scale
     assert lib.gpusq_spgemm_int8(good, good, good, good, None, good, 1, None, 8, 8, 32, 8, None) == ERR_UNSUPPORTED
+    # fp16 activations quantised inside the GEMM: the same checks, and problems of the tile kernel are refused
+    lib.gpusq_spgemm_int8_xf16.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, i64, i64, i64, ci, vp]
+    assert lib.gpusq_spgemm_int8_xf16(good, good, None, None, None, good, 1, None, 8, 8, 32, 0, None) == ERR_NULL  # scales
+    assert lib.gpusq_spgemm_int8_xf16(good, good, good, good, None, good, 2, None, 8, 8, 32, 0, None) == ERR_NULL  # out_scale
+    assert lib.gpusq_spgemm_int8_xf16(good, good, good, good, None, odd, 1, None, 8, 8, 32, 0, None) == ERR_ALIGN
+    assert lib.gpusq_spgemm_int8_xf16(good, good, good, good, None, good, 1, None, 12608, 3072, 768, 0, None) == ERR_UNSUPPORTED
     lib.gpusq_spgemm_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp]
     assert lib.gpusq_spgemm_fp16(good, None, None, good, 8, 8, 32, 0, None) == ERR_NULL
     assert lib.gpusq_spgemm_fp16(good, good, None, odd, 8, 8, 32, 0, None) == ERR_ALIGN

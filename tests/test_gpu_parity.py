@@ -656,6 +656,51 @@ def test_fused_patch_embedding_matches_the_convolution_oracle(g, B, C, H, W, D, 
 
 
 # ------------------------------------------------------------------------------------------------ chained INT8 block
+@pytest.mark.parametrize("kernel", [None, 0, 1])
+@pytest.mark.parametrize("M,K,N,seed", [(197, 192, 768, 61), (197, 768, 2304, 62), (50, 80, 36, 63), (333, 1040, 520, 64), (1, 16, 4, 65)])
+def test_int8_gemm_quantising_fp16_activations_itself(g, force_kernel, M, K, N, seed, kernel):
+    """gpusq_spgemm_int8_xf16 (static activation scale, latency kernel) against the oracle's quantiser followed by its
+    sparse GEMM and epilogue, and against the library's own two-launch route: bit-exact accumulators, fp16 and int8
+    outputs; shapes with a ragged last K step, rows past M inside a tile, several K passes."""
+    force_kernel(kernel)
+    rng = np.random.default_rng(seed)
+    X = (rng.standard_normal((M, K)) * 1.5).astype(np.float16)
+    if M * K > 8:
+        X.reshape(-1)[:8] = np.array([0.0, -0.0, 65504.0, -65504.0, 6e-8, 1.0, -1.0, 0.5], np.float16)  # extremes: clamped / zero codes
+    W = synth.weights(N, K, seed=seed, ids=(1,), sigma=0.05)
+    bias = synth.bias(N, seed=seed, ids=(2,))
+    Wq, s_w, vals, meta = _oracle_weights(W)
+    s_a = np.float32(4.0 / 127.0)  # a static scale that clips the tails
+    Xq, _ = oracle.quantize_tensor_int8(X.astype(np.float32), scale=float(s_a))
+    acc = oracle.spgemm_int8(Xq, vals, meta)
+    v, m = g.compress(dev(Wq))
+    packed = g.pack(v, m, K)
+    sa, sw, b = dev(np.array([s_a], np.float32)), dev(s_w), dev(bias)
+    Xd = dev(X)
+    raw = g.spgemm_int8_xf16(Xd, packed, N, sa, sw, out_dtype=torch.int32)
+    assert np.array_equal(host(raw), acc)
+    y = host(g.spgemm_int8_xf16(Xd, packed, N, sa, sw, bias=b))
+    assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(acc, float(s_a), s_w, bias)["y16"].view(np.uint16))
+    so = np.float32(max(np.abs(acc).max(), 1) * s_a * s_w.max() / 127.0)
+    q = host(g.spgemm_int8_xf16(Xd, packed, N, sa, sw, bias=b, out_dtype=torch.int8, out_scale=dev(np.array([so], np.float32))))
+    assert np.array_equal(q, oracle.epilogue_int8_f32(acc, float(s_a), s_w, bias, out_scale=float(so))["q8"])
+    # the two-launch route of the library gives the same bits
+    Xq_d, _ = g.quantize_int8(Xd, g.PER_TENSOR, scale=sa)
+    assert np.array_equal(host(Xq_d), Xq)
+    assert torch.equal(g.spgemm_int8(Xq_d, packed, N, out_dtype=torch.int32), raw)
+
+
+def test_int8_gemm_quantising_fp16_activations_refuses_tile_kernel_problems(g):
+    M, K, N = 4096, 256, 1024
+    assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] == 2
+    z = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    packed = torch.zeros((g.packed_bytes(torch.int8, N, K),), dtype=torch.uint8, device="cuda")
+    one = torch.ones((1,), dtype=torch.float32, device="cuda")
+    with pytest.raises(g.GpusqError) as e:
+        g.spgemm_int8_xf16(z, packed, N, one, torch.ones((N,), dtype=torch.float32, device="cuda"))
+    assert e.value.status == g.ERR_UNSUPPORTED
+
+
 def _oracle_weights(W):
     P, _ = oracle.prune_2to4(W)
     Wq, s_w = oracle.quantize_rows_int8(P)
@@ -705,9 +750,21 @@ def test_encoder_block_chain_and_its_graph(g, M, D, hidden, seed):
     blk.prepare_weights(*[dev(W) for W in Ws])
     x, biases = dev(X), [dev(b) for b in bs]
     stub = lambda q, out: out.copy_(q[:, 2 * D:])
+    # first with a quantise launch in front of qkv and fc1 (six launches), which leaves the codes to look at; then, for
+    # few rows, the route the helper picks there: qkv and fc1 quantise their fp16 input themselves (four launches)
+    folds = blk.fold_quantise
+    assert folds == (M < 1000 and D <= 384)
+    blk.fold_quantise = False
     y = host(blk.forward(x, biases, stub))
     assert np.array_equal(host(blk.qkv.Xq), Xq) and np.array_equal(host(blk.qkv.Y), qkv)
     assert np.array_equal(host(blk.proj.Y).view(np.uint16), proj.view(np.uint16)) and np.array_equal(host(blk.fc1.Xq), hq)
+    if folds:
+        codes6, y6 = blk.fc1.Y.clone(), blk.fc2.Y.clone()
+        blk.fold_quantise = True
+        for t in (blk.qkv.Y, blk.proj.Y, blk.fc1.Y, blk.fc2.Y):
+            t.zero_()
+        y = host(blk.forward(x, biases, stub))
+        assert np.array_equal(host(blk.qkv.Y), qkv) and torch.equal(blk.fc1.Y, codes6) and torch.equal(blk.fc2.Y, y6)
     g_hip = host(blk.fc1.Y).astype(np.int32)
     flips = g_hip != gq.astype(np.int32)
     assert np.abs(g_hip - gq).max() <= 1 and flips.mean() < 5e-3
