@@ -858,7 +858,8 @@ constexpr int kLdsRow = kStepBytes + 16;  // 144-byte row pitch: 16 rows x 16-by
 
 // Workgroup = 4 wavefronts arranged WN (along n) x WM (along m); a wavefront owns TN x TM accumulator tiles.
 // Workgroup tile: BN = WN*TN*16 output channels x BM = WM*TM*16 activation rows.  X goes global -> registers -> LDS
-// (zero-filled past the row end and past M), the weight fragments go straight from global memory to registers.
+// (zero-filled past the row end, rows past M re-read the last row), and so do the weight fragments and index words of
+// the tile, a 256th of them per thread.
 // XF16 (INT8 path only): X is given in fp16 and quantised on its way through the registers, with the caller's static
 // activation scale and the code rule of the activation quantiser; a chunk of 16 codes is then 32 bytes in memory.
 template <bool IS_I8, int TN, int TM, int WN, int WM, bool XF16 = false>
@@ -871,7 +872,11 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   constexpr int XW = XF16 ? 2 : 1;  // bytes of X in memory per byte of the X operand
   constexpr int XCH = BM / 32;      // 16-byte chunks of the X slab each thread moves per K step
 
+  constexpr int RBW = BN / kRowBlock;  // 64-channel row blocks of the workgroup's tile (= WN: a wavefront spans one)
+  constexpr int kAStep = RBW * 4 * kFragValueBytes;  // kept values of the tile per K step; 1 KB of index words per row block behind them
+  static_assert(RBW == WN && (RBW == 1 || RBW == 2), "the workgroup's fragments lie in one packed tile");
   __shared__ __attribute__((aligned(16))) uint8_t Xs[2][BM * kLdsRow];
+  __shared__ __attribute__((aligned(16))) uint8_t As[2][kAStep + RBW * 1024];
   __shared__ __attribute__((aligned(16))) float cs[BN];
   __shared__ __attribute__((aligned(16))) float bs[BN];
 
@@ -889,7 +894,6 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   }
   const int64_t k_bytes = (int64_t)a.K * ES;
   const int ksteps = (int)((k_bytes + kStepBytes - 1) / kStepBytes);
-  const int rb0 = (n_blk * BN + wn * TN * 16) / kRowBlock;
   const uint8_t* Xg = (const uint8_t*)a.X;
   const uint8_t* Wg = (const uint8_t*)a.W;
 
@@ -903,8 +907,8 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   // few matrix instructions, and what a step costs is the memory latency divided by the number of steps in flight.
   constexpr int D = TM == 1 ? (XF16 ? 4 : 6) : 3;  // (fp16 X in flight takes twice the registers per step)
   v4i xr[D][XCH][XW];
-  v4i av[D][TN];
-  int ai[D][TN];
+  v4i ar[D][RBW];  // this thread's 16-byte pieces of the tile's kept values (thread t: lane t % 64 of fragment t / 64 + 4j)
+  v4i ir[D];       // threads below 64 * RBW: the index words of lane t % 64 for row block t / 64
 
   // Addresses: a wavefront-uniform base that advances by a constant per K step (scalar arithmetic) plus a 32-bit lane
   // offset fixed for the whole tile, so a K step issues its loads with next to no vector arithmetic: with one wavefront
@@ -928,12 +932,17 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   }
   const int tail_bytes = (int)(k_bytes % kStepBytes);  // 0: K is a whole number of steps
   static_assert(TN == 4, "a wavefront's fragments are the four of one 64-channel row block");
-  // (the packed buffer is padded to whole 256-channel tiles, so the wavefront's row block always exists: rb < row_blocks)
-  const int rb = rb0;
-  const int f0 = (rb & 3) * 4;
-  const global_u8* Wrow = uniform_ptr(Wg + (int64_t)(rb >> 2) * ksteps * tile_bytes(IS_I8));
-  const uint32_t a_lane = (uint32_t)(f0 * kFragValueBytes + lane * 16);
-  const uint32_t i_lane = (uint32_t)index_offset(IS_I8, f0, lane);  // the index words of fragments f0 .. f0+3 are adjacent
+  // The weights, like X, enter the CU once per workgroup and K step and reach the wavefronts through LDS: the
+  // wavefronts along m need the same fragments, and fetched by each of them straight into registers they were what
+  // bound a K step (4 x 5 KB + 8 KB of X per step is all a CU can draw from the L2).
+  // (the packed buffer is padded to whole 256-channel tiles, so the tile's row blocks always exist)
+  const int rbw = n_blk * RBW;
+  const int f0 = (rbw & 3) * 4;
+  const global_u8* Wrow = uniform_ptr(Wg + (int64_t)(rbw >> 2) * ksteps * tile_bytes(IS_I8));
+  const uint32_t a_thr = (uint32_t)(f0 * kFragValueBytes + tid * 16);
+  const bool idx_thr = tid < 64 * RBW;  // (whole wavefronts)
+  // the index words of the 4 fragments of a row block are adjacent per lane: 16 bytes (int8) or 8 bytes (fp16)
+  const uint32_t i_thr = (uint32_t)index_offset(IS_I8, f0 + 4 * ((tid >> 6) & (RBW - 1)), lane);
   auto load_x = [&](int ks, int slot) {
     const global_u8* base = Xtile + (int64_t)ks * (kStepBytes * XW);
     if (tail_bytes != 0 && ks + 1 == ksteps) {  // workgroup-uniform: the ragged last step zero-fills past the row end
@@ -978,19 +987,21 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   auto load_a = [&](int ks, int slot) {
     const global_u8* t = Wrow + (int64_t)ks * tile_bytes(IS_I8);
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
-      av[slot][tn] = *(const __attribute__((address_space(1))) v4i*)(t + a_lane + tn * kFragValueBytes);
-    if constexpr (IS_I8) {
-      const v4i w = *(const __attribute__((address_space(1))) v4i*)(t + i_lane);
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) ai[slot][tn] = w[tn];
-    } else {
-      const ep_v2u w = *(const __attribute__((address_space(1))) ep_v2u*)(t + i_lane);
-      ai[slot][0] = (int)(w[0] & 0xFFFFu);
-      ai[slot][1] = (int)(w[0] >> 16);
-      ai[slot][2] = (int)(w[1] & 0xFFFFu);
-      ai[slot][3] = (int)(w[1] >> 16);
+    for (int j = 0; j < RBW; ++j)
+      ar[slot][j] = *(const __attribute__((address_space(1))) v4i*)(t + a_thr + j * (4 * kFragValueBytes));
+    if (idx_thr) {
+      if constexpr (IS_I8) {
+        ir[slot] = *(const __attribute__((address_space(1))) v4i*)(t + i_thr);
+      } else {
+        const ep_v2u w = *(const __attribute__((address_space(1))) ep_v2u*)(t + i_thr);
+        ir[slot] = v4i{(int)w[0], (int)w[1], 0, 0};
+      }
     }
+  };
+  auto store_a = [&](int buf, int slot) {
+#pragma unroll
+    for (int j = 0; j < RBW; ++j) *(v4i*)(&As[buf][tid * 16 + j * (4 * kFragValueBytes)]) = ar[slot][j];
+    if (idx_thr) *(v4i*)(&As[buf][kAStep + tid * 16]) = ir[slot];
   };
 
   // K steps q * D + r: q passes of D steps without any condition in them (the request D - 1 steps ahead is clamped to
@@ -1004,20 +1015,43 @@ __global__ void __launch_bounds__(256) spgemm_small_kernel(const GemmArgs a, con
   }
   const int b_row = wm * TM * 16 + (lane & 15);
   const int b_col = (lane >> 4) * 16;
+  // The operands alternate between two LDS buffers, and the step is pipelined across them: step ks first writes the
+  // operands of step ks + 1 into the other buffer (last read in step ks - 1, whose closing barrier every wavefront has
+  // passed), then reads its own, multiplies, and closes with the barrier that publishes what it wrote.  So the LDS round
+  // trip of a step's operands runs beside the previous step's reads and matrix instructions instead of in front of its
+  // own.
+  store_x(0, 0);
+  store_a(0, 0);
+  __syncthreads();
   auto compute_step = [&](int ks, int slot) {
-    // The X slab alternates between two LDS buffers; the barrier of step ks - 1 lies behind every wavefront's reads of
-    // step ks - 2, which used this buffer last.
     const int cur = ks & 1;
-    store_x(cur, slot);
-    __syncthreads();
+    if (ks + 1 < ksteps) {  // workgroup-uniform
+      store_x(cur ^ 1, (slot + 1) % D);
+      store_a(cur ^ 1, (slot + 1) % D);
+    }
+    v4i av[TN];
+    int ai[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) av[tn] = *(const v4i*)(&As[cur][(wn * TN + tn) * kFragValueBytes + lane * 16]);
+    const v4i iw = *(const v4i*)(&As[cur][kAStep + wn * 1024 + lane * 16]);
+    if constexpr (IS_I8) {
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) ai[tn] = iw[tn];
+    } else {
+      ai[0] = iw[0] & 0xFFFF;
+      ai[1] = (int)((unsigned)iw[0] >> 16);
+      ai[2] = iw[1] & 0xFFFF;
+      ai[3] = (int)((unsigned)iw[1] >> 16);
+    }
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
       const uint8_t* p = &Xs[cur][(b_row + mt * 16) * kLdsRow + b_col];
       const v4i lo = *(const v4i*)p, hi = *(const v4i*)(p + 64);
       const v8i b = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[slot][tn], b, acc[tn][mt], ai[slot][tn]);
+      for (int tn = 0; tn < TN; ++tn) acc[tn][mt] = smfmac<IS_I8>(av[tn], b, acc[tn][mt], ai[tn]);
     }
+    __syncthreads();
   };
   const int passes = ksteps / D, rest = ksteps - passes * D;
   int ks = 0;
@@ -1136,7 +1170,7 @@ static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
 // Which kernel a problem takes: 0 = small kernel with 64 x 64 tiles, 1 = small kernel with 128 x 128 tiles, 2 = tile
 // kernel.  K that is not a whole number of 128-byte steps needs the zero-filling small kernel.  Otherwise the estimated
 // run times decide (microseconds, fitted to graph-replayed launches on MI355X for M = 197 ... 6304): the small kernel
-// keeps two workgroups per CU busy, costs about 0.8 us per K step and round of 512 workgroups and never less than what
+// keeps two workgroups per CU busy, costs about 0.7 us + 0.45 us per K step per round of 512 workgroups and never less than what
 // one workgroup's chain of loads takes; the tile kernel costs its plan's makespan plus the start-up of its pipeline.
 // With few rows (one image: M = 197) the tile kernel has too few tiles for the chip and the small kernel is about
 // twice as fast; from a few thousand rows on the tile kernel wins.  fused_patches: the patch gather exists in the tile
@@ -1156,8 +1190,8 @@ static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu,
   if (k_bytes % kStepBytes != 0) return wgs64 <= 2 * resident ? 0 : 1;
   if (fused_patches) return 2;
   if (wgs64 > 16 * resident) return 2;  // far beyond the crossover: skip the planning
-  const double per_round = 0.8 * ksteps, chain = 3.6 + 0.25 * ksteps;
-  const double throughput = 4.5 + per_round * (double)wgs64 / (2.0 * resident);
+  const double per_round = 0.7 + 0.45 * ksteps, chain = 3.6 + 0.25 * ksteps;
+  const double throughput = 4.0 + per_round * (double)wgs64 / (2.0 * resident);
   const double est_small = chain > throughput ? chain : throughput;
   const TilePlan p = make_plan((int)M, (int)N, resident, (int)ksteps, gelu);
   const int grid = grid_for(p, resident);

@@ -753,7 +753,7 @@ def test_encoder_block_chain_and_its_graph(g, M, D, hidden, seed):
     # first with a quantise launch in front of qkv and fc1 (six launches), which leaves the codes to look at; then, for
     # few rows, the route the helper picks there: qkv and fc1 quantise their fp16 input themselves (four launches)
     folds = blk.fold_quantise
-    assert folds == (M < 1000 and D <= 384)
+    assert folds == (M <= 256 and D <= 384)
     blk.fold_quantise = False
     y = host(blk.forward(x, biases, stub))
     assert np.array_equal(host(blk.qkv.Xq), Xq) and np.array_equal(host(blk.qkv.Y), qkv)
