@@ -22,8 +22,9 @@
  *     points additionally need K % 16 == 0 and N % 4 == 0 (GPUSQ_ERR_UNSUPPORTED otherwise); M is arbitrary.
  *     Sizes must be positive, each dimension below 2^31 and each tensor below 2^40 elements (GPUSQ_ERR_SHAPE).
  *   - Thread safety: calls on distinct streams may run concurrently; the library holds no mutable global state
- *     besides the last HIP error code, the device's CU count (read once) and, per host thread, the kernel choices
- *     and tile plans of the last few distinct GEMM problems.
+ *     besides the last HIP error code, each device's CU count (read once), the testing override of
+ *     gpusq_force_kernel and, per host thread, the kernel choices and tile plans of the last few distinct GEMM
+ *     problems.
  */
 #ifndef GPUSQ_H
 #define GPUSQ_H
@@ -217,10 +218,16 @@ gpusq_status gpusq_patch_embed16_fp16(const void* img, const void* Wpacked, cons
  * (a full tile has u * full_tm rows), out[4] = row chunks covered by full tiles, out[5] = tail_tm (the remaining rows
  * are cut into tiles of u * tail_tm rows), out[6] = tiles in all, out[7] = workgroups launched.  Same argument checks
  * as the GEMM calls (sizes only).
- * The environment variable GPUSQ_FORCE_KERNEL (0, 1 or 2; read at every call) overrides out[0] and the kernel the
- * GEMM entry points launch, where the forced kernel can run the problem: a testing aid, so that both kernels can be
- * checked on the same shapes. */
+ * The query describes gpusq_spgemm_fp16 / gpusq_spgemm_int8 only: the fused patch-embedding calls
+ * (gpusq_patch_embed16_*) always run on the tile kernel, whatever this query reports for a GEMM of the same sizes. */
 gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]);
+
+/* Testing aid: kernel = 0, 1 or 2 makes the sparse GEMM entry points (and gpusq_spgemm_plan's out[0]) take that kernel
+ * for every problem it can run (kernel 2 needs K * element size % 128 == 0), so that every kernel can be checked on the
+ * same shapes; any other value gives the choice back to the size rules.  Returns the previous setting (-1 = none).
+ * Process-wide; the environment variable GPUSQ_FORCE_KERNEL (0, 1 or 2) gives the initial setting and is read once,
+ * when the library is loaded.  Not meant for production callers. */
+int gpusq_force_kernel(int kernel);
 
 /* ---- dense twins: the same computation from the masked but uncompressed W [N][K], on dense matrix instructions,
  * built the same way; the baseline the sparse kernels are compared with. */

@@ -259,6 +259,8 @@ gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, 
   return plan_spgemm(dt == GPUSQ_I8, M, N, K, epilogue, cus, out);
 }
 
+int gpusq_force_kernel(int kernel) { return set_forced_kernel(kernel); }
+
 gpusq_status gpusq_spgemm_fp16(const void* X, const void* Wpacked, const float* bias, void* Y, int64_t M, int64_t N,
                                int64_t K, int epilogue, void* stream) {
   gpusq_status st = check_gemm(X, Wpacked, bias, Y, M, N, K, epilogue);

@@ -19,6 +19,7 @@
 //                       global->LDS copies (no staging registers), one persistent workgroup of 8 wavefronts per CU.
 //                       Needs K*elemsize % 128 == 0.
 //   spgemm_small_kernel 64 x 64 / 128 x 128 tiles through registers; any K % 16 == 0; used for small or ragged-K problems.
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -1089,14 +1090,30 @@ static gpusq_status launch_small(const GemmArgs& a, hipStream_t s) {
   return check_launch();
 }
 
+// Compute units of the current device, read once per device (a racing first call reads the same value twice).
 static int num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cus = n;
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> cus[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+  int n = cus[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cus[dev].store(n, std::memory_order_relaxed);
   }
-  return cus;
+  return n;
+}
+
+// Testing aid: -1 = the size rules decide, 0 / 1 / 2 = run every problem the kernel can take on that kernel.  Set by
+// gpusq_force_kernel(); the environment variable GPUSQ_FORCE_KERNEL gives the initial value and is read once, when the
+// library is loaded, so that no launch pays for an environment lookup.
+static int initial_forced_kernel() {
+  const char* f = getenv("GPUSQ_FORCE_KERNEL");
+  return (f && f[0] >= '0' && f[0] <= '2' && f[1] == 0) ? f[0] - '0' : -1;
+}
+static std::atomic<int> g_forced_kernel{initial_forced_kernel()};
+int set_forced_kernel(int kernel) {
+  return g_forced_kernel.exchange(kernel >= 0 && kernel <= 2 ? kernel : -1);
 }
 
 // Estimated run time (microseconds, fitted to traces and timings of the kernel on MI355X) of one tile of 64*tm rows: a
@@ -1179,12 +1196,9 @@ static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu,
   const int64_t k_bytes = K * (is_i8 ? 1 : 2);
   const int64_t ksteps = ceil_div(k_bytes, kStepBytes);
   const int64_t wgs64 = ceil_div(M, 64) * ceil_div(N, 64);
-  // Testing aid: GPUSQ_FORCE_KERNEL = 0, 1 or 2 overrides the choice (2 only where the tile kernel can run the problem).
-  if (const char* f = getenv("GPUSQ_FORCE_KERNEL")) {
-    if (f[0] >= '0' && f[0] <= '2' && f[1] == 0) {
-      const int c = f[0] - '0';
-      if (c != 2 || k_bytes % kStepBytes == 0) return c;
-    }
+  // Testing aid: a forced kernel overrides the choice (2 only where the tile kernel can run the problem).
+  if (const int c = g_forced_kernel.load(std::memory_order_relaxed); c >= 0) {
+    if (c != 2 || k_bytes % kStepBytes == 0) return c;
   }
   if (M * N <= (int64_t)256 * 1024) return 0;
   if (k_bytes % kStepBytes != 0) return wgs64 <= 2 * resident ? 0 : 1;
@@ -1222,7 +1236,7 @@ gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilog
 // takes the host several microseconds, which is what a launch of a 10 us GEMM is bound by when it is repeated.
 struct Decision {
   bool is_i8, gelu, patches;
-  char forced;  // first character of GPUSQ_FORCE_KERNEL, 0 when unset
+  int forced;  // the forced kernel when the decision was taken, -1 for none
   int64_t M, N, K;
   int resident, choice;
   TilePlan plan;  // valid when choice == 2
@@ -1231,8 +1245,7 @@ static const Decision& decide(bool is_i8, int64_t M, int64_t N, int64_t K, bool 
   constexpr int kSlots = 16;
   thread_local Decision cache[kSlots];
   thread_local int used = 0, next = 0;
-  const char* f = getenv("GPUSQ_FORCE_KERNEL");
-  const char forced = (f && f[0] && f[1] == 0) ? f[0] : (char)0;
+  const int forced = g_forced_kernel.load(std::memory_order_relaxed);
   for (int i = 0; i < used; ++i) {
     const Decision& d = cache[i];
     if (d.M == M && d.N == N && d.K == K && d.is_i8 == is_i8 && d.gelu == gelu && d.patches == patches && d.forced == forced &&
@@ -1267,6 +1280,8 @@ static gpusq_status launch_typed(const GemmArgs& a, hipStream_t s) {
   const dim3 grid((unsigned)grid_for(plan, resident));
   if ((ceil_div(plan.total, grid.x) + 2) * ksteps >= ((int64_t)1 << 30)) return GPUSQ_ERR_UNSUPPORTED;
   if ((int64_t)a.N * 16 * 4 >= ((int64_t)1 << 31)) return GPUSQ_ERR_UNSUPPORTED;  // 32-bit lane offsets inside 16 rows of Y
+  // 32-bit lane offsets inside the 256 rows of X of a tile (tile_x_offsets; the patch gather has its own limit)
+  if (a.patch_P == 0 && 255 * k_bytes + kStepBytes >= ((int64_t)1 << 32)) return GPUSQ_ERR_UNSUPPORTED;
   if (a.patch_P != 0) {
     spgemm_tile_kernel<IS_I8, 0, GPUSQ_F16, true><<<grid, 512, 0, s>>>(a, plan);
     return check_launch();

@@ -25,7 +25,7 @@ EXPORTS = [
     "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_spgemm_int8_xf16", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
     "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
-    "gpusq_int4_to_sparse_int8", "gpusq_prune_n_of_m",
+    "gpusq_int4_to_sparse_int8", "gpusq_prune_n_of_m", "gpusq_force_kernel",
 ]
 
 
@@ -75,6 +75,8 @@ def lib():
         L.gpusq_patch_embed16_int8.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_patch_embed16_fp16.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, vp]
         L.gpusq_spgemm_plan.argtypes = [ci, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
+        L.gpusq_force_kernel.argtypes = [ci]
+        L.gpusq_force_kernel.restype = ci
         L.gpusq_prune_4to8_pairs.argtypes = [vp, vp, vp, ci, i64, i64, vp]
         L.gpusq_prune_n_of_m.argtypes = [vp, vp, ci, ci, i64, i64, vp]
         L.gpusq_int4_to_sparse_int8.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp]
@@ -261,6 +263,12 @@ def spgemm_plan(dtype, M, N, K, epilogue=0, cus=0):
     _check(lib().gpusq_spgemm_plan(_TORCH_DT[dtype], M, N, K, epilogue, cus, out), "gpusq_spgemm_plan")
     keys = ("kernel", "unit_rows", "tiles_n", "full_tm", "full_chunks", "tail_tm", "tiles", "workgroups")
     return dict(zip(keys, list(out)))
+
+
+def force_kernel(kernel):
+    """gpusq_force_kernel (testing aid): 0 / 1 / 2 = run the sparse GEMMs on that kernel, None or -1 = size rules.
+    Returns the previous setting."""
+    return lib().gpusq_force_kernel(-1 if kernel is None else int(kernel))
 
 
 def packed_bytes(dtype, N, K):

@@ -183,3 +183,37 @@ def test_tile_plan_covers_every_row_exactly_once(lib):
     assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 2 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
     assert _plan(lib, I8, 0, 4096, 128, 0, 256)[0] == 2 and _plan(lib, I8, 128, 4096, 130, 0, 256)[0] == 2
     assert _plan(lib, 0, 128, 4096, 128, 0, 256)[0] == 4 and _plan(lib, I8, 128, 4098, 128, 0, 256)[0] == 4
+
+
+def test_force_kernel_override_is_an_explicit_call(lib):
+    """the testing override: set and cleared through the ABI (no environment lookup per launch), visible in the plan query"""
+    lib.gpusq_force_kernel.argtypes = [ctypes.c_int]
+    I8 = 2
+    prev = lib.gpusq_force_kernel(-1)
+    try:
+        assert _plan(lib, I8, 12608, 3072, 768, 0, 256)[1][0] == 2
+        assert lib.gpusq_force_kernel(0) == -1
+        assert _plan(lib, I8, 12608, 3072, 768, 0, 256)[1][0] == 0
+        assert lib.gpusq_force_kernel(2) == 0
+        assert _plan(lib, I8, 197, 768, 768, 0, 256)[1][0] == 2
+        assert _plan(lib, I8, 197, 768, 144, 0, 256)[1][0] != 2   # ragged K cannot run on the tile kernel: the rules decide
+        assert lib.gpusq_force_kernel(7) == 2                      # anything else clears the override
+        assert lib.gpusq_force_kernel(-1) == -1
+    finally:
+        lib.gpusq_force_kernel(prev)
+
+
+def test_gelu_fit_stays_within_its_stated_bound_of_the_exact_function():
+    """The epilogue's GELU (a polynomial fit in fp32, csrc/epilogue.h) against the oracle's erf form in fp64, over every
+    finite fp16 argument and a dense fp32 grid: the difference stays below the stated 0.15 units in the last place of the
+    exact value as an fp16 number.  The GPU tests build their element-wise code check on this bound."""
+    np = pytest.importorskip("numpy")
+    import oracle
+    import gelu_fit
+    h = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float32)
+    x = np.concatenate([np.linspace(-14.0, 14.0, 2000001).astype(np.float32), h, -h])
+    exact = oracle.epilogue_fp16_f64(x.astype(np.float64).reshape(1, -1), None, True)["ref"][0]
+    err = np.abs(gelu_fit.gelu_fit_f32(x).astype(np.float64) - exact) / gelu_fit.ulp16(exact)
+    assert 0.05 < err.max() <= gelu_fit.FIT_BOUND_ULP16
+    # so a rounded fp16 output is within one unit of the exact value's rounding, and a re-quantised code moves only at a tie
+    assert np.isfinite(gelu_fit.gelu_fit_f32(np.array([-65504.0, 65504.0, 0.0, -0.0], np.float32))).all()

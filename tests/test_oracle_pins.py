@@ -368,6 +368,33 @@ def test_epilogue_special_cases_and_gelu_table():
     assert np.array_equal(o["y16"].astype(np.float64), o["ref"])
 
 
+def test_fp16_epilogue_gelu_follows_the_bias_and_matches_the_table():
+    """FP16 path with GELU: the bias is added first, then the activation [Sec. 2.2: GELU is the feed-forward activation,
+    applied to the layer's output].  acc[m][n] = x_n - b_n with a different non-zero exactly representable b_n per
+    channel, so acc + bias = x_n exactly and the result must be x_n * Phi(x_n) from the table; activation-then-bias,
+    a dropped bias, a bias indexed along m, or a tanh-form GELU all miss the table by far more than the tolerance."""
+    cdf = read_golden("normal_cdf.txt")
+    xs = sorted(float(k) for k in cdf)
+    b = np.array([0.25 * (j + 1) * (-1) ** j for j in range(len(xs))], np.float32)  # 0.25, -0.5, 0.75, ...
+    acc = np.stack([np.array(xs) - b.astype(np.float64), np.array(xs[::-1]) - b.astype(np.float64)])
+    o = oracle.epilogue_fp16_f64(acc, b, gelu=True)
+    for j, x in enumerate(xs):
+        assert o["ref"][0, j] == pytest.approx(x * cdf[x], rel=2e-9, abs=1e-12)
+        xr = xs[len(xs) - 1 - j]
+        assert o["ref"][1, j] == pytest.approx(xr * cdf[xr], rel=2e-9, abs=1e-12)
+    # the fp16 result is the fp64 value rounded once (numpy's conversion as the independent rounding)
+    assert np.array_equal(o["y16"].view(np.uint16), o["ref"].astype(np.float16).view(np.uint16))
+    # the wrong orders really are distinguishable on this input
+    wrong = np.array([(x - float(bj)) * cdf.get(x, 0.5) + float(bj) for x, bj in zip(xs, b)])
+    assert np.abs(wrong - o["ref"][0]).max() > 1e-2
+    # without GELU the same call returns acc + bias
+    o = oracle.epilogue_fp16_f64(acc, b, gelu=False)
+    assert np.array_equal(o["ref"][0], np.array(xs)) and np.array_equal(o["ref"][1], np.array(xs[::-1]))
+    # limits: GELU(0) = 0, identity for large x, vanishing for very negative x
+    o = oracle.epilogue_fp16_f64(np.array([[-1.0, 7.0, -9.0]]), np.array([1.0, 1.0, 1.0], np.float32), gelu=True)
+    assert o["ref"][0, 0] == 0 and o["ref"][0, 1] == pytest.approx(8.0, rel=1e-12) and abs(o["ref"][0, 2]) < 1e-12
+
+
 def test_epilogue_fp32_sequence_within_one_fp16_ulp_of_fp64():
     Xq, s_a, Wq, s_w, vals, meta = _int8_problem(29, 128, 64, seed=21)
     acc = oracle.spgemm_int8(Xq, vals, meta)
