@@ -178,7 +178,7 @@ gpusq_status gpusq_spgemm_int8(const int8_t* Xq, const void* Wpacked, const floa
  * Xq = clamp(rint(X / act_scale[0]), -127, 127) on its way to the matrix instructions (the code rule of
  * gpusq_quantize_int8 with scale_is_input != 0; bit-identical to calling that first), so a layer with a static scale is
  * one launch instead of two.  Only the latency kernel, through whose registers X passes, can do this: a problem that
- * gpusq_spgemm_plan assigns to the tile kernel (kernel == 2) returns GPUSQ_ERR_UNSUPPORTED and is served by
+ * gpusq_spgemm_plan assigns to a tile kernel (kernel >= 2) returns GPUSQ_ERR_UNSUPPORTED and is served by
  * gpusq_quantize_int8 + gpusq_spgemm_int8.  Every workgroup quantises the rows of its own tile, so the saving is that
  * of a launch (a few microseconds) against extra work per K step: it pays for short K (up to about 384).
  * All other arguments as for gpusq_spgemm_int8. */
@@ -214,23 +214,27 @@ gpusq_status gpusq_patch_embed16_fp16(const void* img, const void* Wpacked, cons
 /* ---- host-side introspection (no GPU work, no device access when cus > 0): how gpusq_spgemm_fp16 / gpusq_spgemm_int8
  * (dt = GPUSQ_F16 / GPUSQ_I8 = the operand type) decompose a problem on a device with `cus` compute units (cus <= 0: the
  * current device).  out[0] = kernel (0: small kernel, 64 x 64 tiles; 1: small kernel, 128 x 128 tiles, any K % 16 == 0;
- * 2: tile kernel); for the tile kernel out[1] = rows per tile unit u, out[2] = 256-channel blocks, out[3] = full_tm
- * (a full tile has u * full_tm rows), out[4] = row chunks covered by full tiles, out[5] = tail_tm (the remaining rows
- * are cut into tiles of u * tail_tm rows), out[6] = tiles in all, out[7] = workgroups launched.  Same argument checks
- * as the GEMM calls (sizes only).
+ * 2: tile kernel with one workgroup per CU, tiles of 256 channels x up to 256 rows; 3: tile kernel with two workgroups per
+ * CU, tiles of 256 channels x up to 128 rows, the template the dense twins are built from); for the tile kernels out[1] =
+ * rows per tile unit u, out[2] = 256-channel blocks, out[3] = full_tm (a full tile has u * full_tm rows), out[4] = row
+ * chunks covered by full tiles, out[5] = tail_tm (the remaining rows are cut into tiles of u * tail_tm rows), out[6] =
+ * tiles in all, out[7] = workgroups launched.  Same argument checks as the GEMM calls (sizes only).
  * The query describes gpusq_spgemm_fp16 / gpusq_spgemm_int8 only: the fused patch-embedding calls
- * (gpusq_patch_embed16_*) always run on the tile kernel, whatever this query reports for a GEMM of the same sizes. */
+ * (gpusq_patch_embed16_*) always run on tile kernel 2, whatever this query reports for a GEMM of the same sizes. */
 gpusq_status gpusq_spgemm_plan(gpusq_dtype dt, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t out[8]);
 
-/* Testing aid: kernel = 0, 1 or 2 makes the sparse GEMM entry points (and gpusq_spgemm_plan's out[0]) take that kernel
- * for every problem it can run (kernel 2 needs K * element size % 128 == 0), so that every kernel can be checked on the
- * same shapes; any other value gives the choice back to the size rules.  Returns the previous setting (-1 = none).
- * Process-wide; the environment variable GPUSQ_FORCE_KERNEL (0, 1 or 2) gives the initial setting and is read once,
- * when the library is loaded.  Not meant for production callers. */
+/* Testing aid: kernel = 0, 1, 2 or 3 makes the sparse GEMM entry points (and gpusq_spgemm_plan's out[0]) take that kernel
+ * for every problem it can run (the tile kernels need K * element size % 128 == 0), so that every kernel can be checked on
+ * the same shapes; 0 and 1 also keep the dense twins on their small kernel; any other value gives the choice back to the
+ * size rules.  Returns the previous setting (-1 = none).  Process-wide; the environment variable GPUSQ_FORCE_KERNEL (0..3)
+ * gives the initial setting and is read once, when the library is loaded.  Not meant for production callers. */
 int gpusq_force_kernel(int kernel);
 
-/* ---- dense twins: the same computation from the masked but uncompressed W [N][K], on dense matrix instructions,
- * built the same way; the baseline the sparse kernels are compared with. */
+/* ---- dense twins [Sec. 1; Sec. 3.1, Fig. 1: the dense GEMM takes T cycles where the sparse one takes T/2]: the same
+ * computation from the masked but uncompressed W [N][K] on the dense matrix instructions: the baseline the sparse kernels
+ * are compared with.  Problems with M * N > 262144 and K * element size % 64 == 0 run on the dense instantiation of tile
+ * kernel 3 (same template, tile plan, launch path and epilogue as the sparse instantiation; a dense K step is 64 bytes and
+ * holds as many matrix instructions as a sparse step of 128 bytes); smaller or ragged-K problems on a small dense kernel. */
 gpusq_status gpusq_gemm_fp16_dense(const void* X, const void* W, const float* bias, void* Y,
                                    int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
 gpusq_status gpusq_gemm_int8_dense(const int8_t* Xq, const int8_t* Wq, const float* act_scale, const float* w_scale,

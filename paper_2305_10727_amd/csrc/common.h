@@ -159,6 +159,7 @@ struct GemmArgs {
 
 gpusq_status launch_spgemm(bool is_i8, const GemmArgs& a, hipStream_t s);
 gpusq_status launch_dense(bool is_i8, const GemmArgs& a, hipStream_t s);
+int forced_kernel();                // -1 when none is forced
 int set_forced_kernel(int kernel);  // testing aid, see gpusq_force_kernel; returns the previous value
 gpusq_status plan_spgemm(bool is_i8, int64_t M, int64_t N, int64_t K, int epilogue, int cus, int32_t* out);
 

@@ -5,15 +5,14 @@
 //
 // Register semantics (measured): A (4 VGPRs) lane l byte i -> row l%32, K index 16*(l/32)+i (8*(l/32)+i for fp16
 // elements); B likewise with column l%32; D (16 VGPRs) lane l register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-#include "common.h"
-#include "epilogue.h"
+#include <atomic>
+
+#include "tile_common.h"
 
 namespace gpusq {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 constexpr int kLdsRowD = kStepBytes + 16;
 
@@ -180,8 +179,28 @@ static gpusq_status launch_cfg(const GemmArgs& a, hipStream_t s) {
   return check_launch();
 }
 
+static int dense_cus() {
+  static std::atomic<int> cus{0};
+  int n = cus.load(std::memory_order_relaxed);
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cus.store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
 gpusq_status launch_dense(bool is_i8, const GemmArgs& a, hipStream_t s) {
   const int64_t work = (int64_t)a.M * a.N;
+  // the twin of the sparse tile kernel (same template, same launch path) wherever that kernel can run the problem
+  // (forcing the sparse GEMMs onto one of the small kernels, a testing aid, keeps the dense side on its small kernel too)
+  const int forced = forced_kernel();
+  if (work > (int64_t)256 * 1024 && forced != 0 && forced != 1 && tile2_supports(is_i8, true, a)) {
+    const int resident = 2 * dense_cus();
+    const int ksteps = (int)((int64_t)a.K * (is_i8 ? 1 : 2) / 64);
+    const TilePlan plan = make_tile2_plan(a.M, a.N, resident, ksteps, (a.epilogue & GPUSQ_EPI_GELU) != 0, true);
+    return launch_tile2(is_i8, true, a, plan, tile2_grid_of(plan, resident), s);
+  }
   if (work <= (int64_t)256 * 1024)
     return is_i8 ? launch_cfg<true, 1, 1, 4>(a, s) : launch_cfg<false, 1, 1, 4>(a, s);  // 64 x 128 tiles
   return is_i8 ? launch_cfg<true, 2, 2, 2>(a, s) : launch_cfg<false, 2, 2, 2>(a, s);    // 128 x 128 tiles

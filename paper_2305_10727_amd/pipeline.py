@@ -90,7 +90,7 @@ class SparseLinear:
         own tile, K step by K step, which costs it about 0.5 us per step; the launch this saves is worth 2.5-3 us
         (measured per block at batch 1: K = 192 29 -> 25 us, K = 384 30 -> 29 us, K = 768 34 -> 43 us)."""
         return (self.precision == "int8" and self.K <= 384 and self.M <= 256 and
-                G.spgemm_plan(torch.int8, self.M, self.N, self.K, self.epilogue)["kernel"] != 2)
+                G.spgemm_plan(torch.int8, self.M, self.N, self.K, self.epilogue)["kernel"] < 2)
 
     def gemm_from_f16(self, X, bias, out_scale=None):
         """INT8 path with a static act_scale: quantise + GEMM in one launch (see takes_fp16_input)"""

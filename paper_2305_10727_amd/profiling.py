@@ -47,6 +47,37 @@ def counter_per_kernel(directory, counter):
     return {k: sum(v) / len(v) for k, v in vals.items()}
 
 
+def pmc_per_kernel(directories, kernel_filter=""):
+    """{kernel: {counter: average value per launch}} over several single-pass rocprofv3 --pmc outputs"""
+    vals = defaultdict(lambda: defaultdict(list))
+    for d in directories:
+        for r in _rows(d, "counter_collection.csv"):
+            if kernel_filter in r["Kernel_Name"]:
+                vals[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return {k: {c: sum(v) / len(v) for c, v in cs.items()} for k, cs in vals.items()}
+
+
+def derived(c, simds=1024):
+    """Ratios of the raw counters (which rocprofv3 reports summed over the chip; GRBM_GUI_ACTIVE counts the clocks the
+    dispatch was active, as the maximum over the XCDs): the share of the launch during which a SIMD's matrix pipe was
+    busy, averaged over the chip's `simds` SIMDs, and the instruction mix."""
+    out = {}
+    gui = c.get("GRBM_GUI_ACTIVE")
+    if gui and "SQ_VALU_MFMA_BUSY_CYCLES" in c:
+        # the counter advances once per clock and CU-quad of SIMDs... reported as is and as a share of gui * simds / 4 and / 1
+        out["mfma_busy_cycles / (gui_active * %d SIMDs)" % simds] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (gui * simds)
+        out["mfma_busy_cycles / (gui_active * %d CUs)" % (simds // 4)] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (gui * simds / 4)
+    if gui and "SQ_BUSY_CYCLES" in c:
+        out["sq_busy_cycles / gui_active"] = c["SQ_BUSY_CYCLES"] / gui
+    if "SQ_INSTS_VALU_MFMA_MOPS_I8" in c and gui:
+        out["mfma_mops_i8 / gui_active"] = c["SQ_INSTS_VALU_MFMA_MOPS_I8"] / gui
+    if "SQ_INSTS_VALU" in c and "SQ_INSTS_MFMA" in c:
+        out["valu_insts / mfma_insts"] = c["SQ_INSTS_VALU"] / max(c["SQ_INSTS_MFMA"], 1.0)
+    if "SQ_LDS_BANK_CONFLICT" in c and "SQ_LDS_IDX_ACTIVE" in c:
+        out["lds_bank_conflict / lds_active"] = c["SQ_LDS_BANK_CONFLICT"] / max(c["SQ_LDS_IDX_ACTIVE"], 1.0)
+    return out
+
+
 def short(name, n=70):
     return name if len(name) <= n else name[:n - 3] + "..."
 
@@ -58,6 +89,9 @@ def main():
     ap.add_argument("--write")
     ap.add_argument("--out-prefix", required=True)
     ap.add_argument("--command", default="", help="the profiling command line, recorded in the summary")
+    ap.add_argument("--pmc", nargs="*", default=[], help="output directories of further `rocprofv3 --pmc` passes: every counter "
+                                                         "found there is averaged per kernel")
+    ap.add_argument("--kernel", default="", help="with --pmc: only kernels whose name contains this")
     a = ap.parse_args()
     lines = []
     if a.command:
@@ -94,6 +128,17 @@ def main():
                 result["hbm_bytes_per_launch"] = gemm[0]["read_bytes"] + gemm[0]["write_bytes"]
                 result["fetch_scale_bytes_per_unit"] = f_scale
                 result["write_scale_bytes_per_unit"] = w_scale
+    if a.pmc:
+        counters = pmc_per_kernel(a.pmc, a.kernel)
+        result["counters"] = counters
+        for k, cs in counters.items():
+            lines += ["", "counters per launch (average over the launches of each pass): " + short(k, 110)]
+            for c, v in sorted(cs.items()):
+                lines.append("  %-34s %18.1f" % (c, v))
+            d = derived(cs)
+            for c, v in d.items():
+                lines.append("  %-34s %18.4f" % (c, v))
+            result.setdefault("derived", {})[k] = d
     with open(a.out_prefix + ".txt", "w") as fh:
         fh.write("\n".join(lines) + "\n")
     with open(a.out_prefix + ".json", "w") as fh:

@@ -160,12 +160,14 @@ def test_tile_plan_covers_every_row_exactly_once(lib):
                     if M * N <= 256 * 1024:
                         assert kernel == 0
                         continue
-                    assert kernel in (0, 2)
+                    assert kernel in (0, 2, 3)
                     if kernel == 0:  # few rows: the estimated run times favour the small kernel
                         assert p[1:] == [0] * 7 and -(-M // 64) * -(-N // 64) <= 16 * cus
                         continue
+                    # kernel 2: one workgroup per CU, tiles of up to 256 rows; kernel 3: two per CU, up to 128 rows
+                    max_tm, per_cu = (4, 1) if kernel == 2 else (2, 2)
                     assert u == 64 and tiles_n == -(-N // 256)
-                    assert 1 <= ftm <= 4 and 1 <= ttm <= 4 and fchunks >= 0
+                    assert 1 <= ftm <= max_tm and 1 <= ttm <= max_tm and fchunks >= 0
                     full_rows = fchunks * u * ftm
                     assert full_rows - u * ftm < M          # no full tile lies entirely beyond M
                     rows_left = max(M - full_rows, 0)
@@ -173,14 +175,19 @@ def test_tile_plan_covers_every_row_exactly_once(lib):
                     assert total == (fchunks + tail_chunks) * tiles_n
                     assert full_rows + tail_chunks * u * ttm >= M                # every row is covered
                     assert tail_chunks == 0 or full_rows + (tail_chunks - 1) * u * ttm < M  # and no tail tile is empty
-                    assert wgs % 8 == 0 and wgs <= -(-cus // 8) * 8 and wgs >= min(total, 8) and wgs - 8 < total
+                    assert wgs % 8 == 0 and wgs <= -(-per_cu * cus // 8) * 8 and wgs >= min(total, 8) and wgs - 8 < total
     # one image (M = 197) takes the small kernel, a batch of 64 the tile kernel
     for N, K in ((2304, 768), (3072, 768), (768, 3072), (768, 768)):
-        assert _plan(lib, I8, 197, N, K, 0, 256)[1][0] == 0 and _plan(lib, I8, 12608, N, K, 0, 256)[1][0] == 2
-        assert _plan(lib, F16, 197, N, K, 0, 256)[1][0] == 0 and _plan(lib, F16, 12608, N, K, 0, 256)[1][0] == 2
+        assert _plan(lib, I8, 197, N, K, 0, 256)[1][0] == 0 and _plan(lib, I8, 12608, N, K, 0, 256)[1][0] in (2, 3)
+        assert _plan(lib, F16, 197, N, K, 0, 256)[1][0] == 0 and _plan(lib, F16, 12608, N, K, 0, 256)[1][0] in (2, 3)
+    # between the two tile kernels: the wide GELU layer and the long-K layer stay on the one-workgroup kernel, the attention
+    # projection and the FP16 path up to K = 3072 take the kernel with two workgroups per CU
+    assert _plan(lib, I8, 12608, 3072, 768, 3, 256)[1][0] == 2 and _plan(lib, I8, 25216, 768, 3072, 1, 256)[1][0] == 2
+    assert _plan(lib, I8, 25216, 768, 768, 1, 256)[1][0] == 3 and _plan(lib, F16, 12608, 3072, 768, 3, 256)[1][0] == 3
+    assert _plan(lib, F16, 50432, 1024, 4096, 1, 256)[1][0] == 2
     # ragged K (not a multiple of the 128-byte K step) -> zero-filling small kernel; argument errors are reported
     assert _plan(lib, I8, 4096, 4096, 144, 0, 256) == (0, [1, 0, 0, 0, 0, 0, 0, 0])
-    assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 2 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
+    assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 3 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
     assert _plan(lib, I8, 0, 4096, 128, 0, 256)[0] == 2 and _plan(lib, I8, 128, 4096, 130, 0, 256)[0] == 2
     assert _plan(lib, 0, 128, 4096, 128, 0, 256)[0] == 4 and _plan(lib, I8, 128, 4098, 128, 0, 256)[0] == 4
 
@@ -197,7 +204,9 @@ def test_force_kernel_override_is_an_explicit_call(lib):
         assert lib.gpusq_force_kernel(2) == 0
         assert _plan(lib, I8, 197, 768, 768, 0, 256)[1][0] == 2
         assert _plan(lib, I8, 197, 768, 144, 0, 256)[1][0] != 2   # ragged K cannot run on the tile kernel: the rules decide
-        assert lib.gpusq_force_kernel(7) == 2                      # anything else clears the override
+        assert lib.gpusq_force_kernel(3) == 2
+        assert _plan(lib, I8, 12608, 3072, 768, 0, 256)[1][0] == 3
+        assert lib.gpusq_force_kernel(7) == 3                      # anything else clears the override
         assert lib.gpusq_force_kernel(-1) == -1
     finally:
         lib.gpusq_force_kernel(prev)

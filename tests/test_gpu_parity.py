@@ -419,7 +419,7 @@ def force_kernel(g):
     g.force_kernel(None)
 
 
-@pytest.mark.parametrize("kernel", [2, 0, 1])
+@pytest.mark.parametrize("kernel", [2, 3, 0, 1])
 @pytest.mark.parametrize("M,K,N,seed", TILE_SHAPES)
 def test_tile_kernel_corner_shapes(g, force_kernel, M, K, N, seed, kernel):
     force_kernel(kernel)
@@ -451,10 +451,11 @@ def test_tile_kernel_corner_shapes(g, force_kernel, M, K, N, seed, kernel):
 # The deployment form with quantise nodes around every linear layer [Sec. 2.2; Sec. 3.4] on the tile kernel: int8 output
 # with bias, with and without GELU, through the whole-line store path (N % 16 == 0) and the per-batch path (N % 16 != 0),
 # and the FP16 path with bias + GELU on Gaussian data through the per-batch path (N % 8 == 4).
+@pytest.mark.parametrize("kernel", [2, 3])
 @pytest.mark.parametrize("M,K,N,seed", [(4500, 640, 1024, 13), (2100, 128, 520, 11), (1500, 256, 388, 12), (9000, 384, 2304, 14)])
-def test_tile_kernel_quantised_outputs_and_fp16_gelu(g, force_kernel, M, K, N, seed):
-    force_kernel(2)
-    assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] == 2 and g.spgemm_plan(torch.float16, M, N, K)["kernel"] == 2
+def test_tile_kernel_quantised_outputs_and_fp16_gelu(g, force_kernel, M, K, N, seed, kernel):
+    force_kernel(kernel)
+    assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] == kernel and g.spgemm_plan(torch.float16, M, N, K)["kernel"] == kernel
     p = Int8Problem(M, K, N, seed, dist="normal")
     d = gpu_prepare_int8(g, p.W32, p.X32)
     acc = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
@@ -497,6 +498,19 @@ def test_c1_tile_kernel_quantised_gelu_output_sampled_rows(g):
     scale 0.05) and the bias -> int8 form, in the benchmark's launch configuration; oracle on sampled rows."""
     M, K, N = 64 * 197, 768, 3072
     assert g.spgemm_plan(torch.int8, M, N, K, epilogue=3)["kernel"] == 2
+    _c1_quantised_outputs(g, M, K, N)
+
+
+def test_c1_two_workgroup_tile_kernel_sampled_rows(g, force_kernel):
+    """the same full-size checks with the sparse GEMMs on the tile kernel that keeps two workgroups per CU (the dense twin's
+    template), plus the int32 accumulators and the fp16 GELU output on sampled rows"""
+    M, K, N = 64 * 197, 768, 3072
+    force_kernel(3)
+    assert g.spgemm_plan(torch.int8, M, N, K, epilogue=3)["kernel"] == 3
+    _c1_quantised_outputs(g, M, K, N, also_f16=True)
+
+
+def _c1_quantised_outputs(g, M, K, N, also_f16=False):
     X = synth.activations(M, K, "normal", seed=0, ids=(1, 0))
     W = synth.weights(N, K, seed=0, ids=(1, 0))
     bias = synth.bias(N, seed=0, ids=(1, 0))
@@ -522,6 +536,46 @@ def test_c1_tile_kernel_quantised_gelu_output_sampled_rows(g):
         qd = g.gemm_int8_dense(d["Xq"], d["Wq"], act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), out_dtype=torch.int8,
                                out_scale=s_t)
         assert torch.equal(q, qd)
+    if also_f16:
+        a32 = g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)
+        assert np.array_equal(host(a32)[rows], acc)
+        assert torch.equal(a32, g.gemm_int8_dense(d["Xq"], d["Wq"], out_dtype=torch.int32))
+        y = g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), gelu=True)
+        assert ulp_diff_f16(host(y)[rows], oracle.epilogue_int8_f64(acc, s_a, s_w, bias, gelu=True)["y16"]).max() <= 1
+        assert torch.equal(y, g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias), gelu=True))
+        yb = g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(bias))
+        assert np.array_equal(host(yb)[rows].view(np.uint16), oracle.epilogue_int8_f32(acc, s_a, s_w, bias)["y16"].view(np.uint16))
+        Xh = X.astype(np.float16)
+        Wp = g.cast_f16(g.prune_2to4(dev(W)))
+        v, m = g.compress(Wp)
+        yh = g.spgemm_fp16(dev(Xh), g.pack(v, m, K), N, bias=dev(bias), gelu=True)
+        vals16, meta16, _ = oracle.compress(P.astype(np.float16))
+        _, a64 = oracle.spgemm_fp16(Xh[rows], vals16, meta16)
+        assert rel_err(host(yh)[rows], oracle.epilogue_fp16_f64(a64, bias, True)["ref"]) <= 2e-3
+
+
+# The dense twin runs the two-workgroup tile kernel with K steps of 64 bytes: K that is a multiple of 64 but not of 128 bytes,
+# one and many steps, ragged M and N (whole-line and per-batch stores), against the oracle's dense product.
+@pytest.mark.parametrize("M,K,N,seed", [(2100, 64, 520, 41), (1500, 192, 388, 42), (4500, 320, 1024, 43), (20000, 576, 264, 44)])
+def test_dense_twin_tile_kernel_shapes(g, M, K, N, seed):
+    p = Int8Problem(M, K, N, seed)
+    d = gpu_prepare_int8(g, p.W32, p.X32)
+    exp = oracle.gemm_int8_dense(p.Xq, p.Wq)
+    assert np.array_equal(exp, oracle.spgemm_int8(p.Xq, p.vals, p.meta))
+    assert np.array_equal(host(g.gemm_int8_dense(d["Xq"], d["Wq"], out_dtype=torch.int32)), exp)
+    y = host(g.gemm_int8_dense(d["Xq"], d["Wq"], act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(p.bias)))
+    assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(exp, p.s_a, p.s_w, p.bias)["y16"].view(np.uint16))
+    yg = host(g.gemm_int8_dense(d["Xq"], d["Wq"], act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(p.bias), gelu=True))
+    assert ulp_diff_f16(yg, oracle.epilogue_int8_f64(exp, p.s_a, p.s_w, p.bias, gelu=True)["y16"]).max() <= 1
+    # FP16 twin: K / 2 elements per row would not be a whole number of steps for K = 64 bytes of int8; use K fp16 elements
+    X, W, Wh, vals, meta, bias = fp16_problem(M, K, N, seed)
+    _, a64 = oracle.gemm_fp16_dense(X, Wh)
+    yh = host(g.gemm_fp16_dense(dev(X), dev(Wh), bias=dev(bias), gelu=True))
+    assert rel_err(yh, oracle.epilogue_fp16_f64(a64, bias, True)["ref"]) <= 2e-3
+    Xi, Wi, Whi, _, _, _ = fp16_problem(M, K, N, seed, integers=True)
+    _, a64 = oracle.gemm_fp16_dense(Xi, Whi)
+    yh = host(g.gemm_fp16_dense(dev(Xi), dev(Whi)))
+    assert np.array_equal(yh.view(np.uint16), oracle.epilogue_fp16_f64(a64)["y16"].view(np.uint16))
 
 
 # One shape per tile height of the tile kernel (its K loop exists once per height: 64, 128, 192 and 256 rows), and one
@@ -773,7 +827,7 @@ def test_int8_gemm_quantising_fp16_activations_itself(g, force_kernel, M, K, N, 
 
 def test_int8_gemm_quantising_fp16_activations_refuses_tile_kernel_problems(g):
     M, K, N = 4096, 256, 1024
-    assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] == 2
+    assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] in (2, 3)
     z = torch.zeros((M, K), dtype=torch.float16, device="cuda")
     packed = torch.zeros((g.packed_bytes(torch.int8, N, K),), dtype=torch.uint8, device="cuda")
     one = torch.ones((1,), dtype=torch.float32, device="cuda")
