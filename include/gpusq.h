@@ -81,6 +81,17 @@ size_t gpusq_quantize_workspace_bytes(int mode, int64_t rows, int64_t cols);
 gpusq_status gpusq_quantize_int8(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode,
                                  int scale_is_input, int64_t rows, int64_t cols, void* workspace, void* stream);
 
+/* ---- the per-tensor form of gpusq_quantize_int8 for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (mode is
+ * GPUSQ_PER_TENSOR, there is no workspace), same kernels, bit-identical Xq and scale; the partial maxima of the range
+ * pass live in a 4 KB device array inside the library (one per GPU, held until the process ends), which serves every
+ * size gpusq_quantize_int8 accepts: rows * cols up to 2^40, GPUSQ_ERR_SHAPE beyond.  The call allocates and frees
+ * nothing.  Its first use on a device looks up the array's address there (hipGetSymbolAddress), so make that first call
+ * outside a graph capture.  All calls on one GPU share the array: calls that overlap in time on the same GPU (different
+ * streams, or graph branches that run side by side) race on it and must be ordered by the caller. */
+gpusq_status gpusq_quantize_tensor_int8_noalloc(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale,
+                                                int scale_is_input, int64_t rows, int64_t cols, void* stream);
+
 /* ---- compression [Sec. 3.1, Fig. 1 and Fig. 2 captions]: the N x K operand becomes N x K/2 kept values plus
  * 2 bits of metadata per kept value giving its position in its group of 4.
  *   W      : [N][K] of dt (GPUSQ_F16 or GPUSQ_I8)

@@ -96,6 +96,16 @@ gpusq_status gpusq_quantize_int8(const void* X, gpusq_dtype dt, int8_t* Xq, floa
   return launch_quantize(X, dt, Xq, scale, mode, scale_is_input, rows, cols, workspace, (hipStream_t)stream);
 }
 
+gpusq_status gpusq_quantize_tensor_int8_noalloc(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input,
+                                                int64_t rows, int64_t cols, void* stream) {
+  if (!X || !Xq || !scale) return GPUSQ_ERR_NULL;
+  // the same size limits as gpusq_quantize_int8: the library's own scratch (4 KB of partial maxima) serves any of them
+  if (rows <= 0 || cols <= 0 || rows > INT32_MAX || cols > INT32_MAX || rows * cols > kMaxElems) return GPUSQ_ERR_SHAPE;
+  if (dt != GPUSQ_F32 && dt != GPUSQ_F16) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(X) || !aligned16(Xq)) return GPUSQ_ERR_ALIGN;
+  return launch_quantize_tensor_static(X, dt, Xq, scale, scale_is_input, rows, cols, (hipStream_t)stream);
+}
+
 gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt, int64_t N,
                             int64_t K, void* stream) {
   if (!W || !values || !meta) return GPUSQ_ERR_NULL;

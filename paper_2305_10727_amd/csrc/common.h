@@ -170,6 +170,8 @@ gpusq_status launch_im2col_patches(const void* img, void* X, gpusq_dtype dt, int
                                    int64_t K_pad, hipStream_t s);
 gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int mode, int scale_is_input,
                              int64_t rows, int64_t cols, void* workspace, hipStream_t s);
+gpusq_status launch_quantize_tensor_static(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input,
+                                           int64_t rows, int64_t cols, hipStream_t s);
 gpusq_status launch_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input, int64_t rows,
                                        int64_t cols, hipStream_t s);
 gpusq_status launch_prune_pairs(const float* Win, float* Wout, uint8_t* mask, int one_per_group, int64_t N, int64_t K, hipStream_t s);

@@ -2,6 +2,8 @@
 // 2-bit metadata, decompression, and re-tiling into the kernel-native packed format.
 // All of them stream their operands once and are bound by HBM bandwidth; work is laid out wavefront-parallel over
 // groups of 4 (one lane per group or per pair of groups), with 16-byte accesses where the layout allows.
+#include <atomic>
+
 #include "common.h"
 
 namespace gpusq {
@@ -358,6 +360,52 @@ gpusq_status launch_quantize(const void* X, gpusq_dtype dt, int8_t* Xq, float* s
                              int64_t rows, int64_t cols, void* workspace, hipStream_t s) {
   if (dt == GPUSQ_F32) return quantize_typed<float>((const float*)X, Xq, scale, mode, scale_is_input, rows, cols, workspace, s);
   return quantize_typed<_Float16>((const _Float16*)X, Xq, scale, mode, scale_is_input, rows, cols, workspace, s);
+}
+
+// ---- per-tensor quantiser for callers that cannot allocate -------------------------------------------------------
+// The per-workgroup partial maxima of the range pass live in this file-scope device array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy until the process ends; its address on a device is
+// looked up once per device (hipGetSymbolAddress with that device current) and kept.  The array's name is only a
+// host-side handle: host code passes the looked-up pointer to the kernels, never the name.
+static __device__ __align__(256) float g_amax_scratch[kAmaxMaxBlocks];
+
+static float* amax_scratch_of_current_device(gpusq_status* st) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<float*> ptrs[kMaxDevices];
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    if (e != hipSuccess) set_last_hip_error(e);
+    *st = e != hipSuccess ? GPUSQ_ERR_HIP : GPUSQ_ERR_UNSUPPORTED;
+    return nullptr;
+  }
+  float* p = ptrs[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(g_amax_scratch));
+    if (e != hipSuccess || !sym) {
+      set_last_hip_error(e);
+      *st = GPUSQ_ERR_HIP;
+      return nullptr;
+    }
+    p = (float*)sym;
+    ptrs[dev].store(p, std::memory_order_release);  // (a racing first call looks up the same address)
+  }
+  *st = GPUSQ_OK;
+  return p;
+}
+
+gpusq_status launch_quantize_tensor_static(const void* X, gpusq_dtype dt, int8_t* Xq, float* scale, int scale_is_input,
+                                           int64_t rows, int64_t cols, hipStream_t s) {
+  float* scratch = nullptr;
+  if (!scale_is_input) {  // a given scale needs no range pass and no scratch
+    gpusq_status st;
+    scratch = amax_scratch_of_current_device(&st);
+    if (!scratch) return st;
+  }
+  // Nothing has to be cleared: the range pass overwrites the partial maxima the quantising pass reads (the same
+  // number of them in both launches), whatever an earlier call left behind.
+  return launch_quantize(X, dt, Xq, scale, GPUSQ_PER_TENSOR, scale_is_input, rows, cols, scratch, s);
 }
 
 // The same per-row quantiser with the 4-bit range: codes -7..7 in int8 containers, scale = max|row| / 7.

@@ -26,6 +26,7 @@ EXPORTS = [
     "gpusq_spgemm_int8", "gpusq_spgemm_int8_xf16", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
     "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
     "gpusq_int4_to_sparse_int8", "gpusq_prune_n_of_m", "gpusq_force_kernel",
+    "gpusq_quantize_tensor_int8_noalloc",
 ]
 
 
@@ -58,6 +59,8 @@ def lib():
         L.gpusq_quantize_workspace_bytes.restype = ctypes.c_size_t
         L.gpusq_quantize_workspace_bytes.argtypes = [ci, i64, i64]
         L.gpusq_quantize_int8.argtypes = [vp, ci, vp, vp, ci, ci, i64, i64, vp, vp]
+        L.gpusq_quantize_tensor_int8_noalloc.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
+        L.gpusq_quantize_tensor_int8_noalloc.restype = ci
         L.gpusq_compress.argtypes = [vp, vp, vp, vp, ci, i64, i64, vp]
         L.gpusq_decompress.argtypes = [vp, vp, vp, ci, i64, i64, vp]
         L.gpusq_packed_bytes.restype = ctypes.c_size_t
@@ -153,6 +156,15 @@ def quantize_int8(X, mode, scale=None):
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=X.device)
     _check(lib().gpusq_quantize_int8(_ptr(X), _TORCH_DT[X.dtype], _ptr(Xq), _ptr(scale), mode, int(given), rows, cols,
                                      _ptr(ws), _stream()), "gpusq_quantize_int8")
+    return Xq, scale
+
+
+def quantize_tensor_int8_noalloc(X, Xq, scale, scale_is_input=False):
+    """gpusq_quantize_tensor_int8_noalloc: per-tensor codes into the caller's Xq [rows, cols] int8 and scale [1] fp32;
+    nothing is allocated, here or in the library."""
+    rows, cols = X.shape
+    _check(lib().gpusq_quantize_tensor_int8_noalloc(_ptr(X), _TORCH_DT[X.dtype], _ptr(Xq), _ptr(scale), int(bool(scale_is_input)),
+                                                    rows, cols, _stream()), "gpusq_quantize_tensor_int8_noalloc")
     return Xq, scale
 
 
