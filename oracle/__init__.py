@@ -17,9 +17,15 @@ CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", 
 
 
 def build(force=False):
-    """Compile the oracle with gcc (plain C, no GPU headers)."""
+    """Compile the oracle with gcc (plain C, no GPU headers); a forced build also compiles its self-test driver
+    (oracle/selftest.c, the program the sanitizer test runs) to check that it builds."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", *CFLAGS, "-o", _LIB, _SRC, "-lm"])
+    if force:
+        import tempfile
+        with tempfile.TemporaryDirectory(prefix="oracle_build_") as tmp:
+            flags = [f for f in CFLAGS if f not in ("-shared", "-fPIC")]
+            subprocess.check_call(["gcc", *flags, "-o", os.path.join(tmp, "selftest"), os.path.join(_HERE, "selftest.c"), _SRC, "-lm"])
     return _LIB
 
 

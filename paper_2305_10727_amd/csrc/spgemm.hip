@@ -138,13 +138,16 @@ __device__ __forceinline__ void issue_step_copy(uint32_t lds_wave, uint32_t lds_
 // fetches row 8j + l/8 of block j, chunk (l%8) ^ ((row >> 1) & 7).  The X slab is stored row-major with the 16-byte
 // chunk c of row r at chunk position c ^ ((r >> 1) & 7), so that the 16 rows a quarter-wavefront reads at the same K
 // offset fall in 16 different 16-byte bank groups; the swizzle is applied by choosing which global chunk each lane
-// fetches.  Rows past the end of X re-read the last row (their results are never stored).
-__device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], int64_t m0, int M, int64_t k_bytes, int wave, int lane) {
+// fetches.  Rows past the end of X, and rows past the end of a tile shorter than 256 rows (`rows` = its height), re-read
+// the last row they may: their results are never stored, and a short tile then draws no rows from memory that it does
+// not use (the number of copies stays the same, the waits count them).
+__device__ __forceinline__ void tile_x_offsets(uint32_t (&xoff)[4], int64_t m0, int M, int rows, int64_t k_bytes, int wave, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = 8 * (wave + i * 8) + (lane >> 3);
     const int c = (lane & 7) ^ ((r >> 1) & 7);
-    const int64_t last = (int64_t)M - 1 - m0;  // >= 0: a tile starts inside X
+    int64_t last = (int64_t)M - 1 - m0;  // >= 0: a tile starts inside X
+    last = last < rows - 1 ? last : rows - 1;
     const int64_t rr = r < last ? r : last;
     xoff[i] = (uint32_t)(rr * k_bytes + c * 16);
   }
@@ -369,7 +372,7 @@ __global__ void __launch_bounds__(512, 1) spgemm_tile_kernel(const GemmArgs a, c
       patch_x_offsets<IS_I8>(pf_xoff, t.m0, a, wave, lane_now);
       pf_x = Xg;
     } else {
-      tile_x_offsets(pf_xoff, t.m0, a.M, k_bytes, wave, lane_now);
+      tile_x_offsets(pf_xoff, t.m0, a.M, kTileUnitRows * t.tm, k_bytes, wave, lane_now);
       pf_x = Xg + t.m0 * k_bytes;
     }
     pf_w = Wg + t.n_blk * w_col_bytes + wave_lds;

@@ -132,13 +132,14 @@ __global__ void __launch_bounds__(512, 4) gemm_tile2_kernel(const GemmArgs a, co
     const Tile t = tile_of(item);
     int l = lane;
     asm volatile("" : "+v"(l));  // (computed here, per tile)
-    const int64_t last = (int64_t)a.M - 1 - t.m0;  // >= 0: a tile starts inside X
+    int64_t last = (int64_t)a.M - 1 - t.m0;  // >= 0: a tile starts inside X
+    last = last < kTileUnitRows * t.tm - 1 ? last : kTileUnitRows * t.tm - 1;  // a short tile draws no rows it does not use
 #pragma unroll
     for (int i = 0; i < G::XBLOCKS; ++i) {
       // block j = wave + 8 i of the slab: rows 8j..8j+7 (128-byte rows) / 16j..16j+15 (64-byte rows); the 16-byte chunk c of
       // row r is stored at chunk position c ^ swizzle(r), applied by choosing which global chunk a lane fetches, so that
       // the 16 rows a quarter-wavefront reads at one K offset fall into 16 different bank groups.  Rows past the end of X
-      // re-read the last row (their results are never stored).
+      // or of a short tile re-read the last row they may (their results are never stored).
       const int j = wave + 8 * i;
       int r, c;
       if constexpr (DENSE) {

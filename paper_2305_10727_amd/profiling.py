@@ -57,24 +57,31 @@ def pmc_per_kernel(directories, kernel_filter=""):
     return {k: {c: sum(v) / len(v) for c, v in cs.items()} for k, cs in vals.items()}
 
 
-def derived(c, simds=1024):
-    """Ratios of the raw counters (which rocprofv3 reports summed over the chip; GRBM_GUI_ACTIVE counts the clocks the
-    dispatch was active, as the maximum over the XCDs): the share of the launch during which a SIMD's matrix pipe was
-    busy, averaged over the chip's `simds` SIMDs, and the instruction mix."""
+def derived(c, simds=1024, xcds=8):
+    """Ratios of the raw counters.  rocprofv3 reports a counter summed over the chip; GRBM_GUI_ACTIVE (clocks during which
+    the dispatch was active) is summed over the `xcds` dies, so gui / xcds is the launch's length in shader clocks.  The
+    matrix pipe of a SIMD is busy 16 clocks per 16x16 matrix instruction (SQ_VALU_MFMA_BUSY_CYCLES = 16 x SQ_INSTS_MFMA),
+    so mfma_util is the share of the launch during which a SIMD's matrix pipe was busy, averaged over all `simds` SIMDs;
+    a vector instruction occupies its SIMD's vector ALU for 4 clocks (64 lanes on 16)."""
     out = {}
     gui = c.get("GRBM_GUI_ACTIVE")
-    if gui and "SQ_VALU_MFMA_BUSY_CYCLES" in c:
-        # the counter advances once per clock and CU-quad of SIMDs... reported as is and as a share of gui * simds / 4 and / 1
-        out["mfma_busy_cycles / (gui_active * %d SIMDs)" % simds] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (gui * simds)
-        out["mfma_busy_cycles / (gui_active * %d CUs)" % (simds // 4)] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (gui * simds / 4)
-    if gui and "SQ_BUSY_CYCLES" in c:
-        out["sq_busy_cycles / gui_active"] = c["SQ_BUSY_CYCLES"] / gui
-    if "SQ_INSTS_VALU_MFMA_MOPS_I8" in c and gui:
-        out["mfma_mops_i8 / gui_active"] = c["SQ_INSTS_VALU_MFMA_MOPS_I8"] / gui
+    clocks = gui / xcds if gui else None
+    if clocks:
+        out["launch_clocks (gui_active / %d XCDs)" % xcds] = clocks
+    if clocks and "SQ_VALU_MFMA_BUSY_CYCLES" in c:
+        out["mfma_util = mfma_busy_cycles / (launch_clocks * %d SIMDs)" % simds] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (clocks * simds)
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in c and "SQ_INSTS_MFMA" in c:
+        out["mfma_busy_cycles / mfma_insts"] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / max(c["SQ_INSTS_MFMA"], 1.0)
+    if clocks and "SQ_INSTS_VALU" in c:
+        out["valu_util = 4 * valu_insts / (launch_clocks * %d SIMDs)" % simds] = 4.0 * c["SQ_INSTS_VALU"] / (clocks * simds)
+    if clocks and "SQ_LDS_IDX_ACTIVE" in c:
+        out["lds_util = lds_idx_active / (launch_clocks * %d CUs)" % (simds // 4)] = c["SQ_LDS_IDX_ACTIVE"] / (clocks * simds / 4)
     if "SQ_INSTS_VALU" in c and "SQ_INSTS_MFMA" in c:
         out["valu_insts / mfma_insts"] = c["SQ_INSTS_VALU"] / max(c["SQ_INSTS_MFMA"], 1.0)
     if "SQ_LDS_BANK_CONFLICT" in c and "SQ_LDS_IDX_ACTIVE" in c:
-        out["lds_bank_conflict / lds_active"] = c["SQ_LDS_BANK_CONFLICT"] / max(c["SQ_LDS_IDX_ACTIVE"], 1.0)
+        out["lds_bank_conflict / lds_idx_active"] = c["SQ_LDS_BANK_CONFLICT"] / max(c["SQ_LDS_IDX_ACTIVE"], 1.0)
+    if clocks and "SQ_WAVE_CYCLES" in c and "SQ_WAIT_INST_ANY" in c:
+        out["wait_inst_any / wave_cycles"] = c["SQ_WAIT_INST_ANY"] / max(c["SQ_WAVE_CYCLES"], 1.0)
     return out
 
 

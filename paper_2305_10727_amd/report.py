@@ -14,7 +14,31 @@ from . import synth
 from .pipeline import EncoderBlockLinears, SparseLinear, SparsePatchEmbed
 
 SPARSE_PEAK = {"int8": 10070.0, "fp16": 5030.0}  # nominal dense-equivalent T(FL)OP/s of the gfx950 sparse matrix instructions
+DENSE_PEAK = {"int8": 5035.0, "fp16": 2515.0}
+HBM_PEAK = 8000.0  # GB/s
 INFINITY_CACHE = 256 << 20
+
+
+def measured_peaks():
+    """sparse matrix rates measured by `python -m paper_2305_10727_amd.probes` (committed run), or None"""
+    import json
+    import os
+    f = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles", "hardware_probes.json")
+    if not os.path.exists(f):
+        return {}
+    d = {k: v["value"] for k, v in json.load(open(f)).items()}
+    return {"int8": d.get("sparse_int8_16x16x128_rate"), "fp16": d.get("sparse_fp16_16x16x64_rate")}
+
+
+def ideal_speedup(M, K, N, prec):
+    """sparse / dense ratio with each side on its own roofline at the nominal peaks: max(matrix time, HBM time of the
+    algorithmic bytes); the dense side reads N*K*e weight bytes and no metadata"""
+    e = 1 if prec == "int8" else 2
+    ops = 2.0 * M * N * K
+    io = M * K * e + 8 * N + M * N * 2
+    t_s = max(ops / (SPARSE_PEAK[prec] * 1e12), (io + N * K * e // 2 + N * K // 8) / (HBM_PEAK * 1e9))
+    t_d = max(ops / (DENSE_PEAK[prec] * 1e12), (io + N * K * e) / (HBM_PEAK * 1e9))
+    return t_d / t_s
 
 
 def _time(fns, iters):
@@ -61,11 +85,61 @@ def layer_rows(M, K, N, gelu, iters):
         td_hot = _time([lambda s=sets[0]: s[0].gemm_dense(s[1], bias)], iters)
         td_cold = _time([lambda s=s: s[0].gemm_dense(s[1], bias) for s in sets], iters)
         alg = M * K * e + N * K * e // 2 + N * K // 8 + 8 * N + M * N * 2
+        kernel = G.spgemm_plan(torch.int8 if prec == "int8" else torch.float16, M, N, K, sets[0][0].epilogue)["kernel"]
+        # the sparse instantiation of the dense twin's template (tile kernel 3), where the size rules picked another kernel
+        t_same = t_cold
+        if kernel != 3 and K * e % 128 == 0 and M * N > 256 * 1024:
+            G.force_kernel(3)
+            t_same = _time([lambda s=s: s[0].gemm(s[1], bias) for s in sets], iters)
+            G.force_kernel(None)
+        mp = measured_peaks().get(prec)
         rows.append(dict(prec=prec, t_hot=t_hot, t_cold=t_cold, td_hot=td_hot, td_cold=td_cold, tops=ops / t_cold / 1e6,
-                         frac=ops / t_cold / 1e6 / SPARSE_PEAK[prec], hbm=alg / t_cold / 1e6 / 8.0, sets=n_sets))
+                         frac=ops / t_cold / 1e6 / SPARSE_PEAK[prec], hbm=alg / t_cold / 1e6 / 8.0, sets=n_sets, kernel=kernel,
+                         t_same=t_same, ideal=ideal_speedup(M, K, N, prec), frac_measured=(ops / t_cold / 1e6 / mp) if mp else float("nan")))
         del sets
         torch.cuda.empty_cache()
     return rows
+
+
+def full_depth_row(cfg, prec, iters):
+    """every linear layer of the model, depth times, each layer with weights of its own"""
+    dev = torch.device("cuda")
+    M, depth = cfg["M"], cfg["depth"]
+    kinds = []  # per GEMM kind: one SparseLinear per layer (sharing activations, codes and output), its input, its bias
+    weights_bytes = 0
+    ops = 0.0
+    for name, K, N, gelu, _dist in cfg["layers"]:
+        X = torch.randn(M, K, device=dev).half()
+        bias = torch.randn(N, device=dev) * 0.01
+        lins = []
+        for layer in range(depth):
+            lin = SparseLinear(M, K, N, prec, gelu=gelu, bias=True)
+            if lins:  # the activation-side buffers are shared between the layers of a kind
+                for nm in ("Y", "Xq", "act_scale", "workspace", "W_pruned", "values", "meta"):
+                    if hasattr(lins[0], nm):
+                        setattr(lin, nm, getattr(lins[0], nm))
+            lin.prepare_weights(torch.randn(N, K, device=dev) * 0.02, fused=K * 4 <= 64 * 1024)
+            weights_bytes += lin.packed.numel()
+            lins.append(lin)
+        if prec == "int8":
+            lins[0].quantize_activations(X)
+        kinds.append((lins, X, bias))
+        ops += 2.0 * M * N * K * depth
+
+    def sparse_pass():
+        for layer in range(depth):
+            for lins, X, bias in kinds:
+                lins[layer].gemm(X, bias)
+
+    def dense_pass():
+        for layer in range(depth):
+            for lins, X, bias in kinds:
+                lins[layer].gemm_dense(X, bias)
+    t_s = _time([sparse_pass], iters)
+    t_d = _time([dense_pass], iters)
+    del kinds
+    torch.cuda.empty_cache()
+    return dict(t_sparse=t_s, t_dense=t_d, ops=ops, launches=4 * depth, weights_mb=weights_bytes / 1e6)
 
 
 def main():
@@ -76,28 +150,46 @@ def main():
     ap.add_argument("--only-blocks", action="store_true", help="skip the per-layer and patch-embedding tables")
     ap.add_argument("--only-int4", action="store_true", help="only the INT4 format table")
     a = ap.parse_args()
-    lines = ["| config | layer | M | K | N | GELU | path | sparse cold us | sparse hot us | dense cold us | dense hot us | speedup (cold) | "
-             "TOPS dense-equiv. (cold) | of sparse peak | of 8 TB/s (algorithmic bytes) |",
-             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    lines = ["Sparse GEMM against its dense twin per linear layer.  The dense twin is the dense instantiation of tile kernel 3 (two workgroups "
+             "per CU); `same template` is the sparse instantiation of that kernel, `sparse` the kernel the size rules pick (column `kernel`).  "
+             "`ideal` = both sides on their own roofline at the nominal peaks (sparse 10.07 / 5.03, dense 5.03 / 2.52 P(FL)OP/s, 8 TB/s).", "",
+             "| config | layer | M | K | N | GELU | path | kernel | sparse cold us | sparse hot us | same template cold us | dense cold us | dense hot us | "
+             "speedup (cold) | same-template speedup | ideal | TOPS dense-equiv. (cold) | of nominal sparse peak | of measured sparse peak | "
+             "of 8 TB/s (algorithmic bytes) |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     totals = {}
     for cfg_name in ([] if a.only_blocks or a.only_int4 else a.configs.split(",")):
         cfg = synth.CONFIGS[cfg_name]
         M = cfg["M"]
         for name, K, N, gelu, _dist in cfg["layers"]:
             for r in layer_rows(M, K, N, gelu, a.iters):
-                lines.append("| %s | %s | %d | %d | %d | %s | %s | %.1f | %.1f | %.1f | %.1f | %.2f | %.0f | %.3f | %.3f |" % (
-                    cfg_name, name, M, K, N, "yes" if gelu else "no", r["prec"], r["t_cold"], r["t_hot"], r["td_cold"], r["td_hot"],
-                    r["td_cold"] / r["t_cold"], r["tops"], r["frac"], r["hbm"]))
+                lines.append("| %s | %s | %d | %d | %d | %s | %s | %d | %.1f | %.1f | %.1f | %.1f | %.1f | %.2f | %.2f | %.2f | %.0f | %.3f | %.3f | %.3f |" % (
+                    cfg_name, name, M, K, N, "yes" if gelu else "no", r["prec"], r["kernel"], r["t_cold"], r["t_hot"], r["t_same"], r["td_cold"],
+                    r["td_hot"], r["td_cold"] / r["t_cold"], r["td_cold"] / r["t_same"], r["ideal"], r["tops"], r["frac"], r["frac_measured"],
+                    r["hbm"]))
                 key = (cfg_name, r["prec"])
                 t = totals.setdefault(key, [0.0, 0.0, 0.0])
                 t[0] += r["t_cold"] * cfg["depth"]
                 t[1] += r["td_cold"] * cfg["depth"]
                 t[2] += 2.0 * M * N * K * cfg["depth"]
                 print(lines[-1], flush=True)
-    lines += ["", "Whole configuration (sum over its layers x depth, cold buffers; the same weights are reused across the depth):", "",
+    lines += ["", "Whole configuration, sum of the per-layer times above x depth (cold activation buffers, one weight set):", "",
               "| config | path | sparse ms | dense ms | speedup | TOPS dense-equiv. |", "|---|---|---|---|---|---|"]
     for (cfg_name, prec), (ts, td, ops) in totals.items():
         lines.append("| %s | %s | %.3f | %.3f | %.2f | %.0f |" % (cfg_name, prec, ts / 1e3, td / 1e3, td / ts, ops / ts / 1e6))
+    lines += ["", "Full-depth pass over all linear layers, timed as one sequence of 4 x depth launches with DISTINCT weights per layer (the "
+              "weights of a layer are not cached from the layer before) and one activation / output buffer per kind of GEMM:", "",
+              "| config | path | depth | launches | packed weights MB | sparse ms | dense ms | speedup | TOPS dense-equiv. |", "|---|---|---|---|---|---|---|---|---|"]
+    for cfg_name in ([] if a.only_blocks or a.only_int4 else a.configs.split(",")):
+        cfg = synth.CONFIGS[cfg_name]
+        if cfg["depth"] <= 1:
+            continue
+        for prec in ("int8", "fp16"):
+            r = full_depth_row(cfg, prec, max(3, a.iters // 10))
+            lines.append("| %s | %s | %d | %d | %.0f | %.3f | %.3f | %.2f | %.0f |" % (cfg_name, prec, cfg["depth"], r["launches"], r["weights_mb"],
+                                                                                r["t_sparse"] / 1e3, r["t_dense"] / 1e3, r["t_dense"] / r["t_sparse"],
+                                                                                r["ops"] / r["t_sparse"] / 1e6))
+            print(lines[-1], flush=True)
     lines += ["", "Patch embedding (a convolution with kernel = stride = P, run as quantise + im2col + sparse GEMM; images N(0,1) fp16, "
               "hot buffers):", "", "| model | images | P | M | K | N | path | quantise us | im2col us | sparse GEMM us | whole layer us | whole layer, patches "
               "gathered by the GEMM (P = 16) us |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
