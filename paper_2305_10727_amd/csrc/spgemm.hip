@@ -813,7 +813,6 @@ static TilePlan make_plan(int M, int N, int resident, int ksteps, bool gelu) {
     const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * 64 * ftm;
     p.total = p.full_tiles + (rows_left > 0 ? (int)ceil_div(rows_left, 64 * ttm) * tiles_n : 0);
     p.inv_tiles_n = (tiles_n > 1 && tiles_n <= 4096 && p.total < (1 << 20)) ? (uint32_t)((((uint64_t)1 << 32) + tiles_n - 1) / tiles_n) : 0u;
-    p.stagger = 0;
     const double c = plan_makespan(p, grid_for(p, resident), ksteps, gelu, 1.0);  // (plans are compared at the full-chip step cost)
     if (best_cost < 0 || c < best_cost) {
       best_cost = c;
@@ -852,10 +851,12 @@ static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu,
   if (k_bytes % kStepBytes != 0) return wgs64 <= 2 * resident ? 0 : 1;
   if (fused_patches) return 2;
   // Between the two tile kernels the measured times decide (every linear layer of the ViT-B, Swin-B, ViT-L and ViT-H
-  // workloads, both kernels within 10 % of each other): the kernel with two workgroups per CU is ahead on the FP16 path up
-  // to K = 3072 (1-19 %) and on the INT8 path for layers with few output channels and short K (the attention projections:
-  // 3-19 %); the single-workgroup kernel keeps the wide GELU layers and the long-K layers.
-  const int tile_kernel = is_i8 ? ((N <= 1536 && K <= 1024 && !gelu) ? 3 : 2) : (K <= 3072 ? 3 : 2);
+  // workloads, FP16 and INT8, with hot and with cold buffers; the two are within 10 % of each other almost everywhere): the
+  // kernel with two workgroups per CU is ahead, by up to 20 %, on layers with few output channels, short K and no GELU
+  // (the attention projections and the QKV layer of the narrow models: few tiles per CU, where its smaller tiles
+  // balance better); the single-workgroup kernel keeps the wide layers, the GELU layers and every long-K layer, where
+  // its deeper ring hides the latency of cold activations (the other kernel is 15-25 % behind there on cold buffers).
+  const int tile_kernel = (N <= 1536 && K <= 1024 && !gelu) ? 3 : 2;
   if (wgs64 > 16 * resident) return tile_kernel;  // far beyond the crossover with the small kernel: skip the planning
   const double per_round = 0.7 + 0.45 * ksteps, chain = 3.6 + 0.25 * ksteps;
   const double throughput = 4.0 + per_round * (double)wgs64 / (2.0 * resident);

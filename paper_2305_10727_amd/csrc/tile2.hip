@@ -191,12 +191,6 @@ __global__ void __launch_bounds__(512, 4) gemm_tile2_kernel(const GemmArgs a, co
     }
   };
 
-  // The dispatcher gives a CU its second workgroup once every CU has one; that workgroup (slot 1 of the CU, bits 16..19 of
-  // the hardware id register) waits before its first request.
-  if (plan.stagger != 0 && ((__builtin_amdgcn_s_getreg((3 << 11) | (16 << 6) | 4) & 1u) != 0)) {
-    for (uint32_t i = 0; i < plan.stagger; ++i) __builtin_amdgcn_s_sleep(16);
-  }
-
   acc_t acc[kTileTN][kT2TM];
   const uint32_t a_off = (uint32_t)(G::XSLAB + wn * kTileTN * kFragValueBytes + lane * 16);
   const uint32_t i_off = DENSE ? 0u : (uint32_t)(G::XSLAB + index_offset(IS_I8, wn * kTileTN, lane));
@@ -353,8 +347,6 @@ TilePlan make_tile2_plan(int M, int N, int resident, int ksteps, bool gelu, bool
     const int64_t rows_left = (int64_t)M - (int64_t)full_chunks * kTileUnitRows * ftm;
     p.total = p.full_tiles + (rows_left > 0 ? (int)ceil_div(rows_left, kTileUnitRows * ttm) * tiles_n : 0);
     p.inv_tiles_n = (tiles_n > 1 && tiles_n <= 4096 && p.total < (1 << 20)) ? (uint32_t)((((uint64_t)1 << 32) + tiles_n - 1) / tiles_n) : 0u;
-    const char* sg = getenv("GPUSQ_STAGGER");
-    p.stagger = sg ? (uint32_t)atoi(sg) : 0u;
     const double c = tile2_makespan(p, tile2_grid(p, resident), ksteps, gelu, dense);
     if (best_cost < 0 || c < best_cost) {
       best_cost = c;

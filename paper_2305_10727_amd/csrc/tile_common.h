@@ -41,9 +41,6 @@ struct TilePlan {
   int total;        // full + tail tiles
   // ceil(2^32 / tiles_n), or 0 when the shortcut below does not apply (tiles_n = 1 or > 4096, or 2^20 tiles or more)
   uint32_t inv_tiles_n;
-  // tile2 kernel only: shader clocks (in units of 1024) by which the second workgroup of a CU starts late, so that one
-  // workgroup's K loop runs beside the other's epilogue instead of both fighting for the same unit at the same time
-  uint32_t stagger;
 };
 
 // idx / tiles_n without a division (a tile is decoded three times per tile, between K steps, by every wavefront, and an

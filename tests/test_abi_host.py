@@ -180,14 +180,14 @@ def test_tile_plan_covers_every_row_exactly_once(lib):
     for N, K in ((2304, 768), (3072, 768), (768, 3072), (768, 768)):
         assert _plan(lib, I8, 197, N, K, 0, 256)[1][0] == 0 and _plan(lib, I8, 12608, N, K, 0, 256)[1][0] in (2, 3)
         assert _plan(lib, F16, 197, N, K, 0, 256)[1][0] == 0 and _plan(lib, F16, 12608, N, K, 0, 256)[1][0] in (2, 3)
-    # between the two tile kernels: the wide GELU layer and the long-K layer stay on the one-workgroup kernel, the attention
-    # projection and the FP16 path up to K = 3072 take the kernel with two workgroups per CU
+    # between the two tile kernels: wide, GELU and long-K layers stay on the one-workgroup kernel, layers with few output
+    # channels, short K and no GELU take the kernel with two workgroups per CU
     assert _plan(lib, I8, 12608, 3072, 768, 3, 256)[1][0] == 2 and _plan(lib, I8, 25216, 768, 3072, 1, 256)[1][0] == 2
-    assert _plan(lib, I8, 25216, 768, 768, 1, 256)[1][0] == 3 and _plan(lib, F16, 12608, 3072, 768, 3, 256)[1][0] == 3
-    assert _plan(lib, F16, 50432, 1024, 4096, 1, 256)[1][0] == 2
+    assert _plan(lib, F16, 12608, 3072, 768, 3, 256)[1][0] == 2 and _plan(lib, F16, 50432, 1024, 4096, 1, 256)[1][0] == 2
+    assert _plan(lib, I8, 25216, 768, 768, 1, 256)[1][0] == 3 and _plan(lib, F16, 12544, 1536, 512, 1, 256)[1][0] == 3
     # ragged K (not a multiple of the 128-byte K step) -> zero-filling small kernel; argument errors are reported
     assert _plan(lib, I8, 4096, 4096, 144, 0, 256) == (0, [1, 0, 0, 0, 0, 0, 0, 0])
-    assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 3 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
+    assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 2 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
     assert _plan(lib, I8, 0, 4096, 128, 0, 256)[0] == 2 and _plan(lib, I8, 128, 4096, 130, 0, 256)[0] == 2
     assert _plan(lib, 0, 128, 4096, 128, 0, 256)[0] == 4 and _plan(lib, I8, 128, 4098, 128, 0, 256)[0] == 4
 
