@@ -155,8 +155,8 @@ def main():
     lin16.prepare_weights(W)
     t_gemm16 = time_kernel(lambda: lin16.gemm(Xh, bias), it, torch)
     t_dense16 = time_kernel(lambda: lin16.gemm_dense(Xh, bias), it, torch)
-    gpusq.force_kernel(2)
-    t_gemm16_k2 = time_kernel(lambda: lin16.gemm(Xh, bias), it, torch)
+    gpusq.force_kernel(3)
+    t_gemm16_twin = time_kernel(lambda: lin16.gemm(Xh, bias), it, torch)
     gpusq.force_kernel(None)
     lin8o = SparseLinear(M, K, N, "int8", gelu=gelu, bias=True, out_dtype=torch.int8)
     lin8o.prepare_weights(W)
@@ -221,9 +221,10 @@ def main():
             "spgemm_fp16_ms": t_gemm16, "spgemm_fp16_tflops": tops(t_gemm16),
             "spgemm_fp16_frac_of_sparse_peak_5030": tops(t_gemm16) / 5030.0,
             "spgemm_fp16_frac_of_measured_sparse_peak": (tops(t_gemm16) / sparse_f16_peak) if sparse_f16_peak else None,
-            "spgemm_fp16_kernel2_ms": t_gemm16_k2,
+            "spgemm_fp16_same_template_ms": t_gemm16_twin,
             "gemm_fp16_dense_ms": t_dense16, "gemm_fp16_dense_tflops": tops(t_dense16),
-            "fp16_speedup_vs_dense_same_template": t_dense16 / t_gemm16, "fp16_ideal_speedup_vs_dense": 1.90,
+            "fp16_speedup_vs_dense_same_template": t_dense16 / t_gemm16_twin, "fp16_speedup_vs_dense": t_dense16 / t_gemm16,
+            "fp16_ideal_speedup_vs_dense": 1.90,
             "quantize_act_ms": t_qact, "weight_prep_ms": t_wprep, "weight_prep_with_intermediate_outputs_ms": t_wprep_all,
         },
         "paper_context": "A100 INT8 2:4 vs FP32 dense end-to-end: 1.26-1.47x latency, 2.40-2.60x throughput (Table 2); "

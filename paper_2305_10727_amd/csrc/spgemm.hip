@@ -851,12 +851,14 @@ static int kernel_choice(bool is_i8, int64_t M, int64_t N, int64_t K, bool gelu,
   if (k_bytes % kStepBytes != 0) return wgs64 <= 2 * resident ? 0 : 1;
   if (fused_patches) return 2;
   // Between the two tile kernels the measured times decide (every linear layer of the ViT-B, Swin-B, ViT-L and ViT-H
-  // workloads, FP16 and INT8, with hot and with cold buffers; the two are within 10 % of each other almost everywhere): the
-  // kernel with two workgroups per CU is ahead, by up to 20 %, on layers with few output channels, short K and no GELU
-  // (the attention projections and the QKV layer of the narrow models: few tiles per CU, where its smaller tiles
-  // balance better); the single-workgroup kernel keeps the wide layers, the GELU layers and every long-K layer, where
-  // its deeper ring hides the latency of cold activations (the other kernel is 15-25 % behind there on cold buffers).
-  const int tile_kernel = (N <= 1536 && K <= 1024 && !gelu) ? 3 : 2;
+  // workloads, FP16 and INT8, with hot and with cold buffers, the two kernels timed in turn; they are within 10 % of each
+  // other almost everywhere): the kernel with two workgroups per CU is ahead, by 15-20 %, on layers with few output
+  // channels, short K and no GELU (the attention projections and the QKV layer of the narrow models: few tiles per CU,
+  // where its smaller tiles balance better); for FP16 only from 1024 output channels on (below that it is up to 14 %
+  // behind once the activations come from HBM).  The single-workgroup kernel keeps the wide layers, the GELU layers and
+  // every long-K layer, where its deeper ring hides the latency of cold activations (the other kernel is 10-25 % behind
+  // there on cold buffers).
+  const int tile_kernel = (N <= 1536 && K <= 1024 && !gelu && (is_i8 || N >= 1024)) ? 3 : 2;
   if (wgs64 > 16 * resident) return tile_kernel;  // far beyond the crossover with the small kernel: skip the planning
   const double per_round = 0.7 + 0.45 * ksteps, chain = 3.6 + 0.25 * ksteps;
   const double throughput = 4.0 + per_round * (double)wgs64 / (2.0 * resident);

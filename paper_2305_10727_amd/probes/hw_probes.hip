@@ -10,6 +10,7 @@
 //   stream         copy and fill kernels on 512 MiB, 16 bytes per lane
 //   LDS            ds_read_b128 from 16 wavefronts per CU, conflict-free and in the GEMM's swizzled B-operand pattern
 //   copies         global_load_lds_dwordx4 from an L2-resident buffer, 16 wavefronts per CU
+//   co-issue       a wavefront of matrix instructions and a wavefront of fp32 fma on one SIMD, alone and side by side
 //   clock          wall_clock64 (100 MHz) against clock64 (shader clock) inside the kernels
 #include <hip/hip_runtime.h>
 
@@ -188,6 +189,70 @@ __global__ void __launch_bounds__(1024) lds_copy_rate(const char* __restrict__ s
   if (threadIdx.x == 0) clk[blockIdx.x] = c1 - c0;
 }
 
+// Matrix against vector issue on one SIMD.  8 wavefronts per CU, two per SIMD: wavefronts 0..3 (one per SIMD) run
+// sparse matrix instructions, wavefronts 4..7 a chain of 8 independent fp32 fma streams (MODE bit 0 / bit 1; both bits:
+// side by side); MODE 4: wavefronts 0..3 alone run 8 x (one matrix instruction, two fma) interleaved in program order.
+// clk[16 wg + wave] = clocks that wavefront spent in its loop.
+template <int MODE>
+__global__ void __launch_bounds__(512, 1) coissue_probe(const int* __restrict__ src, int* __restrict__ out, long long* __restrict__ clk, int iters) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const v4i a = *(const v4i*)(src + (threadIdx.x & 63) * 4);
+  const v8i b = *(const v8i*)(src + 1024 + (threadIdx.x & 63) * 8);
+  v4i acc[8];
+  float f[8];
+  for (int i = 0; i < 8; ++i) {
+    acc[i] = v4i{0, 0, 0, 0};
+    f[i] = (float)(src[(threadIdx.x + i) & 1023] & 0xffff) * 1e-6f;
+  }
+  __syncthreads();
+  const long long c0 = clock64();
+  if (MODE == 4) {
+    if (wave < 4)
+      for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          acc[i] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(a, b, acc[i], 0x44444444, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          f[i] = __builtin_fmaf(f[i], 0.999f, 0.001f);
+          f[(i + 4) & 7] = __builtin_fmaf(f[(i + 4) & 7], 0.999f, 0.001f);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+  } else if (wave < 4) {
+    if (MODE & 1)
+      for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(a, b, acc[i], 0x44444444, 0, 0);
+  } else if (MODE & 2) {
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = __builtin_fmaf(f[i], 0.999f, 0.001f);
+  }
+  const long long c1 = clock64();
+  int s = 0;
+  for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3] + (int)f[i];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if ((threadIdx.x & 63) == 0) clk[blockIdx.x * 16 + wave] = c1 - c0;
+}
+
+template <int MODE>
+static void run_coissue(const int* src, int* out, long long* clk, int wgs, int iters, double* matrix_clk, double* vector_clk) {
+  coissue_probe<MODE><<<wgs, 512>>>(src, out, clk, 50);
+  CK(hipDeviceSynchronize());
+  coissue_probe<MODE><<<wgs, 512>>>(src, out, clk, iters);
+  CK(hipDeviceSynchronize());
+  std::vector<long long> h(16 * wgs);
+  CK(hipMemcpy(h.data(), clk, sizeof(long long) * 16 * wgs, hipMemcpyDeviceToHost));
+  double m = 0, v = 0;
+  for (int i = 0; i < wgs; ++i) {
+    m += (double)h[16 * i];
+    v += (double)h[16 * i + 4];
+  }
+  *matrix_clk = m / wgs / iters;
+  *vector_clk = v / wgs / iters;
+}
+
 __global__ void clock_sampler(long long* out, int n, int spin) {
   for (int i = 0; i < n; ++i) {
     out[2 * i] = clock64();
@@ -291,6 +356,23 @@ int main(int argc, char** argv) {
     CK(hipDeviceSynchronize());
     emit("global_to_lds_copy_l2_resident", 16.0 * 4 * 1024 * iters / mean_clk(clk, wgs), "B/clk/CU", "global_load_lds_dwordx4, 16 wavefronts per CU, 4 copies in flight each, all CUs");
     CK(hipFree(l2buf));
+  }
+
+  // ---- matrix against vector issue on one SIMD (a quarter of the CUs, so that the clock stays up and the counts are per clock)
+  {
+    const int wgs = cus / 4, iters = 2000;
+    double m, v, m2, v2;
+    run_coissue<1>(src, out, clk, wgs, iters, &m, &v);
+    emit("coissue_8_matrix_instructions_alone", m, "clk", "one wavefront per SIMD, 8 independent sparse INT8 matrix instructions per iteration");
+    run_coissue<2>(src, out, clk, wgs, iters, &m, &v);
+    emit("coissue_32_fma_alone", v, "clk", "one wavefront per SIMD, 32 fp32 fma per iteration (8 independent chains)");
+    run_coissue<3>(src, out, clk, wgs, iters, &m2, &v2);
+    emit("coissue_matrix_wavefront_beside_fma_wavefront", m2, "clk", "per iteration of the matrix wavefront while an fma wavefront shares its SIMD");
+    emit("coissue_fma_wavefront_beside_matrix_wavefront", v2, "clk", "per iteration of the fma wavefront, averaged over its whole run (it runs alone once the matrix wavefront is done)");
+    emit("coissue_fma_rate_while_matrix_pipe_busy", (v2 > m2 && v > 0) ? (1.0 - (v2 - m2) / v) * v / m2 : 0.0, "of alone",
+         "share of its stand-alone rate the fma wavefront reaches while the matrix wavefront runs");
+    run_coissue<4>(src, out, clk, wgs, iters, &m, &v);
+    emit("coissue_one_wavefront_8_matrix_16_fma_interleaved", m, "clk", "8 x (matrix instruction, 2 fma) in one wavefront's program order");
   }
 
   // ---- the shader clock while the c1 sparse INT8 GEMM runs back to back (ViT-Base fc1 at batch 64)

@@ -58,29 +58,48 @@ def pmc_per_kernel(directories, kernel_filter=""):
 
 
 def derived(c, simds=1024, xcds=8):
-    """Ratios of the raw counters.  rocprofv3 reports a counter summed over the chip; GRBM_GUI_ACTIVE (clocks during which
-    the dispatch was active) is summed over the `xcds` dies, so gui / xcds is the launch's length in shader clocks.  The
-    matrix pipe of a SIMD is busy 16 clocks per 16x16 matrix instruction (SQ_VALU_MFMA_BUSY_CYCLES = 16 x SQ_INSTS_MFMA),
-    so mfma_util is the share of the launch during which a SIMD's matrix pipe was busy, averaged over all `simds` SIMDs;
-    a vector instruction occupies its SIMD's vector ALU for 4 clocks (64 lanes on 16)."""
+    """Ratios of the raw counters.  rocprofv3 reports a counter summed over the chip.  Time base: SQ_BUSY_CYCLES counts,
+    per shader engine (8 dies x 4), the clocks during which the engine holds a wavefront, so busy_cycles / 32 is the
+    launch's length in shader clocks (it agrees within 10 % with the traced duration times the shader clock sampled
+    during the GEMM; GRBM_GUI_ACTIVE / 8 dies, the fallback, also counts the dispatch's set-up and the collection of the
+    counters and reads 30-40 % long).  SQ_WAVE_CYCLES counts the lifetimes of the wavefronts in units of 4 clocks:
+    4 x wave_cycles / waves is the mean lifetime, shorter than the launch by what the workgroups that finish early idle.
+    The matrix pipe of a SIMD is busy 16 clocks per 16x16 matrix instruction (SQ_VALU_MFMA_BUSY_CYCLES = 16 x
+    SQ_INSTS_MFMA), so mfma_util is the share of the launch during which a SIMD's matrix pipe was busy, averaged over all
+    `simds` SIMDs.  SQ_ACTIVE_INST_VALU counts, in units of 4 clocks, the time wavefronts spend executing vector
+    instructions (an ordinary one occupies the SIMD's vector ALU for 4 clocks, a transcendental for 16); without that
+    counter 4 clocks per vector instruction are assumed."""
     out = {}
-    gui = c.get("GRBM_GUI_ACTIVE")
-    clocks = gui / xcds if gui else None
-    if clocks:
+    clocks = None
+    if c.get("SQ_BUSY_CYCLES"):
+        clocks = c["SQ_BUSY_CYCLES"] / (4 * xcds)
+        out["launch_clocks (busy_cycles / %d shader engines)" % (4 * xcds)] = clocks
+    elif c.get("GRBM_GUI_ACTIVE"):
+        clocks = c["GRBM_GUI_ACTIVE"] / xcds
         out["launch_clocks (gui_active / %d XCDs)" % xcds] = clocks
+    if c.get("SQ_WAVE_CYCLES") and c.get("SQ_WAVES"):
+        out["mean wavefront lifetime in clocks (4 x wave_cycles / waves)"] = 4.0 * c["SQ_WAVE_CYCLES"] / c["SQ_WAVES"]
     if clocks and "SQ_VALU_MFMA_BUSY_CYCLES" in c:
         out["mfma_util = mfma_busy_cycles / (launch_clocks * %d SIMDs)" % simds] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (clocks * simds)
     if "SQ_VALU_MFMA_BUSY_CYCLES" in c and "SQ_INSTS_MFMA" in c:
         out["mfma_busy_cycles / mfma_insts"] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / max(c["SQ_INSTS_MFMA"], 1.0)
-    if clocks and "SQ_INSTS_VALU" in c:
-        out["valu_util = 4 * valu_insts / (launch_clocks * %d SIMDs)" % simds] = 4.0 * c["SQ_INSTS_VALU"] / (clocks * simds)
+    # SQ_INSTS_VALU and SQ_ACTIVE_INST_VALU include the matrix instructions (one unit of 4 clocks each, their issue)
+    mfma_insts = c.get("SQ_INSTS_MFMA", 0.0)
+    if clocks and "SQ_ACTIVE_INST_VALU" in c:
+        out["valu_util = 4 * (active_inst_valu - mfma_insts) / (launch_clocks * %d SIMDs)" % simds] = \
+            4.0 * (c["SQ_ACTIVE_INST_VALU"] - mfma_insts) / (clocks * simds)
+    elif clocks and "SQ_INSTS_VALU" in c:
+        out["valu_util = 4 * (valu_insts - mfma_insts) / (launch_clocks * %d SIMDs)" % simds] = 4.0 * (c["SQ_INSTS_VALU"] - mfma_insts) / (clocks * simds)
+    if clocks and "SQ_VALU_MFMA_BUSY_CYCLES" in c and "SQ_ACTIVE_INST_VALU" in c:
+        out["mfma_util + valu_util (matrix and vector instructions share a SIMD's issue: what is left is waiting)"] = \
+            (c["SQ_VALU_MFMA_BUSY_CYCLES"] + 4.0 * (c["SQ_ACTIVE_INST_VALU"] - mfma_insts)) / (clocks * simds)
     if clocks and "SQ_LDS_IDX_ACTIVE" in c:
         out["lds_util = lds_idx_active / (launch_clocks * %d CUs)" % (simds // 4)] = c["SQ_LDS_IDX_ACTIVE"] / (clocks * simds / 4)
     if "SQ_INSTS_VALU" in c and "SQ_INSTS_MFMA" in c:
-        out["valu_insts / mfma_insts"] = c["SQ_INSTS_VALU"] / max(c["SQ_INSTS_MFMA"], 1.0)
+        out["other vector instructions per matrix instruction"] = (c["SQ_INSTS_VALU"] - c["SQ_INSTS_MFMA"]) / max(c["SQ_INSTS_MFMA"], 1.0)
     if "SQ_LDS_BANK_CONFLICT" in c and "SQ_LDS_IDX_ACTIVE" in c:
         out["lds_bank_conflict / lds_idx_active"] = c["SQ_LDS_BANK_CONFLICT"] / max(c["SQ_LDS_IDX_ACTIVE"], 1.0)
-    if clocks and "SQ_WAVE_CYCLES" in c and "SQ_WAIT_INST_ANY" in c:
+    if "SQ_WAVE_CYCLES" in c and "SQ_WAIT_INST_ANY" in c:
         out["wait_inst_any / wave_cycles"] = c["SQ_WAIT_INST_ANY"] / max(c["SQ_WAVE_CYCLES"], 1.0)
     return out
 

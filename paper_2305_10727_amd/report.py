@@ -80,18 +80,30 @@ def layer_rows(M, K, N, gelu, iters):
                 lin.quantize_activations(X)
             sets.append((lin, X))
         ops = 2.0 * M * N * K
-        t_hot = _time([lambda s=sets[0]: s[0].gemm(s[1], bias)], iters)
-        t_cold = _time([lambda s=s: s[0].gemm(s[1], bias) for s in sets], iters)
-        td_hot = _time([lambda s=sets[0]: s[0].gemm_dense(s[1], bias)], iters)
-        td_cold = _time([lambda s=s: s[0].gemm_dense(s[1], bias) for s in sets], iters)
         alg = M * K * e + N * K * e // 2 + N * K // 8 + 8 * N + M * N * 2
         kernel = G.spgemm_plan(torch.int8 if prec == "int8" else torch.float16, M, N, K, sets[0][0].epilogue)["kernel"]
-        # the sparse instantiation of the dense twin's template (tile kernel 3), where the size rules picked another kernel
-        t_same = t_cold
-        if kernel != 3 and K * e % 128 == 0 and M * N > 256 * 1024:
-            G.force_kernel(3)
-            t_same = _time([lambda s=s: s[0].gemm(s[1], bias) for s in sets], iters)
-            G.force_kernel(None)
+        # The variants are timed in turn, three rounds of them, and each reports its median: the shader clock moves with
+        # the load of the seconds before, so a variant timed once, after a pause or after a heavier kernel, is off by up
+        # to 10 %.  `same` is the sparse instantiation of the dense twin's template (tile kernel 3), where the size rules
+        # picked another kernel.
+        hot = [lambda s=sets[0]: s[0].gemm(s[1], bias)]
+        cold = [lambda s=s: s[0].gemm(s[1], bias) for s in sets]
+        dense_hot = [lambda s=sets[0]: s[0].gemm_dense(s[1], bias)]
+        dense_cold = [lambda s=s: s[0].gemm_dense(s[1], bias) for s in sets]
+        with_twin = kernel != 3 and K * e % 128 == 0 and M * N > 256 * 1024
+        samples = {name: [] for name in ("hot", "cold", "dense_hot", "dense_cold", "same")}
+        for _round in range(3):
+            samples["hot"].append(_time(hot, iters))
+            samples["cold"].append(_time(cold, iters))
+            if with_twin:
+                G.force_kernel(3)
+                samples["same"].append(_time(cold, iters))
+                G.force_kernel(None)
+            samples["dense_hot"].append(_time(dense_hot, iters))
+            samples["dense_cold"].append(_time(dense_cold, iters))
+        med = {name: sorted(v)[len(v) // 2] for name, v in samples.items() if v}
+        t_hot, t_cold, td_hot, td_cold = med["hot"], med["cold"], med["dense_hot"], med["dense_cold"]
+        t_same = med.get("same", t_cold)
         mp = measured_peaks().get(prec)
         rows.append(dict(prec=prec, t_hot=t_hot, t_cold=t_cold, td_hot=td_hot, td_cold=td_cold, tops=ops / t_cold / 1e6,
                          frac=ops / t_cold / 1e6 / SPARSE_PEAK[prec], hbm=alg / t_cold / 1e6 / 8.0, sets=n_sets, kernel=kernel,

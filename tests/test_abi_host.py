@@ -185,6 +185,7 @@ def test_tile_plan_covers_every_row_exactly_once(lib):
     assert _plan(lib, I8, 12608, 3072, 768, 3, 256)[1][0] == 2 and _plan(lib, I8, 25216, 768, 3072, 1, 256)[1][0] == 2
     assert _plan(lib, F16, 12608, 3072, 768, 3, 256)[1][0] == 2 and _plan(lib, F16, 50432, 1024, 4096, 1, 256)[1][0] == 2
     assert _plan(lib, I8, 25216, 768, 768, 1, 256)[1][0] == 3 and _plan(lib, F16, 12544, 1536, 512, 1, 256)[1][0] == 3
+    assert _plan(lib, F16, 25216, 768, 768, 1, 256)[1][0] == 2  # FP16: only from 1024 output channels on
     # ragged K (not a multiple of the 128-byte K step) -> zero-filling small kernel; argument errors are reported
     assert _plan(lib, I8, 4096, 4096, 144, 0, 256) == (0, [1, 0, 0, 0, 0, 0, 0, 0])
     assert _plan(lib, F16, 4096, 4096, 64, 0, 256)[1][0] == 2 and _plan(lib, F16, 4096, 4096, 80, 0, 256)[1][0] == 1
