@@ -4,11 +4,13 @@
 //
 // Why two workgroups.  A tile has two phases that use different units of a SIMD: the K loop (matrix pipe, LDS reads,
 // operand copies) and the fused epilogue (dequantise, bias, GELU, convert: vector ALU, about 13 issue slots per output,
-// and the output stores).  For the short K of the ViT linears the two phases are about equally long, so a CU that runs
-// them one after the other leaves each unit idle half of the time.  Here a workgroup of 8 wavefronts owns a tile of 256
-// channels x 128 rows and needs at most 128 registers per lane and 80 KB of LDS, so two workgroups are resident per CU
-// (four wavefronts per SIMD) and the hardware interleaves one workgroup's epilogue with the other's K loop; the matrix
-// pipe serves the oldest wavefront first, which drives the two out of phase by itself.
+// and the output stores).  Here a workgroup of 8 wavefronts owns a tile of 256 channels x 128 rows and needs at most 128
+// registers per lane and 80 KB of LDS, so two workgroups are resident per CU (four wavefronts per SIMD) and one
+// workgroup's epilogue can run beside the other's K loop.  Measured, the overlap is partial (a wavefront of vector
+// instructions beside a busy matrix pipe issues at about half its rate) and is paid for with more LDS reads per matrix
+// instruction (wavefront tile 128 x 32) and a ring of two stages: against the kernel with one workgroup per CU this one
+// is 15-20 % ahead where there are few tiles per CU (its smaller tiles balance better), level on most shapes and behind
+// on long K with cold activations; the size rule in spgemm.hip sends it the former.
 //
 // One template, two operand formats:
 //   sparse: K step = 128 bytes of an activation row; the packed weight tile of the step (16 fragments x 1 KB of kept
