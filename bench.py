@@ -213,7 +213,7 @@ def main():
             "spgemm_int8_frac_of_sparse_peak_10070": tops(t_gemm) / 10070.0,
             # the dense twin is the dense instantiation of tile kernel 3; the same-template ratio is kernel 3 sparse against
             # it, the shipped ratio is the kernel the size rules pick (kernel 2 here) against it.  Ideal ratios: both sides
-            # on their own roofline at the nominal peaks (INT8 c1: both bound by the Y write).
+            # on their own roofline at the nominal peaks (INT8 c1: the sparse side bound by the Y write, the dense side just by its matrix rate).
             "spgemm_int8_same_template_ms": t_gemm_twin, "gemm_int8_dense_ms": t_dense, "gemm_int8_dense_tops": tops(t_dense),
             "int8_speedup_vs_dense_same_template": t_dense / t_gemm_twin, "int8_speedup_vs_dense": t_dense / t_gemm,
             "int8_ideal_speedup_vs_dense": 1.07,

@@ -172,7 +172,11 @@ gpusq_status gpusq_prepare_weights(const float* W, gpusq_dtype dt, float* W_prun
  * the dense GEMM on the zero-filled operand, computed over the kept values only].
  * FP16: Y[m][n] = fp16( act( sum_k X[m][k] * W[n][k]  (fp32 accumulation) + bias[n] ) )
  *   X [M][K] fp16, Wpacked from gpusq_pack(GPUSQ_F16), bias [N] fp32 (required iff GPUSQ_EPI_BIAS), Y [M][N] fp16;
- *   act = exact-erf GELU iff GPUSQ_EPI_GELU. */
+ *   act = GELU in its exact (erf) form x * Phi(x) iff GPUSQ_EPI_GELU [Sec. 2.2 / 3.4: the activation of the MLP block],
+ *   evaluated in fp32 as max(x, 0) - |x| * 2^P(|x|) with a degree-5 polynomial P fitted to log2 Phi(-t): within 0.15
+ *   units in the last place of the exact value as an fp16 number over the whole fp16 range (negative tail included),
+ *   so the fp16 output is within one fp16 ulp of the exactly rounded value.  The same evaluation serves every call
+ *   below that takes GPUSQ_EPI_GELU. */
 gpusq_status gpusq_spgemm_fp16(const void* X, const void* Wpacked, const float* bias, void* Y,
                                int64_t M, int64_t N, int64_t K, int epilogue, void* stream);
 /* INT8: acc[m][n] = sum_k Xq[m][k] * Wq[n][k] in int32 (exact);
