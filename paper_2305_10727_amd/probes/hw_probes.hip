@@ -7,6 +7,7 @@
 //                  wavefronts per CU on every CU; timed with HIP events around the launch (a timestamp taken by one
 //                  wavefront of a workgroup would only show that wavefront's share: the matrix pipe of a SIMD serves
 //                  its wavefronts one instruction at a time, 16 clocks each for the 16x16 shapes, and the oldest first)
+//   vector ALU     fp32 fma and the GELU epilogue's instruction mix on every CU, with the clock they run at
 //   stream         copy and fill kernels on 512 MiB, 16 bytes per lane
 //   LDS            ds_read_b128 from 16 wavefronts per CU, conflict-free and in the GEMM's swizzled B-operand pattern
 //   copies         global_load_lds_dwordx4 from an L2-resident buffer, 16 wavefronts per CU
@@ -126,6 +127,69 @@ static void run_matrix(const char* key, double ops_per_instr, const int* src, in
   snprintf(k, sizeof k, "%s_shader_clock", key);
   snprintf(n, sizeof n, "clock64 / wall_clock64 x 100 MHz during the loop (%d workgroups of %d threads)", wgs, threads);
   emit(k, cs / ws * 100.0, "MHz", n);
+}
+
+// Vector ALU under load.  8 wavefronts per CU run 16 independent fp32 chains per lane.  MIX 0: fma only; MIX 1: the shape of
+// the fused GELU epilogue per output (convert from int32, scale-and-bias fma, five fma of a polynomial, exp2, max, closing fma).
+template <int MIX>
+__global__ void __launch_bounds__(512) vector_rate(const int* __restrict__ src, int* __restrict__ out, long long* __restrict__ clk, int iters) {
+  float f[16];
+  int q[16];
+  for (int i = 0; i < 16; ++i) {
+    q[i] = src[(threadIdx.x + 64 * i) & 4095] & 0xfffff;
+    f[i] = (float)(q[i] & 0xffff) * 1e-5f;
+  }
+  const float c = 0.999f + (float)(src[threadIdx.x & 63] & 1) * 1e-6f, b = 1e-3f;
+  __syncthreads();
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (MIX == 0) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) f[i] = __builtin_fmaf(f[i], c, b);
+      } else {
+        const float x = __builtin_fmaf((float)(q[i] + it), c * 1e-5f, f[i] * 1e-3f - 3.0f);
+        const float t = __builtin_fabsf(x);
+        float p = __builtin_fmaf(t, -0.01f, 0.02f);
+        p = __builtin_fmaf(p, t, -0.03f);
+        p = __builtin_fmaf(p, t, -0.3f);
+        p = __builtin_fmaf(p, t, -1.0f);
+        p = __builtin_fmaf(p, t, -1.0f);
+        f[i] = __builtin_fmaf(-t, __builtin_amdgcn_exp2f(p), __builtin_fmaxf(x, 0.0f));
+      }
+    }
+  }
+  __syncthreads();
+  const long long c1 = clock64(), w1 = wall_clock64();
+  float s = 0;
+  for (int i = 0; i < 16; ++i) s += f[i];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = (int)s;
+  if (threadIdx.x == 0) {
+    clk[2 * blockIdx.x] = c1 - c0;
+    clk[2 * blockIdx.x + 1] = w1 - w0;
+  }
+}
+
+template <int MIX>
+static void run_vector(const char* key, double instr_per_iter, const int* src, int* out, long long* clk, int wgs, const char* note) {
+  const int iters = 4000;
+  vector_rate<MIX><<<wgs, 512>>>(src, out, clk, iters);  // warm-up at full length: the clocks settle
+  CK(hipDeviceSynchronize());
+  vector_rate<MIX><<<wgs, 512>>>(src, out, clk, iters);
+  CK(hipDeviceSynchronize());
+  std::vector<long long> h(2 * wgs);
+  CK(hipMemcpy(h.data(), clk, sizeof(long long) * 2 * wgs, hipMemcpyDeviceToHost));
+  double cs = 0, ws = 0;
+  for (int i = 0; i < wgs; ++i) {
+    cs += h[2 * i];
+    ws += h[2 * i + 1];
+  }
+  char k[128];
+  snprintf(k, sizeof k, "%s_clocks_per_instruction_per_simd", key);
+  emit(k, cs / wgs / (iters * instr_per_iter * 2.0), "clk", note);  // 8 wavefronts per CU = 2 per SIMD
+  snprintf(k, sizeof k, "%s_shader_clock", key);
+  emit(k, cs / ws * 100.0, "MHz", "clock64 / wall_clock64 x 100 MHz during the loop, all CUs");
 }
 
 __global__ void __launch_bounds__(256) copy_kernel(const v4i* __restrict__ in, v4i* __restrict__ out, size_t n) {
@@ -305,6 +369,10 @@ int main(int argc, char** argv) {
   CK(hipMemset(src, 0, hs.size() * 4));
   run_matrix<0, false>("sparse_int8_zero_operands", 2.0 * 16 * 16 * 128, src, out, clk, cus, 512, "all-zero operands: fewer toggling bits, higher clock");
   CK(hipMemcpy(src, hs.data(), hs.size() * 4, hipMemcpyHostToDevice));
+
+  // ---- vector ALU rates and the clock they run at
+  run_vector<0>("vector_fp32_fma", 16 * 8, src, out, clk, cus, "8 wavefronts per CU, 16 independent chains of fp32 fma per lane");
+  run_vector<1>("vector_gelu_epilogue_mix", 16 * 13, src, out, clk, cus, "per output 13 instructions as compiled: 8 fma-class, integer add, convert, multiply, max, v_exp_f32");
 
   // ---- streaming
   {

@@ -57,6 +57,9 @@ def pmc_per_kernel(directories, kernel_filter=""):
     return {k: {c: sum(v) / len(v) for c, v in cs.items()} for k, cs in vals.items()}
 
 
+VALU_CLOCKS = 2.6
+
+
 def derived(c, simds=1024, xcds=8):
     """Ratios of the raw counters.  rocprofv3 reports a counter summed over the chip.  Time base: SQ_BUSY_CYCLES counts,
     per shader engine (8 dies x 4), the clocks during which the engine holds a wavefront, so busy_cycles / 32 is the
@@ -66,9 +69,7 @@ def derived(c, simds=1024, xcds=8):
     4 x wave_cycles / waves is the mean lifetime, shorter than the launch by what the workgroups that finish early idle.
     The matrix pipe of a SIMD is busy 16 clocks per 16x16 matrix instruction (SQ_VALU_MFMA_BUSY_CYCLES = 16 x
     SQ_INSTS_MFMA), so mfma_util is the share of the launch during which a SIMD's matrix pipe was busy, averaged over all
-    `simds` SIMDs.  SQ_ACTIVE_INST_VALU counts, in units of 4 clocks, the time wavefronts spend executing vector
-    instructions (an ordinary one occupies the SIMD's vector ALU for 4 clocks, a transcendental for 16); without that
-    counter 4 clocks per vector instruction are assumed."""
+    `simds` SIMDs."""
     out = {}
     clocks = None
     if c.get("SQ_BUSY_CYCLES"):
@@ -83,16 +84,17 @@ def derived(c, simds=1024, xcds=8):
         out["mfma_util = mfma_busy_cycles / (launch_clocks * %d SIMDs)" % simds] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (clocks * simds)
     if "SQ_VALU_MFMA_BUSY_CYCLES" in c and "SQ_INSTS_MFMA" in c:
         out["mfma_busy_cycles / mfma_insts"] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / max(c["SQ_INSTS_MFMA"], 1.0)
-    # SQ_INSTS_VALU and SQ_ACTIVE_INST_VALU include the matrix instructions (one unit of 4 clocks each, their issue)
+    # SQ_INSTS_VALU includes the matrix instructions.  A SIMD's vector ALU is 32 lanes wide: with two or more wavefronts
+    # it takes an fp32 fma every 2.6 clocks (measured, probes: vector_fp32_fma), the instruction mix of the GELU epilogue
+    # one instruction every 3.6 clocks; VALU_CLOCKS is the former, so valu_util is a lower bound for epilogue-heavy kernels.
     mfma_insts = c.get("SQ_INSTS_MFMA", 0.0)
-    if clocks and "SQ_ACTIVE_INST_VALU" in c:
-        out["valu_util = 4 * (active_inst_valu - mfma_insts) / (launch_clocks * %d SIMDs)" % simds] = \
-            4.0 * (c["SQ_ACTIVE_INST_VALU"] - mfma_insts) / (clocks * simds)
-    elif clocks and "SQ_INSTS_VALU" in c:
-        out["valu_util = 4 * (valu_insts - mfma_insts) / (launch_clocks * %d SIMDs)" % simds] = 4.0 * (c["SQ_INSTS_VALU"] - mfma_insts) / (clocks * simds)
-    if clocks and "SQ_VALU_MFMA_BUSY_CYCLES" in c and "SQ_ACTIVE_INST_VALU" in c:
-        out["mfma_util + valu_util (matrix and vector instructions share a SIMD's issue: what is left is waiting)"] = \
-            (c["SQ_VALU_MFMA_BUSY_CYCLES"] + 4.0 * (c["SQ_ACTIVE_INST_VALU"] - mfma_insts)) / (clocks * simds)
+    if clocks and "SQ_INSTS_VALU" in c:
+        other = c["SQ_INSTS_VALU"] - mfma_insts
+        out["vector instructions (matrix ones excluded) per SIMD and clock"] = other / (clocks * simds)
+        out["valu_util = %.1f clocks * vector instructions / (launch_clocks * %d SIMDs)" % (VALU_CLOCKS, simds)] = VALU_CLOCKS * other / (clocks * simds)
+        if "SQ_VALU_MFMA_BUSY_CYCLES" in c:
+            out["mfma_util + valu_util (a busy matrix pipe takes about half of the vector issue away: the two mostly add)"] = \
+                (c["SQ_VALU_MFMA_BUSY_CYCLES"] + VALU_CLOCKS * other) / (clocks * simds)
     if clocks and "SQ_LDS_IDX_ACTIVE" in c:
         out["lds_util = lds_idx_active / (launch_clocks * %d CUs)" % (simds // 4)] = c["SQ_LDS_IDX_ACTIVE"] / (clocks * simds / 4)
     if "SQ_INSTS_VALU" in c and "SQ_INSTS_MFMA" in c:

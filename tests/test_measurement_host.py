@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_counter_ratios_follow_from_their_definitions():
     from paper_2305_10727_amd.profiling import derived
     # a made-up launch of 1000 shader clocks on a chip of 1024 SIMDs / 32 shader engines in which every SIMD issues 10
-    # matrix instructions (16 clocks of matrix pipe each) and 50 other vector instructions, 4 of them double-length
+    # matrix instructions (16 clocks of matrix pipe each) and 50 other vector instructions
     simds, clocks, mfma, valu = 1024, 1000.0, 10, 50
     c = {
         "SQ_BUSY_CYCLES": clocks * 32,
@@ -33,8 +33,9 @@ def test_counter_ratios_follow_from_their_definitions():
     assert get("launch_clocks") == clocks
     assert get("mean wavefront lifetime") == 900.0
     assert get("mfma_util =") == pytest.approx(mfma * 16 / clocks)
-    assert get("valu_util =") == pytest.approx(4.0 * (valu + 4) / clocks)
-    assert get("mfma_util + valu_util") == pytest.approx((mfma * 16 + 4.0 * (valu + 4)) / clocks)
+    assert get("vector instructions (matrix ones excluded)") == pytest.approx(valu / clocks)
+    assert get("valu_util =") == pytest.approx(2.6 * valu / clocks)
+    assert get("mfma_util + valu_util") == pytest.approx((mfma * 16 + 2.6 * valu) / clocks)
     assert get("lds_util") == pytest.approx(0.25)
     assert get("other vector instructions per matrix instruction") == pytest.approx(valu / mfma)
     assert get("lds_bank_conflict") == pytest.approx(0.1)
