@@ -42,7 +42,8 @@ typedef enum {
   GPUSQ_ERR_SHAPE = 2,       /* non-positive size, K % 4 != 0, or a size beyond the supported range */
   GPUSQ_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned */
   GPUSQ_ERR_UNSUPPORTED = 4, /* valid for the method but not implemented (dtype, divisibility, epilogue bits) */
-  GPUSQ_ERR_HIP = 5          /* a HIP call or kernel launch failed */
+  GPUSQ_ERR_HIP = 5,         /* a HIP call or kernel launch failed */
+  GPUSQ_ERR_NOT_2TO4 = 6     /* gpusq_check_2to4 only: a group of 4 has more than two non-zero elements */
 } gpusq_status;
 
 typedef enum { GPUSQ_F32 = 0, GPUSQ_F16 = 1, GPUSQ_I8 = 2, GPUSQ_I32 = 3 } gpusq_dtype;
@@ -104,6 +105,14 @@ gpusq_status gpusq_quantize_tensor_int8_noalloc(const void* X, gpusq_dtype dt, i
  *            (0 iff W obeys the 2:4 pattern). */
 gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,
                             int64_t N, int64_t K, void* stream);
+/* ---- validation [Sec. 3.1: in a 2:4 tensor every group of four contiguous elements along K holds at most two
+ * non-zero values].  Counts the groups of W [N][K] (GPUSQ_F32, GPUSQ_F16 or GPUSQ_I8) with more than two non-zero
+ * elements (-0 is zero) into *violations (device int32, required, 4-byte aligned; N*K/4 must fit an int32) and, the one
+ * call of this library that waits for the device, synchronises `stream` and returns GPUSQ_OK for a count of 0,
+ * GPUSQ_ERR_NOT_2TO4 otherwise (not usable under stream capture: GPUSQ_ERR_HIP there).  The other calls stay
+ * asynchronous and never return this status: gpusq_compress reports the same count through its optional counter. */
+gpusq_status gpusq_check_2to4(const void* W, gpusq_dtype dt, int32_t* violations, int64_t N, int64_t K, void* stream);
+
 /* inverse: zero-fill W [N][K] and scatter the values to the recorded positions */
 gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt,
                               int64_t N, int64_t K, void* stream);

@@ -54,6 +54,7 @@ const char* gpusq_status_string(gpusq_status s) {
     case GPUSQ_ERR_ALIGN: return "pointer not 16-byte aligned";
     case GPUSQ_ERR_UNSUPPORTED: return "valid request that this build does not implement";
     case GPUSQ_ERR_HIP: return "HIP runtime or launch failure (see gpusq_last_hip_error)";
+    case GPUSQ_ERR_NOT_2TO4: return "the tensor has a group of 4 with more than two non-zero elements";
   }
   return "unknown status";
 }
@@ -114,6 +115,25 @@ gpusq_status gpusq_compress(const void* W, void* values, uint8_t* meta, int32_t*
   if (dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
   if (!aligned16(W) || !aligned16(values) || !aligned16(meta)) return GPUSQ_ERR_ALIGN;
   return launch_compress(W, values, meta, violations, dt, N, K, (hipStream_t)stream);
+}
+
+gpusq_status gpusq_check_2to4(const void* W, gpusq_dtype dt, int32_t* violations, int64_t N, int64_t K, void* stream) {
+  if (!W || !violations) return GPUSQ_ERR_NULL;
+  gpusq_status st = check_nk(N, K);
+  if (st != GPUSQ_OK) return st;
+  if (N * K / 4 > INT32_MAX) return GPUSQ_ERR_SHAPE;  // the count is an int32
+  if (dt != GPUSQ_F32 && dt != GPUSQ_F16 && dt != GPUSQ_I8) return GPUSQ_ERR_UNSUPPORTED;
+  if (!aligned16(W) || ((uintptr_t)violations & 3u) != 0) return GPUSQ_ERR_ALIGN;
+  st = launch_count_violations(W, dt, violations, N, K, (hipStream_t)stream);
+  if (st != GPUSQ_OK) return st;
+  int32_t count = 0;
+  hipError_t e = hipMemcpyAsync(&count, violations, sizeof count, hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) {
+    set_last_hip_error(e);
+    return GPUSQ_ERR_HIP;
+  }
+  return count == 0 ? GPUSQ_OK : GPUSQ_ERR_NOT_2TO4;
 }
 
 gpusq_status gpusq_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt, int64_t N, int64_t K,

@@ -180,6 +180,7 @@ gpusq_status launch_int4_to_sparse_int8(const uint8_t* values4, const uint8_t* m
 gpusq_status launch_compress_int4(const int8_t* W, uint8_t* values, uint8_t* meta, int32_t* violations, int64_t N, int64_t K,
                                   hipStream_t s);
 gpusq_status launch_decompress_int4(const uint8_t* values, const uint8_t* meta, int8_t* W, int64_t N, int64_t K, hipStream_t s);
+gpusq_status launch_count_violations(const void* W, gpusq_dtype dt, int32_t* violations, int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_compress(const void* W, void* values, uint8_t* meta, int32_t* violations, gpusq_dtype dt,
                              int64_t N, int64_t K, hipStream_t s);
 gpusq_status launch_decompress(const void* values, const uint8_t* meta, void* W, gpusq_dtype dt, int64_t N, int64_t K,

@@ -424,6 +424,8 @@ gpusq_status launch_quantize_rows_int4(const void* X, gpusq_dtype dt, int8_t* Xq
 template <typename T>
 __device__ __forceinline__ unsigned magnitude_key(T v);
 template <>
+__device__ __forceinline__ unsigned magnitude_key<uint32_t>(uint32_t v) { return v & 0x7FFFFFFFu; }
+template <>
 __device__ __forceinline__ unsigned magnitude_key<uint16_t>(uint16_t v) { return v & 0x7FFFu; }
 template <>
 __device__ __forceinline__ unsigned magnitude_key<int8_t>(int8_t v) { return (unsigned)(v < 0 ? -(int)v : (int)v); }
@@ -476,6 +478,47 @@ gpusq_status launch_compress(const void* W, void* values, uint8_t* meta, int32_t
     compress_kernel<uint16_t><<<blocks, 256, 0, s>>>((const uint16_t*)W, (uint16_t*)values, meta, violations, N, K);
   else
     compress_kernel<int8_t><<<blocks, 256, 0, s>>>((const int8_t*)W, (int8_t*)values, meta, violations, N, K);
+  return check_launch();
+}
+
+// Groups of 4 along K with more than two non-zero elements (Sec. 3.1: a 2:4 tensor keeps at most two of every four).
+// One thread per 16 bytes of a row (4 groups of fp32 ... 16 of int8: K % 4 == 0 makes rows whole groups, the pointer is
+// 16-byte aligned, and the tail of the tensor that does not fill 16 bytes goes element by element); -0 counts as zero.
+template <typename T>
+__global__ void __launch_bounds__(256) count_violations_kernel(const T* __restrict__ W, int32_t* __restrict__ violations, int64_t elems) {
+  constexpr int PER = 16 / (int)sizeof(T);  // elements per 16-byte piece: whole groups
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t e0 = id * PER;
+  int bad = 0;
+  if (e0 < elems) {
+    alignas(16) T w[PER];
+    if (e0 + PER <= elems) {
+      *(uint4*)w = *(const uint4*)(W + e0);
+    } else {
+      for (int i = 0; i < PER; ++i) w[i] = e0 + i < elems ? W[e0 + i] : (T)0;
+    }
+#pragma unroll
+    for (int g = 0; g < PER / 4; ++g) {
+      int nz = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) nz += (int)(magnitude_key<T>(w[4 * g + i]) != 0u);
+      bad += (int)(nz > 2);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) bad += __shfl_xor(bad, o, 64);
+  if ((threadIdx.x & 63) == 0 && bad) atomicAdd(violations, bad);
+}
+
+gpusq_status launch_count_violations(const void* W, gpusq_dtype dt, int32_t* violations, int64_t N, int64_t K, hipStream_t s) {
+  const int64_t elems = N * K;
+  fill_u32_kernel<<<1, 1, 0, s>>>((uint32_t*)violations, 0u);
+  if (dt == GPUSQ_F32)
+    count_violations_kernel<uint32_t><<<(unsigned)ceil_div(ceil_div(elems, 4), 256), 256, 0, s>>>((const uint32_t*)W, violations, elems);
+  else if (dt == GPUSQ_F16)
+    count_violations_kernel<uint16_t><<<(unsigned)ceil_div(ceil_div(elems, 8), 256), 256, 0, s>>>((const uint16_t*)W, violations, elems);
+  else
+    count_violations_kernel<int8_t><<<(unsigned)ceil_div(ceil_div(elems, 16), 256), 256, 0, s>>>((const int8_t*)W, violations, elems);
   return check_launch();
 }
 

@@ -22,7 +22,7 @@ _DT_TORCH = {v: k for k, v in _TORCH_DT.items()}
 EXPORTS = [
     "gpusq_status_string", "gpusq_last_hip_error", "gpusq_version", "gpusq_prune_2to4", "gpusq_cast_f16",
     "gpusq_quantize_workspace_bytes",
-    "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
+    "gpusq_quantize_int8", "gpusq_compress", "gpusq_check_2to4", "gpusq_decompress", "gpusq_packed_bytes", "gpusq_pack", "gpusq_prepare_weights", "gpusq_spgemm_fp16",
     "gpusq_spgemm_int8", "gpusq_spgemm_int8_xf16", "gpusq_spgemm_plan", "gpusq_im2col_patches", "gpusq_patch_embed16_int8", "gpusq_patch_embed16_fp16", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense",
     "gpusq_prune_4to8_pairs", "gpusq_quantize_rows_int4", "gpusq_compress_int4", "gpusq_decompress_int4",
     "gpusq_int4_to_sparse_int8", "gpusq_prune_n_of_m", "gpusq_force_kernel",
@@ -62,6 +62,8 @@ def lib():
         L.gpusq_quantize_tensor_int8_noalloc.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
         L.gpusq_quantize_tensor_int8_noalloc.restype = ci
         L.gpusq_compress.argtypes = [vp, vp, vp, vp, ci, i64, i64, vp]
+        L.gpusq_check_2to4.argtypes = [vp, ci, vp, i64, i64, vp]
+        L.gpusq_check_2to4.restype = ci
         L.gpusq_decompress.argtypes = [vp, vp, vp, ci, i64, i64, vp]
         L.gpusq_packed_bytes.restype = ctypes.c_size_t
         L.gpusq_packed_bytes.argtypes = [ci, i64, i64]
@@ -86,7 +88,7 @@ def lib():
         L.gpusq_quantize_rows_int4.argtypes = [vp, ci, vp, vp, ci, i64, i64, vp]
         L.gpusq_compress_int4.argtypes = [vp, vp, vp, vp, i64, i64, vp]
         L.gpusq_decompress_int4.argtypes = [vp, vp, vp, i64, i64, vp]
-        for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_decompress", "gpusq_pack",
+        for name in ("gpusq_prune_2to4", "gpusq_cast_f16", "gpusq_quantize_int8", "gpusq_compress", "gpusq_check_2to4", "gpusq_decompress", "gpusq_pack",
                      "gpusq_spgemm_fp16", "gpusq_spgemm_int8", "gpusq_gemm_fp16_dense", "gpusq_gemm_int8_dense"):
             getattr(L, name).restype = ci
         _lib = L
@@ -177,6 +179,19 @@ def compress(W, want_violations=False):
     _check(lib().gpusq_compress(_ptr(W), _ptr(values), _ptr(meta), _ptr(viol), _TORCH_DT[W.dtype], N, K, _stream()),
            "gpusq_compress")
     return (values, meta, viol) if want_violations else (values, meta)
+
+
+ERR_NOT_2TO4 = 6
+
+
+def check_2to4(W):
+    """gpusq_check_2to4: W [N,K] fp32/fp16/int8 -> (is_2to4, groups with more than two non-zeros); waits for the stream"""
+    N, K = W.shape
+    viol = torch.empty(1, dtype=torch.int32, device=W.device)
+    st = lib().gpusq_check_2to4(_ptr(W), _TORCH_DT[W.dtype], _ptr(viol), N, K, _stream())
+    if st not in (0, ERR_NOT_2TO4):
+        _check(st, "gpusq_check_2to4")
+    return st == 0, int(viol.item())
 
 
 def decompress(values, meta, K):

@@ -36,8 +36,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings_and_version(lib):
     lib.gpusq_status_string.restype = ctypes.c_char_p
-    seen = {lib.gpusq_status_string(i) for i in range(6)}
-    assert len(seen) == 6 and lib.gpusq_status_string(0) == b"ok"
+    seen = {lib.gpusq_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and lib.gpusq_status_string(0) == b"ok" and lib.gpusq_status_string(7) == b"unknown status"
     assert lib.gpusq_version() >= 100
 
 
@@ -56,6 +56,12 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.gpusq_compress(good, good, None, None, 1, 4, 8, None) == ERR_NULL
     assert lib.gpusq_compress(good, good, good, None, 0, 4, 8, None) == ERR_UNSUPPORTED
     assert lib.gpusq_compress(good, good, good, None, 1, 4, 10, None) == ERR_SHAPE
+    lib.gpusq_check_2to4.argtypes = [vp, ci, vp, i64, i64, vp]
+    assert lib.gpusq_check_2to4(good, 0, None, 4, 8, None) == ERR_NULL          # the counter is required
+    assert lib.gpusq_check_2to4(good, 3, good, 4, 8, None) == ERR_UNSUPPORTED   # int32 tensors
+    assert lib.gpusq_check_2to4(good, 0, good, 4, 6, None) == ERR_SHAPE
+    assert lib.gpusq_check_2to4(odd, 0, good, 4, 8, None) == ERR_ALIGN
+    assert lib.gpusq_check_2to4(good, 0, vp(0x10002), 4, 8, None) == ERR_ALIGN
     lib.gpusq_quantize_int8.argtypes = [vp, ci, vp, vp, ci, ci, i64, i64, vp, vp]
     assert lib.gpusq_quantize_int8(good, 0, good, None, 0, 0, 4, 8, None, None) == ERR_NULL
     assert lib.gpusq_quantize_int8(good, 0, good, good, 1, 0, 4, 8, None, None) == ERR_NULL  # per-tensor needs workspace

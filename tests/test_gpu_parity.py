@@ -193,6 +193,38 @@ def test_compress_decompress_bit_exact(g, dtype):
         assert np.array_equal(host(g.decompress(v, m, K)).view(np.uint8), pruned.view(np.uint8))  # round trip = identity
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16, np.int8])
+def test_check_2to4_counts_the_groups_with_more_than_two_nonzeros(g, dtype):
+    """gpusq_check_2to4 against the definition written out (Sec. 3.1: at most two non-zeros in every group of four along
+    K) and, for the two storage types, against the violation count of the oracle's compress"""
+    rng = np.random.default_rng(11)
+    for (N, K) in [(1, 4), (3, 20), (7, 72), (64, 192), (100, 1028), (768, 768)]:  # sizes that end inside a 16-byte piece too
+        W32 = rng.standard_normal((N, K)).astype(np.float32)
+        P, _ = oracle.prune_2to4(W32)
+        if dtype == np.int8:
+            pruned = np.clip(np.rint(P * 40), -127, 127).astype(np.int8)
+        else:
+            pruned = P.astype(dtype)
+        ok, count = g.check_2to4(dev(pruned))
+        assert ok and count == 0
+        neg_zero = pruned.copy()
+        if dtype != np.int8:  # -0 in a dropped slot is still a zero
+            neg_zero[pruned == 0] = dtype(-0.0)
+            assert g.check_2to4(dev(neg_zero)) == (True, 0)
+        planted = pruned.copy()
+        rows, cols = rng.integers(0, N, size=5), rng.integers(0, K // 4, size=5)
+        for r, c in zip(rows, cols):
+            planted[r, 4 * c:4 * c + 4] = np.array([1, -2, 3, 0], dtype)  # three non-zeros
+        expected = int(((planted.reshape(N, K // 4, 4) != 0).sum(-1) > 2).sum())
+        assert expected >= 1
+        ok, count = g.check_2to4(dev(planted))
+        assert not ok and count == expected
+        if dtype != np.float32:
+            assert oracle.compress(planted)[2] == expected and oracle.compress(pruned)[2] == 0
+        dense = rng.integers(1, 4, size=(N, K)).astype(dtype)
+        assert g.check_2to4(dev(dense)) == (False, N * K // 4)
+
+
 @pytest.mark.parametrize("N,K", [(1, 4), (3, 36), (64, 192), (100, 144), (257, 1028), (768, 768), (512, 2048)])
 def test_fused_weight_preparation_bit_exact(g, N, K):
     """gpusq_prepare_weights == prune -> quantise/round -> compress -> pack, against the oracle and the separate calls"""
