@@ -1,10 +1,18 @@
-// Dense twin of the sparse GEMM: the same product computed from the masked but uncompressed weights on the dense
-// matrix instructions (v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_f16), with the same tile pipeline, the same
-// fused epilogue and the same output order.  It is the baseline of the "T cycles vs T/2 cycles" comparison of
-// Sec. 3.1; it reads K bytes of W per output channel where the sparse kernel reads K/2 + K/8.
+// Dense twin of the sparse GEMM: the same product computed from the masked but uncompressed weights on dense matrix
+// instructions, the baseline of the "T cycles vs T/2 cycles" comparison of Sec. 3.1; it reads K bytes of W per output
+// channel where the sparse kernel reads K/2 + K/8.
 //
-// Register semantics (measured): A (4 VGPRs) lane l byte i -> row l%32, K index 16*(l/32)+i (8*(l/32)+i for fp16
-// elements); B likewise with column l%32; D (16 VGPRs) lane l register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+// Wherever the tile kernels can run the problem, the twin is the dense instantiation of the two-workgroup tile kernel
+// (tile2.hip: same template, plan, launch path, LDS ring, fused epilogue and whole-line stores as its sparse
+// instantiation), so that the sparse/dense ratio compares like with like.  The kernel in this file is the small one
+// for the rest (few outputs, K that is not a whole number of 64-byte steps): 4 wavefronts, 64 x 128 or 128 x 128
+// tiles, operands through registers into a double-buffered LDS stage, v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_f16,
+// the per-batch epilogue of epilogue.h.  It is a simpler pipeline than the sparse small kernel's and its times are not
+// used for any sparse/dense ratio that the reports quote for the tile-kernel sizes.
+//
+// Register semantics of the 32x32 instructions (measured): A (4 VGPRs) lane l byte i -> row l%32, K index 16*(l/32)+i
+// (8*(l/32)+i for fp16 elements); B likewise with column l%32; D (16 VGPRs) lane l register r -> row 8*(r/4) + 4*(l/32) +
+// r%4, column l%32.
 #include <atomic>
 
 #include "tile_common.h"

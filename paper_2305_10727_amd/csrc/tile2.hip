@@ -28,7 +28,6 @@
 // other stage is free (every wavefront has issued, and received, its last LDS read of the previous step), so the copies of
 // the next step, possibly the next tile's first, are requested there and land while this step multiplies (and, across a
 // tile boundary, during the epilogue).  A wavefront executes one barrier per step of every tile of its workgroup.
-#include <cstdlib>
 #include <type_traits>
 
 #include "tile_common.h"
