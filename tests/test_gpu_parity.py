@@ -226,7 +226,7 @@ def test_check_2to4_counts_the_groups_with_more_than_two_nonzeros(g, dtype):
 
 
 @pytest.mark.parametrize("N,K", [(1, 4), (3, 36), (64, 192), (100, 144), (257, 1028), (768, 768), (512, 2048), (130, 520), (9, 3076),
-                                 (5, 4104), (16, 8192)])  # (rows of up to 4096 elements and longer ones take different kernels)
+                                 (5, 4104), (16, 8192)])  # (short rows share a workgroup, long ones have one each; ragged sizes)
 def test_fused_weight_preparation_bit_exact(g, N, K):
     """gpusq_prepare_weights == prune -> quantise/round -> compress -> pack, against the oracle and the separate calls"""
     W = synth.weights(N, K, seed=N + K)
