@@ -481,6 +481,30 @@ def test_tile_kernel_corner_shapes(g, force_kernel, M, K, N, seed, kernel):
     assert np.array_equal(yh.view(np.uint16), oracle.epilogue_fp16_f64(a64)["y16"].view(np.uint16))
 
 
+# The classifier head [Sec. 3.2: the linear projection layers take 2:4 sparsity, the head included]: a plain linear layer
+# with 1000 output channels, not a multiple of the 256-channel weight tile (three full tiles and one of 232 channels).
+# One class token per image (M = batch: the latency kernel) and a token-level head of the same width on the tile kernels.
+@pytest.mark.parametrize("M,kernel", [(64, None), (256, None), (4200, 2), (4200, 3)])
+def test_classifier_head_of_1000_classes(g, force_kernel, M, kernel):
+    K, N = 768, 1000
+    force_kernel(kernel)
+    if kernel is not None:
+        assert g.spgemm_plan(torch.int8, M, N, K)["kernel"] == kernel
+    p = Int8Problem(M, K, N, seed=1000 + M, dist="normal")
+    d = gpu_prepare_int8(g, p.W32, p.X32)
+    exp = oracle.spgemm_int8(p.Xq, p.vals, p.meta)
+    assert np.array_equal(host(g.spgemm_int8(d["Xq"], d["packed"], N, out_dtype=torch.int32)), exp)
+    y = host(g.spgemm_int8(d["Xq"], d["packed"], N, act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(p.bias)))
+    assert np.array_equal(y.view(np.uint16), oracle.epilogue_int8_f32(exp, p.s_a, p.s_w, p.bias)["y16"].view(np.uint16))
+    yd = host(g.gemm_int8_dense(d["Xq"], d["Wq"], act_scale=d["s_a"], w_scale=d["s_w"], bias=dev(p.bias)))
+    assert np.array_equal(yd.view(np.uint16), y.view(np.uint16))
+    X, W, Wh, vals, meta, bias = fp16_problem(M, K, N, seed=2000 + M)
+    v, m = g.compress(dev(Wh))
+    _, a64 = oracle.spgemm_fp16(X, vals, meta)
+    yh = host(g.spgemm_fp16(dev(X), g.pack(v, m, K), N, bias=dev(bias)))
+    assert rel_err(yh, oracle.epilogue_fp16_f64(a64, bias, False)["ref"]) <= 2e-3
+
+
 # The deployment form with quantise nodes around every linear layer [Sec. 2.2; Sec. 3.4] on the tile kernel: int8 output
 # with bias, with and without GELU, through the whole-line store path (N % 16 == 0) and the per-batch path (N % 16 != 0),
 # and the FP16 path with bias + GELU on Gaussian data through the per-batch path (N % 8 == 4).
