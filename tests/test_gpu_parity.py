@@ -674,7 +674,7 @@ def _sampled_rows(M, n_random=192, seed=0):
 FULL_SIZE_LAYERS = [
     # (config, layer index): the shapes the other workload configurations add to c1
     ("c2", 0), ("c2", 1), ("c2", 3),          # ViT-Base qkv, proj, fc2 (GELU-shaped input, K = 3072) at batch 128
-    ("c3", 2), ("c3", 3),                     # Swin-B stage 3 fc1 (GELU), fc2 at batch 64
+    ("c3", 0), ("c3", 2), ("c3", 3),          # Swin-B stage 3 qkv (two-workgroup tile kernel in both precisions), fc1 (GELU), fc2 at batch 64
     ("c4_vitl", 3), ("c4_vith", 2),           # ViT-L fc2 (K = 4096), ViT-H fc1 (GELU, M = 65792, N = 5120) at batch 256
 ]
 
